@@ -1,0 +1,159 @@
+/*
+ * lpq.h -- C ABI of the MI355X (gfx950) mixed-precision quantized-linear library.
+ *
+ * The library runs the decoder-layer linears (QKV, out-proj, FC1, FC2) of an LLM pipeline
+ * stage whose layers each carry their own weight bitwidth, as in LLM-PQ (arXiv 2403.01136):
+ *   - Sec. 4.3, problem statement: a stage is a run of consecutive layers i, each with a
+ *     bitwidth b_i from BITs = {3, 4, 8, 16}; it is run at a prefill micro-batch (eta
+ *     prompts of s tokens, M = eta * s rows) and at a decode micro-batch (xi rows).
+ *   - Sec. 2.4: quantise code = round((w - q) / s), s = (w_max - w_min) / (2^b - 1),
+ *     dequantise w~ = s * code + q.  Sec. 4.2: the symmetric scaling factor
+ *     max(|w_max|, |w_min|) / (2^(b-1) - 1) used by the per-row 8-bit scheme.
+ *   - Sec. 4.1: a quantised weight occupies (#weights) * bit / 8 bytes (dense packing).
+ *
+ * Conventions that hold for every entry point
+ *   - All data pointers are DEVICE pointers (HIP global memory on the current device) unless
+ *     the argument is a descriptor struct, which is read on the HOST during the call.
+ *   - The library allocates nothing the caller sees.  The caller owns every buffer and keeps
+ *     it alive until the work enqueued on `hip_stream` has completed.  Split-K partial sums
+ *     live in an internal per-device workspace that grows on demand.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue work and return without synchronising.
+ *   - Arguments are validated on the host before the first HIP call; on any error nothing is
+ *     launched and no buffer is touched.  No exceptions, no errno, no global error state.
+ *   - fp16 is IEEE binary16.  x is [M][K], y is [M][N], both dense row-major, 16-byte
+ *     aligned; y is overwritten.  A linear computes y[m][n] = sum_k x[m][k] * w~[n][k]
+ *     (+ bias[n]) with fp32 accumulation and one final round-to-nearest-even to fp16.
+ *
+ * Storage format of a quantised weight W [N][K] (K contiguous); N % 16 == 0, K % 128 == 0
+ *   A tile is 16 rows x 128 columns (one quantisation group per row); tiles are stored in
+ *   order nt * (K/128) + kt.  Inside a tile, lane = 16*kq + r (r = row in tile, kq = 0..3)
+ *   owns the 32 codes of row r at tile columns 32*j + 8*kq + e (j = 0..3, e = 0..7), numbered
+ *   c = 8*j + e -- the operand layout of one wavefront's four v_mfma_f32_16x16x32_f16 steps.
+ *     bits 4:  16 B per lane at 16*lane; little-endian u32 word j; code e at bit
+ *              4*(e/2) + 16*(e%2) of word j (even e in the low half-word, odd e in the high).
+ *     bits 3:  12 B per lane at 12*lane; three LE u32 words.  Pair P = c/2, half h = c%2.
+ *              P < 15: word P/5, bits 16*h + 3*(P%5) .. +2.  P == 15: bit t of the code is
+ *              bit 16*h + 15 of word t.  (768 B per tile: dense, not padded to 4 bits.)
+ *     bits 8:  32 B per lane as two 16-byte pieces; piece p (j = 2p, 2p+1) at
+ *              1024*p + 16*lane; byte 8*(j%2) + e.  Unsigned for LPQ_ASYM_GROUP, two's
+ *              complement in [-127, 127] for LPQ_SYM_CHANNEL.
+ *     bits 16: the row-major fp16 matrix itself (a byte copy of W).
+ *   scales, zeros: fp16 [N][K/128] row-major (LPQ_ASYM_GROUP); scales fp16 [N] and no zeros
+ *   (LPQ_SYM_CHANNEL); neither for LPQ_FP16.  "zero" is the group minimum, a floating offset.
+ */
+#ifndef LPQ_H
+#define LPQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LPQ_OK = 0,
+    LPQ_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+    LPQ_ERR_BITS = 2,        /* bits not in {3, 4, 8, 16}                                    */
+    LPQ_ERR_SCHEME = 3,      /* unknown scheme, or bits / scheme / group_size do not match   */
+    LPQ_ERR_SHAPE = 4,       /* K % 128, N % 16, K, N, M or n_layers out of range            */
+    LPQ_ERR_ALIGN = 5,       /* a data pointer is not 16-byte aligned                        */
+    LPQ_ERR_BUFSIZE = 6,     /* internal workspace could not be grown                        */
+    LPQ_ERR_DEVICE = 7,      /* a HIP call failed                                            */
+    LPQ_ERR_UNSUPPORTED = 8  /* valid request the library does not implement                 */
+} lpq_status;
+
+typedef enum {
+    LPQ_FP16 = 0,         /* bits = 16: weights used unchanged (Sec. 4.3, BITs contains 16)   */
+    LPQ_ASYM_GROUP = 1,   /* bits in {3,4,8}: per (row, 128 columns) scale and zero = minimum
+                             (Sec. 2.4; asymmetric scaling factor of Sec. 4.2)                */
+    LPQ_SYM_CHANNEL = 2   /* bits = 8: per-row scale, signed codes, no zero (symmetric scaling
+                             factor of Sec. 4.2)                                              */
+} lpq_scheme;
+
+/* Shape and quantisation of one linear's weight.  group_size must be 128 for LPQ_ASYM_GROUP
+ * and 0 (or 128, ignored) otherwise. */
+typedef struct {
+    int32_t bits;        /* 3, 4, 8 or 16 */
+    int32_t scheme;      /* lpq_scheme    */
+    int32_t group_size;
+    int32_t K;           /* input features, % 128 == 0  */
+    int32_t N;           /* output features, % 16 == 0  */
+} lpq_qdesc;
+
+/* One quantised weight: descriptor + caller-owned device buffers sized by lpq_packed_sizes.
+ * zeros is ignored unless scheme == LPQ_ASYM_GROUP; scales is ignored for LPQ_FP16.
+ * bias: optional fp16 [N] (NULL = none). */
+typedef struct {
+    lpq_qdesc d;
+    void *codes;
+    void *scales;
+    void *zeros;
+    const void *bias;
+} lpq_qweight;
+
+/* The four linears of one decoder layer (Sec. 4.1: 4*h1^2 + 2*h1*h2 weights per layer). */
+typedef struct {
+    lpq_qweight qkv, out, fc1, fc2;
+} lpq_layer;
+
+/* Per-layer inputs and outputs of lpq_stage_linears.  The four linears of a layer are
+ * independent here: each reads its own x and writes its own y (attention, activation,
+ * normalisation and residual, which connect them in a model, are outside this library). */
+typedef struct {
+    const void *x_qkv, *x_out, *x_fc1, *x_fc2;   /* fp16 [M][K of that linear] */
+    void *y_qkv, *y_out, *y_fc1, *y_fc2;         /* fp16 [M][N of that linear] */
+} lpq_layer_io;
+
+typedef enum { LPQ_PREFILL = 0, LPQ_DECODE = 1 } lpq_phase;
+
+/* Bytes of the three packed buffers of a weight (Sec. 4.1: codes = K*N*bits/8, dense).
+ * Host-only, touches no device.  Errors: NULL, BITS, SCHEME, SHAPE. */
+lpq_status lpq_packed_sizes(const lpq_qdesc *desc, size_t *code_bytes, size_t *scale_bytes, size_t *zero_bytes);
+
+/* Round-to-nearest quantiser + bit-packer (Sec. 2.4, Sec. 4.2; the on-GPU step of the
+ * on-the-fly quantised loader of Sec. 5).
+ *   w_fp16: device, fp16 [N][K] row-major, 16-byte aligned, read only.
+ *   out:    host struct; out->d must equal *desc; out->codes / scales / zeros are device
+ *           buffers of at least the sizes lpq_packed_sizes reports; they are overwritten.
+ * Results are bit-exact functions of w (fp32 IEEE arithmetic, round-half-even):
+ *   LPQ_ASYM_GROUP  scale = fp16((max - min) / (2^b - 1)) (1.0 if that is zero),
+ *                   zero = min, code = clamp(rint((w - zero) / scale), 0, 2^b - 1)
+ *   LPQ_SYM_CHANNEL scale = fp16(max|w| / 127) (1.0 if zero), code = clamp(rint(w / scale), +-127)
+ *   LPQ_FP16        codes = copy of w.
+ * Weights must be finite.  Errors: NULL, BITS, SCHEME, SHAPE, ALIGN, DEVICE. */
+lpq_status lpq_quantize_pack(const void *w_fp16, const lpq_qdesc *desc, lpq_qweight *out, void *hip_stream);
+
+/* One quantised linear at a prefill micro-batch (Sec. 4.3: M = eta * s tokens): weight tiles
+ * are dequantised in registers to fp16 and multiplied on the matrix cores.
+ *   w: host struct with device buffers;  x: device fp16 [M][K];  y: device fp16 [M][N].
+ * Correct for every M >= 1.  Errors: NULL, BITS, SCHEME, SHAPE (M < 1), ALIGN, DEVICE. */
+lpq_status lpq_qlinear_prefill(const lpq_qweight *w, const void *x, int32_t M, void *y, void *hip_stream);
+
+/* The same function at a decode micro-batch (Sec. 4.3: M = xi rows, one token per sequence):
+ * packed weights are streamed once from HBM and unpacked in registers.  Correct for every
+ * M >= 1 (rows are processed 64 at a time).  Errors as for lpq_qlinear_prefill, plus BUFSIZE. */
+lpq_status lpq_qlinear_decode(const lpq_qweight *w, const void *x, int32_t M, void *y, void *hip_stream);
+
+/* All 4 * n_layers linears of a stage, each layer at its own bitwidth (Sec. 4.3: stage
+ * latency is the sum over its layers of the per-layer latency at that layer's precision).
+ *   layers: host array [n_layers];  io: host array [n_layers] of device pointers.
+ *   phase:  LPQ_PREFILL or LPQ_DECODE selects the kernel family; M as above.
+ * In the decode phase the whole stage is one grouped launch (plus one split-K reduction).
+ * Errors: as above; nothing is launched unless every layer validates. */
+lpq_status lpq_stage_linears(const lpq_layer *layers, int32_t n_layers, lpq_phase phase, int32_t M,
+                             const lpq_layer_io *io, void *hip_stream);
+
+/* Test helper, not on the hot path: w_fp32[n][k] = scale * code + zero (fp32 multiply, then
+ * fp32 add; the fp16 weight itself for LPQ_FP16) read back from the packed buffers.
+ *   w_fp32: device float [N][K].  Errors: NULL, BITS, SCHEME, SHAPE, ALIGN, DEVICE. */
+lpq_status lpq_unpack_dequant(const lpq_qweight *w, void *w_fp32, void *hip_stream);
+
+/* Static string for a status code (never NULL). */
+const char *lpq_status_str(lpq_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LPQ_H */

@@ -1,1 +1,196 @@
-"""MI355X-native mixed-precision quantized linears (the hot path of LLM-PQ, arXiv 2403.01136)."""
+"""MI355X-native mixed-precision quantized linears (the hot path of LLM-PQ, arXiv 2403.01136).
+
+Thin Python binding of the C-ABI library declared in include/lpq.h: argument marshalling only.
+Every step of the path (quantise, pack, decode and prefill linears, stage dispatch) runs in the
+HIP kernels of liblpq.so; torch is used to allocate device memory and to name the stream.
+There is no CPU fallback: if the library is missing, loading raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblpq.so")
+
+LPQ_FP16, LPQ_ASYM_GROUP, LPQ_SYM_CHANNEL = 0, 1, 2
+LPQ_PREFILL, LPQ_DECODE = 0, 1
+LPQ_OK = 0
+LINEARS = ("qkv", "out", "fc1", "fc2")
+EXPORTS = ("lpq_packed_sizes", "lpq_quantize_pack", "lpq_qlinear_prefill", "lpq_qlinear_decode",
+           "lpq_stage_linears", "lpq_unpack_dequant", "lpq_status_str")
+
+
+class lpq_qdesc(ctypes.Structure):
+    _fields_ = [("bits", ctypes.c_int32), ("scheme", ctypes.c_int32), ("group_size", ctypes.c_int32),
+                ("K", ctypes.c_int32), ("N", ctypes.c_int32)]
+
+
+class lpq_qweight(ctypes.Structure):
+    _fields_ = [("d", lpq_qdesc), ("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("zeros", ctypes.c_void_p), ("bias", ctypes.c_void_p)]
+
+
+class lpq_layer(ctypes.Structure):
+    _fields_ = [(n, lpq_qweight) for n in LINEARS]
+
+
+class lpq_layer_io(ctypes.Structure):
+    _fields_ = [("x_" + n, ctypes.c_void_p) for n in LINEARS] + [("y_" + n, ctypes.c_void_p) for n in LINEARS]
+
+
+class LpqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        RuntimeError.__init__(self, "%s failed: status %d (%s)" % (where, status, status_str(status)))
+
+
+_lib = None
+
+
+def load_library():
+    """Load liblpq.so (after torch, so both share one HIP runtime).  Raises if it is not built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("%s is not built; run `python -m paper_2403_01136_amd.build` "
+                               "(there is no fallback path)" % LIB_PATH)
+        import torch  # noqa: F401  (loads the HIP runtime this library must share)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, szp = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)
+        L.lpq_packed_sizes.argtypes = [ctypes.POINTER(lpq_qdesc), szp, szp, szp]
+        L.lpq_quantize_pack.argtypes = [vp, ctypes.POINTER(lpq_qdesc), ctypes.POINTER(lpq_qweight), vp]
+        L.lpq_qlinear_prefill.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, vp]
+        L.lpq_qlinear_decode.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, vp]
+        L.lpq_stage_linears.argtypes = [ctypes.POINTER(lpq_layer), i32, ctypes.c_int, i32, ctypes.POINTER(lpq_layer_io), vp]
+        L.lpq_unpack_dequant.argtypes = [ctypes.POINTER(lpq_qweight), vp, vp]
+        L.lpq_status_str.argtypes = [ctypes.c_int]
+        L.lpq_status_str.restype = ctypes.c_char_p
+        for name in EXPORTS[:-1]:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_str(status):
+    return load_library().lpq_status_str(int(status)).decode()
+
+
+def _check(status, where):
+    if status != LPQ_OK:
+        raise LpqError(status, where)
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def make_desc(bits, scheme, K, N):
+    return lpq_qdesc(bits, scheme, 128 if scheme == LPQ_ASYM_GROUP else 0, K, N)
+
+
+def lpq_packed_sizes(bits, scheme, K, N):
+    """(code_bytes, scale_bytes, zero_bytes) of a weight; host-only."""
+    d = make_desc(bits, scheme, K, N)
+    c, s, z = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load_library().lpq_packed_sizes(ctypes.byref(d), ctypes.byref(c), ctypes.byref(s), ctypes.byref(z)), "lpq_packed_sizes")
+    return c.value, s.value, z.value
+
+
+class QWeight:
+    """Caller-owned packed buffers of one linear (torch tensors on the GPU) plus the ABI struct."""
+
+    def __init__(self, bits, scheme, K, N, device, bias=None):
+        import torch
+        self.bits, self.scheme, self.K, self.N = bits, scheme, K, N
+        cb, sb, zb = lpq_packed_sizes(bits, scheme, K, N)
+        self.codes = torch.empty(cb, dtype=torch.uint8, device=device)
+        self.scales = torch.empty(sb // 2, dtype=torch.float16, device=device) if sb else None
+        self.zeros = torch.empty(zb // 2, dtype=torch.float16, device=device) if zb else None
+        self.bias = bias
+        self.nbytes = cb + sb + zb
+
+    def struct(self):
+        return lpq_qweight(make_desc(self.bits, self.scheme, self.K, self.N), self.codes.data_ptr(),
+                           self.scales.data_ptr() if self.scales is not None else None,
+                           self.zeros.data_ptr() if self.zeros is not None else None,
+                           self.bias.data_ptr() if self.bias is not None else None)
+
+
+def _fp16_2d(t, name):
+    import torch
+    if t.dtype != torch.float16 or t.dim() != 2 or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError("%s must be a contiguous 2-D fp16 CUDA tensor" % name)
+    return t
+
+
+def lpq_quantize_pack(w, bits, scheme, bias=None, stream=None):
+    """w: fp16 [N][K] on the GPU -> QWeight (quantised and packed by the HIP kernel)."""
+    w = _fp16_2d(w, "w")
+    N, K = w.shape
+    qw = QWeight(bits, scheme, K, N, w.device, bias)
+    st, d = qw.struct(), make_desc(bits, scheme, K, N)
+    _check(load_library().lpq_quantize_pack(w.data_ptr(), ctypes.byref(d), ctypes.byref(st), _stream(stream)), "lpq_quantize_pack")
+    return qw
+
+
+def _qlinear(fn_name, qw, x, y, stream):
+    import torch
+    x = _fp16_2d(x, "x")
+    M, K = x.shape
+    if K != qw.K:
+        raise ValueError("x has %d columns, weight has K=%d" % (K, qw.K))
+    if y is None:
+        y = torch.empty((M, qw.N), dtype=torch.float16, device=x.device)
+    else:
+        _fp16_2d(y, "y")
+        if tuple(y.shape) != (M, qw.N):
+            raise ValueError("y must be [%d][%d]" % (M, qw.N))
+    st = qw.struct()
+    _check(getattr(load_library(), fn_name)(ctypes.byref(st), x.data_ptr(), M, y.data_ptr(), _stream(stream)), fn_name)
+    return y
+
+
+def lpq_qlinear_prefill(qw, x, y=None, stream=None):
+    return _qlinear("lpq_qlinear_prefill", qw, x, y, stream)
+
+
+def lpq_qlinear_decode(qw, x, y=None, stream=None):
+    return _qlinear("lpq_qlinear_decode", qw, x, y, stream)
+
+
+class Stage:
+    """Marshalled arguments of lpq_stage_linears, built once and reused across calls.
+
+    layers: list of dicts name -> QWeight; xs / ys: lists of dicts name -> fp16 tensors
+    ([M][K] inputs, [M][N] outputs).  Holds references so the buffers stay alive."""
+
+    def __init__(self, layers, xs, ys):
+        self.n = len(layers)
+        self.keep = (layers, xs, ys)
+        self.M = next(iter(xs[0].values())).shape[0]
+        self.layers = (lpq_layer * self.n)()
+        self.io = (lpq_layer_io * self.n)()
+        for i in range(self.n):
+            for name in LINEARS:
+                qw, x, y = layers[i][name], _fp16_2d(xs[i][name], "x"), _fp16_2d(ys[i][name], "y")
+                if tuple(x.shape) != (self.M, qw.K) or tuple(y.shape) != (self.M, qw.N):
+                    raise ValueError("layer %d %s: x/y shapes do not match the weight" % (i, name))
+                setattr(self.layers[i], name, qw.struct())
+                setattr(self.io[i], "x_" + name, x.data_ptr())
+                setattr(self.io[i], "y_" + name, y.data_ptr())
+
+
+def lpq_stage_linears(stage, phase, stream=None):
+    """Run all 4 * n_layers linears of a Stage in the given phase (LPQ_PREFILL / LPQ_DECODE)."""
+    _check(load_library().lpq_stage_linears(stage.layers, stage.n, phase, stage.M, stage.io, _stream(stream)), "lpq_stage_linears")
+
+
+def lpq_unpack_dequant(qw, stream=None):
+    """Test helper: fp32 [N][K] weights read back from the packed buffers on the GPU."""
+    import torch
+    out = torch.empty((qw.N, qw.K), dtype=torch.float32, device=qw.codes.device)
+    st = qw.struct()
+    _check(load_library().lpq_unpack_dequant(ctypes.byref(st), out.data_ptr(), _stream(stream)), "lpq_unpack_dequant")
+    return out

@@ -1,0 +1,275 @@
+// C-ABI entry points: host-side validation, work decomposition, kernel dispatch.
+// Every argument check happens before the first HIP call (see include/lpq.h).
+#include <algorithm>
+#include <cstdlib>
+#include <mutex>
+#include <vector>
+
+#include "lpq_common.h"
+
+namespace lpq {
+
+int variant_of(const lpq_qdesc& d)
+{
+    if (d.scheme == LPQ_FP16) return d.bits == 16 ? 4 : -1;
+    if (d.scheme == LPQ_ASYM_GROUP) return d.bits == 3 ? 0 : d.bits == 4 ? 1 : d.bits == 8 ? 2 : -1;
+    if (d.scheme == LPQ_SYM_CHANNEL) return d.bits == 8 ? 3 : -1;
+    return -1;
+}
+
+size_t tile_bytes_of(int variant)
+{
+    static const size_t tb[5] = {768, 1024, 2048, 2048, 4096};
+    return tb[variant];
+}
+
+namespace {
+
+lpq_status check_desc(const lpq_qdesc* d)
+{
+    if (!d) return LPQ_ERR_NULL;
+    if (d->bits != 3 && d->bits != 4 && d->bits != 8 && d->bits != 16) return LPQ_ERR_BITS;
+    if (d->scheme != LPQ_FP16 && d->scheme != LPQ_ASYM_GROUP && d->scheme != LPQ_SYM_CHANNEL) return LPQ_ERR_SCHEME;
+    if (variant_of(*d) < 0) return LPQ_ERR_SCHEME;
+    if (d->scheme == LPQ_ASYM_GROUP ? d->group_size != 128 : (d->group_size != 0 && d->group_size != 128)) return LPQ_ERR_SCHEME;
+    if (d->K <= 0 || d->N <= 0 || d->K % 128 != 0 || d->N % 16 != 0) return LPQ_ERR_SHAPE;
+    return LPQ_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+lpq_status check_weight(const lpq_qweight* w)
+{
+    if (!w) return LPQ_ERR_NULL;
+    lpq_status st = check_desc(&w->d);
+    if (st != LPQ_OK) return st;
+    if (!w->codes) return LPQ_ERR_NULL;
+    if (w->d.scheme != LPQ_FP16 && !w->scales) return LPQ_ERR_NULL;
+    if (w->d.scheme == LPQ_ASYM_GROUP && !w->zeros) return LPQ_ERR_NULL;
+    if (misaligned(w->codes) || (w->d.scheme != LPQ_FP16 && misaligned(w->scales)) ||
+        (w->d.scheme == LPQ_ASYM_GROUP && misaligned(w->zeros)) || (w->bias && misaligned(w->bias)))
+        return LPQ_ERR_ALIGN;
+    return LPQ_OK;
+}
+
+lpq_status check_linear(const lpq_qweight* w, const void* x, int32_t M, const void* y)
+{
+    lpq_status st = check_weight(w);
+    if (st != LPQ_OK) return st;
+    if (!x || !y) return LPQ_ERR_NULL;
+    if (M < 1) return LPQ_ERR_SHAPE;
+    if (misaligned(x) || misaligned(y)) return LPQ_ERR_ALIGN;
+    return LPQ_OK;
+}
+
+// ---- split-K workspace: one buffer per device, grown on demand, released at process exit ----
+struct Workspace {
+    std::mutex mu;
+    void* ptr[64] = {};
+    size_t bytes[64] = {};
+};
+Workspace g_ws;
+
+lpq_status workspace(size_t need, float** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_ws.mu);
+    if (g_ws.bytes[dev] < need) {
+        if (g_ws.ptr[dev] && hipFree(g_ws.ptr[dev]) != hipSuccess) return LPQ_ERR_DEVICE;   // waits for in-flight users
+        g_ws.ptr[dev] = nullptr;
+        g_ws.bytes[dev] = 0;
+        const size_t want = std::max(need + need / 4, (size_t)8 << 20);
+        if (hipMalloc(&g_ws.ptr[dev], want) != hipSuccess) { (void)hipGetLastError(); return LPQ_ERR_BUFSIZE; }
+        g_ws.bytes[dev] = want;
+    }
+    *out = static_cast<float*>(g_ws.ptr[dev]);
+    return LPQ_OK;
+}
+
+size_t decode_unit_bytes()
+{
+    static const size_t v = [] {
+        const char* e = std::getenv("LPQ_DECODE_UNIT_KB");
+        long kb = e ? std::atol(e) : 0;
+        return (size_t)(kb > 0 ? kb : 128) << 10;
+    }();
+    return v;
+}
+
+struct LinearCall {
+    const lpq_qweight* w;
+    const void* x;
+    void* y;
+};
+
+// Decode-phase dispatch of a list of independent linears: grouped launches of at most
+// MAX_LIN_PER_LAUNCH linears, 64 token rows per pass.
+lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream)
+{
+    const size_t n = calls.size();
+    const size_t n_launch = (n + MAX_LIN_PER_LAUNCH - 1) / MAX_LIN_PER_LAUNCH;
+    const size_t per_launch = (n + n_launch - 1) / n_launch;
+    // plan every launch first so the workspace is sized (and possibly reallocated) once
+    std::vector<DecodeArgs> plans(n_launch);
+    std::vector<int> red_blocks(n_launch, 0);
+    std::vector<std::vector<size_t>> partial_off(n_launch);
+    size_t ws_floats = 0;
+    for (size_t li = 0; li < n_launch; ++li) {
+        DecodeArgs& a = plans[li];
+        a.M = M;
+        a.m0 = 0;
+        a.n_lin = 0;
+        int units = 0;
+        for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c) {
+            const lpq_qweight& w = *calls[c].w;
+            LinDesc& L = a.lin[a.n_lin++];
+            L.codes = static_cast<const uint8_t*>(w.codes);
+            L.scales = static_cast<const uint16_t*>(w.scales);
+            L.zeros = static_cast<const uint16_t*>(w.zeros);
+            L.x = static_cast<const uint16_t*>(calls[c].x);
+            L.y = static_cast<uint16_t*>(calls[c].y);
+            L.bias = static_cast<const uint16_t*>(w.bias);
+            L.partial = nullptr;
+            L.K = w.d.K;
+            L.N = w.d.N;
+            L.variant = variant_of(w.d);
+            const int rows = decode_rows_per_unit(L.variant);
+            const int KT = L.K / 128;
+            const size_t step_bytes = (size_t)rows * 128 * (size_t)w.d.bits / 8;      // one unit, one 128-column tile
+            const int kt_target = (int)std::max<size_t>(1, decode_unit_bytes() / step_bytes);
+            int ksplit = std::max(1, (KT + kt_target / 2) / kt_target);
+            L.kt_per_split = (KT + ksplit - 1) / ksplit;
+            L.ksplit = (KT + L.kt_per_split - 1) / L.kt_per_split;
+            L.row_groups = (L.N + rows - 1) / rows;
+            L.unit_begin = units;
+            units += L.row_groups * L.ksplit;
+            L.red_begin = red_blocks[li];
+            if (L.ksplit > 1) {
+                partial_off[li].push_back(ws_floats);
+                ws_floats += (size_t)L.ksplit * (size_t)M * (size_t)L.N;
+                const int m_cnt = std::min(M, 64);
+                red_blocks[li] += (int)(((size_t)(L.N / 4) * m_cnt + 255) / 256);
+            } else {
+                partial_off[li].push_back((size_t)-1);
+            }
+        }
+        a.total_units = units;
+    }
+    float* ws = nullptr;
+    if (ws_floats) {
+        lpq_status st = workspace(ws_floats * sizeof(float), &ws);
+        if (st != LPQ_OK) return st;
+    }
+    for (size_t li = 0; li < n_launch; ++li) {
+        DecodeArgs& a = plans[li];
+        for (int i = 0; i < a.n_lin; ++i)
+            if (a.lin[i].ksplit > 1) a.lin[i].partial = ws + partial_off[li][i];
+        for (int m0 = 0; m0 < M; m0 += 64) {
+            a.m0 = m0;
+            if (launch_decode(a, red_blocks[li], stream) != hipSuccess) return LPQ_ERR_DEVICE;
+        }
+    }
+    return LPQ_OK;
+}
+
+}  // namespace
+}  // namespace lpq
+
+using namespace lpq;
+
+extern "C" {
+
+lpq_status lpq_packed_sizes(const lpq_qdesc* desc, size_t* code_bytes, size_t* scale_bytes, size_t* zero_bytes)
+{
+    if (!desc || !code_bytes || !scale_bytes || !zero_bytes) return LPQ_ERR_NULL;
+    lpq_status st = check_desc(desc);
+    if (st != LPQ_OK) return st;
+    const size_t K = (size_t)desc->K, N = (size_t)desc->N;
+    *code_bytes = K * N * (size_t)desc->bits / 8;
+    *scale_bytes = desc->scheme == LPQ_ASYM_GROUP ? N * (K / 128) * 2 : desc->scheme == LPQ_SYM_CHANNEL ? N * 2 : 0;
+    *zero_bytes = desc->scheme == LPQ_ASYM_GROUP ? *scale_bytes : 0;
+    return LPQ_OK;
+}
+
+lpq_status lpq_quantize_pack(const void* w_fp16, const lpq_qdesc* desc, lpq_qweight* out, void* hip_stream)
+{
+    if (!w_fp16 || !desc || !out) return LPQ_ERR_NULL;
+    lpq_status st = check_desc(desc);
+    if (st != LPQ_OK) return st;
+    if (out->d.bits != desc->bits || out->d.scheme != desc->scheme || out->d.K != desc->K || out->d.N != desc->N ||
+        out->d.group_size != desc->group_size)
+        return LPQ_ERR_SHAPE;
+    st = check_weight(out);
+    if (st != LPQ_OK) return st;
+    if (misaligned(w_fp16)) return LPQ_ERR_ALIGN;
+    return launch_quantize_pack(w_fp16, *desc, *out, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPQ_OK : LPQ_ERR_DEVICE;
+}
+
+lpq_status lpq_unpack_dequant(const lpq_qweight* w, void* w_fp32, void* hip_stream)
+{
+    lpq_status st = check_weight(w);
+    if (st != LPQ_OK) return st;
+    if (!w_fp32) return LPQ_ERR_NULL;
+    if (misaligned(w_fp32)) return LPQ_ERR_ALIGN;
+    return launch_unpack_dequant(*w, static_cast<float*>(w_fp32), static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPQ_OK
+                                                                                                                       : LPQ_ERR_DEVICE;
+}
+
+lpq_status lpq_qlinear_prefill(const lpq_qweight* w, const void* x, int32_t M, void* y, void* hip_stream)
+{
+    lpq_status st = check_linear(w, x, M, y);
+    if (st != LPQ_OK) return st;
+    return launch_prefill(*w, x, M, y, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPQ_OK : LPQ_ERR_DEVICE;
+}
+
+lpq_status lpq_qlinear_decode(const lpq_qweight* w, const void* x, int32_t M, void* y, void* hip_stream)
+{
+    lpq_status st = check_linear(w, x, M, y);
+    if (st != LPQ_OK) return st;
+    std::vector<LinearCall> calls(1, LinearCall{w, x, y});
+    return run_decode(calls, M, static_cast<hipStream_t>(hip_stream));
+}
+
+lpq_status lpq_stage_linears(const lpq_layer* layers, int32_t n_layers, lpq_phase phase, int32_t M, const lpq_layer_io* io,
+                             void* hip_stream)
+{
+    if (!layers || !io) return LPQ_ERR_NULL;
+    if (n_layers < 1 || n_layers > 4096) return LPQ_ERR_SHAPE;
+    if (phase != LPQ_PREFILL && phase != LPQ_DECODE) return LPQ_ERR_UNSUPPORTED;
+    std::vector<LinearCall> calls;
+    calls.reserve((size_t)n_layers * 4);
+    for (int32_t i = 0; i < n_layers; ++i) {
+        const lpq_qweight* w[4] = {&layers[i].qkv, &layers[i].out, &layers[i].fc1, &layers[i].fc2};
+        const void* xs[4] = {io[i].x_qkv, io[i].x_out, io[i].x_fc1, io[i].x_fc2};
+        void* ys[4] = {io[i].y_qkv, io[i].y_out, io[i].y_fc1, io[i].y_fc2};
+        for (int j = 0; j < 4; ++j) {
+            lpq_status st = check_linear(w[j], xs[j], M, ys[j]);
+            if (st != LPQ_OK) return st;
+            calls.push_back(LinearCall{w[j], xs[j], ys[j]});
+        }
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (phase == LPQ_DECODE) return run_decode(calls, M, stream);
+    for (const LinearCall& c : calls)
+        if (launch_prefill(*c.w, c.x, M, c.y, stream) != hipSuccess) return LPQ_ERR_DEVICE;
+    return LPQ_OK;
+}
+
+const char* lpq_status_str(lpq_status status)
+{
+    switch (status) {
+    case LPQ_OK: return "ok";
+    case LPQ_ERR_NULL: return "null pointer";
+    case LPQ_ERR_BITS: return "bits must be 3, 4, 8 or 16";
+    case LPQ_ERR_SCHEME: return "bits / scheme / group_size do not match";
+    case LPQ_ERR_SHAPE: return "bad shape (K % 128, N % 16, M >= 1, descriptor mismatch)";
+    case LPQ_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case LPQ_ERR_BUFSIZE: return "workspace allocation failed";
+    case LPQ_ERR_DEVICE: return "HIP call failed";
+    case LPQ_ERR_UNSUPPORTED: return "unsupported request";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

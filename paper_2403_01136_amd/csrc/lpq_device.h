@@ -1,0 +1,153 @@
+// Device-side building blocks shared by the gfx950 kernels: vector types, tile loads in the
+// packed storage format (see include/lpq.h), and in-register unpacking to fp16 MFMA operands.
+//
+// Operand convention used by every matmul kernel here (v_mfma_f32_16x16x32_f16, wave64):
+//   A = activations: lane (i = lane%16 -> token, kq = lane/16) holds x[token][32*j + 8*kq + 0..7]
+//   B = weights:     lane (r = lane%16 -> output row, kq)      holds w~[row][32*j + 8*kq + 0..7]
+//   D (4 floats):    lane holds y[token = 4*(lane/16) + v][row = lane%16], v = 0..3
+// so a lane's per-(row, group) scale and zero apply to its own B operand and to all four of
+// its accumulators.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lpq {
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+enum { SCH_FP16 = 0, SCH_ASYM = 1, SCH_SYM = 2 };
+enum { GROUP = 128, TILE_ROWS = 16 };
+
+// kernel-variant ids: one per (bits, scheme) the library supports
+enum { V_W3 = 0, V_W4 = 1, V_W8 = 2, V_I8 = 3, V_F16 = 4, V_COUNT = 5 };
+
+template <int V> struct VInfo;
+template <> struct VInfo<V_W3>  { enum { BITS = 3,  SCHEME = SCH_ASYM, TILE_BYTES = 768 }; };
+template <> struct VInfo<V_W4>  { enum { BITS = 4,  SCHEME = SCH_ASYM, TILE_BYTES = 1024 }; };
+template <> struct VInfo<V_W8>  { enum { BITS = 8,  SCHEME = SCH_ASYM, TILE_BYTES = 2048 }; };
+template <> struct VInfo<V_I8>  { enum { BITS = 8,  SCHEME = SCH_SYM,  TILE_BYTES = 2048 }; };
+template <> struct VInfo<V_F16> { enum { BITS = 16, SCHEME = SCH_FP16, TILE_BYTES = 4096 }; };
+
+__device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ __forceinline__ uint32_t as_u32(h2 h) { return __builtin_bit_cast(uint32_t, h); }
+__device__ __forceinline__ h2 splat(_Float16 v) { h2 r = {v, v}; return r; }
+__device__ __forceinline__ h2 pk_fma(h2 a, h2 b, h2 c) { return __builtin_elementwise_fma(a, b, c); }
+
+// ---- packed codes of one 16x128 tile, as held by one lane ------------------------------
+template <int V> struct WRaw;
+template <> struct WRaw<V_W3>  { u32x3 q; };
+template <> struct WRaw<V_W4>  { u32x4 q; };
+template <> struct WRaw<V_W8>  { u32x4 q[2]; };
+template <> struct WRaw<V_I8>  { u32x4 q[2]; };
+template <> struct WRaw<V_F16> { u32x4 q[4]; };
+
+// codes: base of the packed buffer; tile = nt * KT + kt.  For fp16, `codes` is the row-major
+// matrix and the lane reads its four 16-byte pieces of row (16*nt + r).
+template <int V>
+__device__ __forceinline__ WRaw<V> load_tile(const uint8_t* __restrict__ codes, long nt, int KT, int kt, int lane)
+{
+    WRaw<V> w;
+    if constexpr (V == V_W3) {
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(codes + ((size_t)nt * KT + kt) * 768 + 12 * lane);
+        w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x3*>(p));
+    } else if constexpr (V == V_W4) {
+        w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(codes + ((size_t)nt * KT + kt) * 1024 + 16 * lane));
+    } else if constexpr (V == V_W8 || V == V_I8) {
+        const uint8_t* p = codes + ((size_t)nt * KT + kt) * 2048 + 16 * lane;
+        w.q[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        w.q[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 1024));
+    } else {
+        const int r = lane & 15, kq = lane >> 4;
+        const uint8_t* p = codes + (((size_t)nt * 16 + r) * (size_t)KT * 128 + (size_t)kt * 128 + 8 * kq) * 2;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w.q[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 64 * j));
+    }
+    return w;
+}
+
+// ---- unpack to fp16 values that are exactly the integer codes --------------------------
+// OR-ing a code field into the mantissa of fp16 1024.0 (0x6400) gives 1024 + c*code exactly,
+// c = 2^(field's bit offset in the half-word); one packed op then removes the offset.
+
+__device__ __forceinline__ h2 magic_to_int(uint32_t biased, int log2c)
+{
+    // (1024 + c*q) -> q, exact: q <= 255 is an fp16 integer
+    if (log2c == 0) return as_h2(biased) - splat((_Float16)1024.0f);
+    const _Float16 inv = (_Float16)(1.0f / (float)(1 << log2c));
+    const _Float16 off = (_Float16)(-1024.0f / (float)(1 << log2c));
+    return pk_fma(as_h2(biased), splat(inv), splat(off));
+}
+
+// out[j] = the lane's 8 operand values of MFMA step j, as integer-valued fp16 codes
+template <int V>
+__device__ __forceinline__ void unpack_codes(const WRaw<V>& w, h8 out[4])
+{
+    constexpr uint32_t MAGIC = 0x64006400u;
+    if constexpr (V == V_W4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t q = w.q[j], t = q >> 8;
+            h2 p0 = magic_to_int((q & 0x000F000Fu) | MAGIC, 0);
+            h2 p1 = magic_to_int((q & 0x00F000F0u) | MAGIC, 4);
+            h2 p2 = magic_to_int((t & 0x000F000Fu) | MAGIC, 0);
+            h2 p3 = magic_to_int((t & 0x00F000F0u) | MAGIC, 4);
+            h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+            out[j] = o;
+        }
+    } else if constexpr (V == V_W3) {
+        h2 pr[16];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const uint32_t q = w.q[i], t = q >> 9;
+            pr[5 * i + 0] = magic_to_int((q & 0x00070007u) | MAGIC, 0);
+            pr[5 * i + 1] = magic_to_int((q & 0x00380038u) | MAGIC, 3);
+            pr[5 * i + 2] = magic_to_int((q & 0x01C001C0u) | MAGIC, 6);
+            pr[5 * i + 3] = magic_to_int((t & 0x00070007u) | MAGIC, 0);
+            pr[5 * i + 4] = magic_to_int((t & 0x00380038u) | MAGIC, 3);
+        }
+        uint32_t u = ((w.q[0] >> 15) & 0x00010001u) | MAGIC;
+        u |= (w.q[1] >> 14) & 0x00020002u;
+        u |= (w.q[2] >> 13) & 0x00040004u;
+        pr[15] = magic_to_int(u, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            h8 o = {pr[4 * j][0], pr[4 * j][1], pr[4 * j + 1][0], pr[4 * j + 1][1],
+                    pr[4 * j + 2][0], pr[4 * j + 2][1], pr[4 * j + 3][0], pr[4 * j + 3][1]};
+            out[j] = o;
+        }
+    } else if constexpr (V == V_W8 || V == V_I8) {
+        constexpr uint32_t M8 = 0x64646464u;
+        const _Float16 off = (V == V_I8) ? (_Float16)1152.0f : (_Float16)1024.0f;   // 1024 (+128 for signed)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t a = w.q[j >> 1][2 * (j & 1)], b = w.q[j >> 1][2 * (j & 1) + 1];
+            if constexpr (V == V_I8) { a ^= 0x80808080u; b ^= 0x80808080u; }       // two's complement -> offset binary
+            h2 p0 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00050004u)) - splat(off);
+            h2 p1 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00070006u)) - splat(off);
+            h2 p2 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00050004u)) - splat(off);
+            h2 p3 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00070006u)) - splat(off);
+            h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+            out[j] = o;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = __builtin_bit_cast(h8, w.q[j]);
+    }
+}
+
+// w~ = scale * code + zero with one fp16 rounding per weight (packed fma)
+__device__ __forceinline__ void apply_scale_zero(h8 v[4], _Float16 s, _Float16 z)
+{
+    const h8 s8 = {s, s, s, s, s, s, s, s}, z8 = {z, z, z, z, z, z, z, z};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = __builtin_elementwise_fma(v[j], s8, z8);
+}
+
+__device__ __forceinline__ f4 mfma16(h8 a, h8 b, f4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+
+}  // namespace lpq

@@ -1,0 +1,93 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the header declares,
+reports sizes, and rejects bad arguments on the host before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2403_01136_amd as lpq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "lpq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lpq_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = lpq.load_library()
+    names = header_functions()
+    assert set(names) == set(lpq.EXPORTS), names
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_packed_sizes_are_dense():
+    # Sec. 4.1: bytes = weights * bit / 8; scale and zero are fp16 per (row, 128 columns)
+    for bits, scheme in ((3, 1), (4, 1), (8, 1), (8, 2), (16, 0)):
+        for K, N in ((128, 16), (5120, 15360), (57344, 14336)):
+            c, s, z = lpq.lpq_packed_sizes(bits, scheme, K, N)
+            assert c * 8 == K * N * bits
+            assert s == (N * (K // 128) * 2 if scheme == 1 else (N * 2 if scheme == 2 else 0))
+            assert z == (s if scheme == 1 else 0)
+
+
+@pytest.mark.parametrize("bits,scheme,K,N,status", [
+    (5, 1, 128, 16, 2), (2, 1, 128, 16, 2), (4, 7, 128, 16, 3), (16, 1, 128, 16, 3), (3, 2, 128, 16, 3), (4, 0, 128, 16, 3),
+    (4, 1, 100, 16, 4), (4, 1, 128, 24, 4), (4, 1, 0, 16, 4), (4, 1, 128, -16, 4),
+])
+def test_bad_descriptors(bits, scheme, K, N, status):
+    with pytest.raises(lpq.LpqError) as e:
+        lpq.lpq_packed_sizes(bits, scheme, K, N)
+    assert e.value.status == status
+
+
+def test_group_size_must_be_128_for_grouped_scheme():
+    lib = lpq.load_library()
+    c = ctypes.c_size_t()
+    d = lpq.lpq_qdesc(4, 1, 64, 128, 16)
+    assert lib.lpq_packed_sizes(ctypes.byref(d), ctypes.byref(c), ctypes.byref(c), ctypes.byref(c)) == 3
+    assert lib.lpq_packed_sizes(None, ctypes.byref(c), ctypes.byref(c), ctypes.byref(c)) == 1
+    d = lpq.lpq_qdesc(4, 1, 128, 128, 16)
+    assert lib.lpq_packed_sizes(ctypes.byref(d), None, ctypes.byref(c), ctypes.byref(c)) == 1
+
+
+def test_entry_points_validate_before_touching_the_device():
+    lib = lpq.load_library()
+    d = lpq.make_desc(4, 1, 128, 16)
+    fake = 0x10000          # never dereferenced: every call below must fail validation first
+    good = lpq.lpq_qweight(d, fake, fake, fake, None)
+    # NULL pointers
+    assert lib.lpq_quantize_pack(None, ctypes.byref(d), ctypes.byref(good), None) == 1
+    assert lib.lpq_qlinear_decode(ctypes.byref(good), None, 1, fake, None) == 1
+    assert lib.lpq_qlinear_prefill(ctypes.byref(good), fake, 1, None, None) == 1
+    nz = lpq.lpq_qweight(d, fake, fake, None, None)
+    assert lib.lpq_qlinear_decode(ctypes.byref(nz), fake, 1, fake, None) == 1
+    assert lib.lpq_unpack_dequant(ctypes.byref(good), None, None) == 1
+    assert lib.lpq_stage_linears(None, 1, 1, 1, None, None) == 1
+    # M < 1
+    assert lib.lpq_qlinear_decode(ctypes.byref(good), fake, 0, fake, None) == 4
+    assert lib.lpq_qlinear_prefill(ctypes.byref(good), fake, -3, fake, None) == 4
+    # alignment
+    assert lib.lpq_qlinear_decode(ctypes.byref(good), fake + 2, 1, fake, None) == 5
+    odd = lpq.lpq_qweight(d, fake + 8, fake, fake, None)
+    assert lib.lpq_qlinear_prefill(ctypes.byref(odd), fake, 1, fake, None) == 5
+    assert lib.lpq_quantize_pack(fake + 4, ctypes.byref(d), ctypes.byref(good), None) == 5
+    # descriptor mismatch between desc and out
+    d2 = lpq.make_desc(3, 1, 128, 16)
+    assert lib.lpq_quantize_pack(fake, ctypes.byref(d2), ctypes.byref(good), None) == 4
+    # bad bits inside a weight
+    bad = lpq.lpq_qweight(lpq.lpq_qdesc(5, 1, 128, 128, 16), fake, fake, fake, None)
+    assert lib.lpq_qlinear_decode(ctypes.byref(bad), fake, 1, fake, None) == 2
+    # stage: bad layer count, bad phase, one bad layer rejects the whole call
+    layers = (lpq.lpq_layer * 1)()
+    io = (lpq.lpq_layer_io * 1)()
+    assert lib.lpq_stage_linears(layers, 0, 1, 1, io, None) == 4
+    assert lib.lpq_stage_linears(layers, 1, 5, 1, io, None) == 8
+    assert lib.lpq_stage_linears(layers, 1, 1, 1, io, None) != 0      # zeroed layer: bits = 0
+    for i in range(9):
+        assert isinstance(lpq.status_str(i), str) and lpq.status_str(i)
+    assert lpq.status_str(99) == "unknown status"

@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-linear hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--only decode|prefill|all]
+
+Workload: the OPT-13B-shaped stage (8 consecutive layers, bits [16,8,4,4,3,3,4,8], g = 128) that
+the headline metric is quoted on, with seeded synthetic weights and activations.  One "step" is one
+decode-phase pass of lpq_stage_linears over the whole stage at the decode micro-batch (M = 16);
+the prefill-phase pass (M = 4 x 512) and the quantise+pack pass are timed in the same run and
+reported in the same JSON line.  Inputs are resident in HBM before any timed region starts.
+
+Prints ONE JSON line: the contract fields, plus `roofline` (dominant kernel: decode, HBM-bound),
+`prefill` (TFLOP/s and its MFMA roofline), `quantize` and `cpu_baseline` (the CPU oracle timed on
+a bounded sample of the same workload on this machine's host cores).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 matrix peak, published
+
+
+def build_stage(cfg, M, device, quant_times=None):
+    """Draw, quantise and pack every linear of the stage on the GPU; returns (Stage, ys)."""
+    import torch
+    import paper_2403_01136_amd as lpq
+    from paper_2403_01136_amd import workloads as wl
+    shapes = wl.linear_shapes(cfg)
+    layers, xs, ys = [], [], []
+    for li, (bits, scheme) in enumerate(cfg["layers"]):
+        lw, lx, ly = {}, {}, {}
+        x_h = wl.act_torch(M, cfg["h"], cfg["act_outliers"], device, cfg["name"], li, "h", M)
+        x_f = wl.act_torch(M, cfg["f"], cfg["act_outliers"], device, cfg["name"], li, "f", M)
+        for name in wl.LINEARS:
+            K, N = shapes[name]
+            w = wl.weight_torch(N, K, device, cfg["name"], li, name)
+            if quant_times is not None:
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                lw[name] = lpq.lpq_quantize_pack(w, bits, scheme)
+                e1.record()
+                torch.cuda.synchronize()
+                quant_times.append((K * N, e0.elapsed_time(e1)))
+            else:
+                lw[name] = lpq.lpq_quantize_pack(w, bits, scheme)
+            del w
+            lx[name] = x_f if name == "fc2" else x_h
+            ly[name] = torch.empty((M, N), dtype=torch.float16, device=device)
+        layers.append(lw), xs.append(lx), ys.append(ly)
+    return lpq.Stage(layers, xs, ys), ys
+
+
+def reuse_stage(stage, M, cfg, device):
+    """A second Stage over the same packed weights with fresh activations of M rows."""
+    import torch
+    import paper_2403_01136_amd as lpq
+    from paper_2403_01136_amd import workloads as wl
+    layers = stage.keep[0]
+    xs, ys = [], []
+    for li in range(len(layers)):
+        x_h = wl.act_torch(M, cfg["h"], cfg["act_outliers"], device, cfg["name"], li, "h", M)
+        x_f = wl.act_torch(M, cfg["f"], cfg["act_outliers"], device, cfg["name"], li, "f", M)
+        xs.append({n: (x_f if n == "fc2" else x_h) for n in wl.LINEARS})
+        ys.append({n: torch.empty((M, layers[li][n].N), dtype=torch.float16, device=device) for n in wl.LINEARS})
+    return lpq.Stage(layers, xs, ys), ys
+
+
+def time_phase(stage, phase, steps, warmup):
+    """W untimed + exactly K timed passes, bracketed by synchronize; HIP events on the launch stream."""
+    import torch
+    import paper_2403_01136_amd as lpq
+    for _ in range(warmup):
+        lpq.lpq_stage_linears(stage, phase)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        lpq.lpq_stage_linears(stage, phase)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def act_bytes(cfg, M):
+    from paper_2403_01136_amd import workloads as wl
+    return sum(2 * M * K + 2 * M * N for _ in cfg["layers"] for (K, N) in wl.linear_shapes(cfg).values())
+
+
+def cpu_baseline(cfg, M, budget_rows=20480):
+    """The CPU oracle (as it stands) on a bounded sample of the same workload: for every layer of the
+    stage, `budget_rows` output rows of its FC1 linear, quantise -> dequantise -> fp64 matmul at the
+    decode micro-batch.  Reported in the metric's unit: packed-weight bytes of the sample per second."""
+    import numpy as np
+    import oracle
+    from paper_2403_01136_amd import workloads as wl
+    K, _ = wl.linear_shapes(cfg)["fc1"]
+    cores = len(os.sched_getaffinity(0))
+    x = wl.act_np(M, K, cfg["act_outliers"], cfg["name"], "cpu_baseline")
+    ws = [wl.weight_np(budget_rows, K, cfg["name"], li, "fc1", "cpu_baseline") for li in range(len(cfg["layers"]))]
+    oracle.default()
+    t0 = time.perf_counter()
+    nbytes = 0
+    for w, (bits, scheme) in zip(ws, cfg["layers"]):
+        oracle.qlinear(x, w, bits, scheme)
+        nbytes += wl.packed_bytes(bits, scheme, K, budget_rows)
+    dt = time.perf_counter() - t0
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle", "seconds": round(dt, 2),
+            "sample": "%d rows of FC1 (K=%d) of each of the %d layers, quantize+dequant+fp64 matmul at M=%d"
+                      % (budget_rows, K, len(cfg["layers"]), M)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--decode-m", type=int, default=None)
+    ap.add_argument("--only", choices=["all", "decode", "prefill"], default="all")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (pipeline stages are independent units; "
+              "see DESIGN.md for how the path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2403_01136_amd as lpq
+    from paper_2403_01136_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no fallback", file=sys.stderr)
+        sys.exit(3)
+    lpq.load_library()
+    device = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    Md = args.decode_m or cfg["decode_Ms"][-1 if args.config != 4 else 2]
+    Mp = cfg["prefill_M"]
+
+    qt = []
+    stage_d, _ = build_stage(cfg, Md, device, quant_times=qt)
+    wbytes = wl.stage_packed_bytes(cfg)
+    out = {"metric": "decode packed-weight GB/s", "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+           "config": {"workload": "configs[%d] %s: %d layers, bits %s, g=128, decode M=%d, prefill M=%d"
+                                  % (args.config, cfg["name"], len(cfg["layers"]), [b for b, _ in cfg["layers"]], Md, Mp),
+                      "packed_weight_bytes": wbytes}}
+    n_w = sum(n for n, _ in qt)
+    q_ms = sum(t for _, t in qt)
+    out["quantize"] = {"value": n_w / q_ms / 1e6, "unit": "Gweights/s", "ms_total": round(q_ms, 3),
+                       "fp16_read_GBs": round(2 * n_w / q_ms / 1e6, 1)}
+
+    if args.only in ("all", "decode"):
+        ms, wall = time_phase(stage_d, lpq.LPQ_DECODE, args.steps, args.warmup)
+        algo = wbytes + act_bytes(cfg, Md)
+        out.update({"value": wbytes / ms / 1e6, "ms_per_step": ms, "host_ms_per_step": wall})
+        out["roofline"] = {"bound": "hbm", "achieved": algo / ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": algo / ms / 1e6 / HBM_PEAK_GBS, "traffic": None, "kernel": "decode_kernel",
+                           "algorithmic_bytes_per_launch": algo}
+    if args.only in ("all", "prefill"):
+        stage_p, _ = reuse_stage(stage_d, Mp, cfg, device)
+        psteps, pwarm = max(3, args.steps // 10), max(1, args.warmup // 5)
+        ms, wall = time_phase(stage_p, lpq.LPQ_PREFILL, psteps, pwarm)
+        flops = wl.stage_flops(cfg, Mp)
+        out["prefill"] = {"metric": "prefill TFLOP/s", "value": flops / ms / 1e9, "unit": "TFLOP/s", "ms_per_step": ms,
+                          "steps": psteps, "warmup": pwarm,
+                          "roofline": {"bound": "mfma", "achieved": flops / ms / 1e9, "peak": MFMA_F16_PEAK_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": flops / ms / 1e9 / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+                                       "kernel": "prefill_kernel", "algorithmic_flops_per_step": flops}}
+        if args.only == "prefill":
+            out.update({"metric": "prefill TFLOP/s", "unit": "TFLOP/s", "value": out["prefill"]["value"],
+                        "ms_per_step": ms, "steps": psteps, "warmup": pwarm, "roofline": out["prefill"]["roofline"]})
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, Md)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -25,22 +25,25 @@
  *     aligned; y is overwritten.  A linear computes y[m][n] = sum_k x[m][k] * w~[n][k]
  *     (+ bias[n]) with fp32 accumulation and one final round-to-nearest-even to fp16.
  *
- * Storage format of a quantised weight W [N][K] (K contiguous); N % 16 == 0, K % 128 == 0
- *   A tile is 16 rows x 128 columns (one quantisation group per row); tiles are stored in
- *   order nt * (K/128) + kt.  Inside a tile, lane = 16*kq + r (r = row in tile, kq = 0..3)
- *   owns the 32 codes of row r at tile columns 32*j + 8*kq + e (j = 0..3, e = 0..7), numbered
- *   c = 8*j + e -- the operand layout of one wavefront's four v_mfma_f32_16x16x32_f16 steps.
- *     bits 4:  16 B per lane at 16*lane; little-endian u32 word j; code e at bit
+ * Storage format of a quantised weight W [N][K] (K contiguous); N % 64 == 0, K % 128 == 0
+ *   A block is 64 rows x 128 columns (one quantisation group per row); blocks are stored in
+ *   order rb * (K/128) + kt, so the blocks of one 64-row band are one contiguous byte stream.
+ *   A block holds four 16-row tiles back to back; tile t holds rows 64*rb + 4*r + t (r = 0..15).
+ *   Inside a tile, lane = 16*kq + r (kq = 0..3) owns the 32 codes of its row at block columns
+ *   32*j + 8*kq + e (j = 0..3, e = 0..7), numbered c = 8*j + e -- the operand layout of one
+ *   wavefront's four v_mfma_f32_16x16x32_f16 steps; a lane's four tiles are four consecutive rows.
+ *     bits 4:  1024-byte tile; 16 B per lane at 16*lane; little-endian u32 word j; code e at bit
  *              4*(e/2) + 16*(e%2) of word j (even e in the low half-word, odd e in the high).
- *     bits 3:  12 B per lane at 12*lane; three LE u32 words.  Pair P = c/2, half h = c%2.
- *              P < 15: word P/5, bits 16*h + 3*(P%5) .. +2.  P == 15: bit t of the code is
- *              bit 16*h + 15 of word t.  (768 B per tile: dense, not padded to 4 bits.)
- *     bits 8:  32 B per lane as two 16-byte pieces; piece p (j = 2p, 2p+1) at
+ *     bits 3:  768-byte tile (dense, not padded to 4 bits); 12 B per lane at 12*lane; three LE
+ *              u32 words.  Pair P = c/2, half h = c%2.  P < 15: word P/5, bits 16*h + 3*(P%5) .. +2.
+ *              P == 15: bit i of the code is bit 16*h + 15 of word i.
+ *     bits 8:  2048-byte tile; 32 B per lane as two 16-byte pieces; piece p (j = 2p, 2p+1) at
  *              1024*p + 16*lane; byte 8*(j%2) + e.  Unsigned for LPQ_ASYM_GROUP, two's
  *              complement in [-127, 127] for LPQ_SYM_CHANNEL.
  *     bits 16: the row-major fp16 matrix itself (a byte copy of W).
- *   scales, zeros: fp16 [N][K/128] row-major (LPQ_ASYM_GROUP); scales fp16 [N] and no zeros
- *   (LPQ_SYM_CHANNEL); neither for LPQ_FP16.  "zero" is the group minimum, a floating offset.
+ *   scales, zeros: fp16 [K/128][N], group-major (index g*N + n) for LPQ_ASYM_GROUP; scales fp16
+ *   [N] and no zeros for LPQ_SYM_CHANNEL; neither for LPQ_FP16.  "zero" is the group minimum, a
+ *   floating offset.
  */
 #ifndef LPQ_H
 #define LPQ_H
@@ -57,7 +60,7 @@ typedef enum {
     LPQ_ERR_NULL = 1,        /* a required pointer is NULL                                   */
     LPQ_ERR_BITS = 2,        /* bits not in {3, 4, 8, 16}                                    */
     LPQ_ERR_SCHEME = 3,      /* unknown scheme, or bits / scheme / group_size do not match   */
-    LPQ_ERR_SHAPE = 4,       /* K % 128, N % 16, K, N, M or n_layers out of range            */
+    LPQ_ERR_SHAPE = 4,       /* K % 128, N % 64, K, N, M or n_layers out of range            */
     LPQ_ERR_ALIGN = 5,       /* a data pointer is not 16-byte aligned                        */
     LPQ_ERR_BUFSIZE = 6,     /* internal workspace could not be grown                        */
     LPQ_ERR_DEVICE = 7,      /* a HIP call failed                                            */
@@ -79,7 +82,7 @@ typedef struct {
     int32_t scheme;      /* lpq_scheme    */
     int32_t group_size;
     int32_t K;           /* input features, % 128 == 0  */
-    int32_t N;           /* output features, % 16 == 0  */
+    int32_t N;           /* output features, % 64 == 0  */
 } lpq_qdesc;
 
 /* One quantised weight: descriptor + caller-owned device buffers sized by lpq_packed_sizes.

@@ -19,7 +19,7 @@ import numpy as np
 
 FP16, ASYM_GROUP, SYM_CHANNEL = 0, 1, 2
 GROUP = 128
-TILE_ROWS = 16
+BLOCK_ROWS = 64
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lpq_oracle.c")
@@ -58,7 +58,7 @@ class Oracle:
     """
 
     FP16, ASYM_GROUP, SYM_CHANNEL = FP16, ASYM_GROUP, SYM_CHANNEL
-    GROUP, TILE_ROWS = GROUP, TILE_ROWS
+    GROUP, BLOCK_ROWS = GROUP, BLOCK_ROWS
 
     def __init__(self, libpath=None):
         if libpath is None:
@@ -73,6 +73,7 @@ class Oracle:
         L.lpq_oracle_quantize.argtypes = [vp, i, i, l, l, vp, vp, vp]
         L.lpq_oracle_pack.argtypes = [vp, i, i, l, l, vp]
         L.lpq_oracle_unpack.argtypes = [vp, i, i, l, l, vp]
+        L.lpq_oracle_store_scales.argtypes = [vp, l, l, vp]
         L.lpq_oracle_dequant.argtypes = [vp, vp, vp, i, i, l, l, vp]
         L.lpq_oracle_fp16_to_f32.argtypes = [vp, l, vp]
         L.lpq_oracle_matmul.argtypes = [vp, vp, l, l, l, vp, vp]
@@ -159,12 +160,27 @@ class Oracle:
             raise ValueError("lpq_oracle_matmul rc=%d" % rc)
         return y
 
+    def store_scales(self, natural, K):
+        """Scales or zeros in natural [N][K/128] order -> the stored [K/128][N] order."""
+        natural = _u16(natural)
+        N, G = natural.shape
+        assert G == K // GROUP
+        out = np.empty((G, N), np.uint16)
+        rc = self._L.lpq_oracle_store_scales(_ptr(natural), K, N, _ptr(out))
+        if rc:
+            raise ValueError("lpq_oracle_store_scales rc=%d" % rc)
+        return out
+
     def quantize_pack(self, w, bits, scheme):
-        """O1-O3 in one call.  Returns (packed uint8, scales uint16 | None, zeros uint16 | None)."""
+        """O1-O3 in one call, everything in stored order: (packed uint8, scales uint16 | None,
+        zeros uint16 | None); grouped scales and zeros are [K/128][N], per-row scales [N]."""
         w = _u16(w)
         if scheme == FP16:
             return w.reshape(-1).view(np.uint8).copy(), None, None
         codes, scales, zeros = self.quantize(w, bits, scheme)
+        if scheme == ASYM_GROUP:
+            K = w.shape[1]
+            scales, zeros = self.store_scales(scales, K), self.store_scales(zeros, K)
         return self.pack(codes, bits, scheme), scales, zeros
 
     def dequant_weights(self, w, bits, scheme):
@@ -204,6 +220,7 @@ packed_sizes = _forward('packed_sizes')
 quantize = _forward('quantize')
 pack = _forward('pack')
 unpack = _forward('unpack')
+store_scales = _forward('store_scales')
 dequant = _forward('dequant')
 fp16_to_f32 = _forward('fp16_to_f32')
 matmul = _forward('matmul')

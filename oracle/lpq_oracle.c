@@ -29,22 +29,26 @@
  * fp32 arithmetic is IEEE round-to-nearest-even with no fused contraction (build with
  * -ffp-contract=off, no fast-math).  fp16 <-> fp32 conversions are written out below.
  *
- * Storage format of the packed codes (a convention of this project, restated here from its
+ * Storage format of the packed buffers (a convention of this project, restated here from its
  * prose description, not shared with the GPU sources):
- *   W is [N][K], K contiguous; N % 16 == 0, K % 128 == 0.  A tile is 16 rows x 128 columns;
- *   tiles are stored in order nt * (K/128) + kt.  A tile is owned by 64 "lanes",
- *   lane = 16 * kq + r (r = row in tile, kq = 0..3); the lane owns the 32 codes of row r at
- *   tile columns 32*j + 8*kq + e (j = 0..3, e = 0..7), numbered c = 8*j + e.
- *     4-bit: 16 bytes per lane at 16*lane: four LE u32, word j; code e sits at bit
- *            4*(e/2) + 16*(e%2) of word j.
- *     3-bit: 12 bytes per lane at 12*lane: three LE u32.  Pair P = c/2, half h = c%2.
- *            P < 15: word P/5, bits 16*h + 3*(P%5) .. +2.  P == 15: bit t of the code is
- *            bit 16*h + 15 of word t (t = 0, 1, 2).
- *     8-bit: 32 bytes per lane in two 16-byte pieces: piece p (j = 2p, 2p+1) at
- *            1024*p + 16*lane; byte 8*(j%2) + e holds code (j, e).  Signed codes are
- *            two's complement.
+ *   W is [N][K], K contiguous; N % 64 == 0, K % 128 == 0.  A block is 64 rows x 128 columns;
+ *   blocks are stored in order (n/64) * (K/128) + k/128.  A block holds four tiles one after
+ *   the other; tile t holds the 16 rows 64*(n/64) + 4*r + t (r = 0..15), i.e. t = n % 4 and
+ *   r = (n % 64) / 4.  A tile is owned by 64 "lanes", lane = 16 * kq + r (kq = 0..3); the lane
+ *   owns the 32 codes of its row at block columns 32*j + 8*kq + e (j = 0..3, e = 0..7),
+ *   numbered c = 8*j + e.
+ *     4-bit: 1024-byte tile; 16 bytes per lane at 16*lane: four LE u32, word j; code e sits at
+ *            bit 4*(e/2) + 16*(e%2) of word j.
+ *     3-bit: 768-byte tile; 12 bytes per lane at 12*lane: three LE u32.  Pair P = c/2, half
+ *            h = c%2.  P < 15: word P/5, bits 16*h + 3*(P%5) .. +2.  P == 15: bit i of the code
+ *            is bit 16*h + 15 of word i (i = 0, 1, 2).
+ *     8-bit: 2048-byte tile; 32 bytes per lane in two 16-byte pieces: piece p (j = 2p, 2p+1) at
+ *            1024*p + 16*lane; byte 8*(j%2) + e holds code (j, e).  Signed codes are two's
+ *            complement.
  *     16-bit: the packed buffer is the row-major fp16 matrix itself.
- *   scales (and zeros): fp16 [N][K/128] row-major; per-row scheme: scales fp16 [N], no zeros.
+ *   scales (and zeros) as stored: fp16 [K/128][N] (group-major: index g*N + n); per-row
+ *   scheme: scales fp16 [N], no zeros.  lpq_oracle_quantize returns them in the natural
+ *   [N][K/128] order; lpq_oracle_store_scales rearranges them into the stored order.
  */
 #include <math.h>
 #include <stddef.h>
@@ -54,7 +58,7 @@
 #pragma STDC FP_CONTRACT OFF
 
 enum { ORC_FP16 = 0, ORC_ASYM_GROUP = 1, ORC_SYM_CHANNEL = 2 };
-enum { ORC_GROUP = 128, ORC_TROWS = 16 };
+enum { ORC_GROUP = 128, ORC_BLOCK_ROWS = 64 };
 
 /* ---- fp16 <-> fp32, written out ------------------------------------------------------ */
 
@@ -95,7 +99,7 @@ uint16_t lpq_oracle_f2h(float f)
 
 static int check_desc(int bits, int scheme, long K, long N)
 {
-    if (K <= 0 || N <= 0 || K % ORC_GROUP || N % ORC_TROWS) return -1;
+    if (K <= 0 || N <= 0 || K % ORC_GROUP || N % ORC_BLOCK_ROWS) return -1;
     if (scheme == ORC_FP16)        return bits == 16 ? 0 : -1;
     if (scheme == ORC_ASYM_GROUP)  return (bits == 3 || bits == 4 || bits == 8) ? 0 : -1;
     if (scheme == ORC_SYM_CHANNEL) return bits == 8 ? 0 : -1;
@@ -202,25 +206,28 @@ static uint32_t get_bits_le32(const uint8_t *base, int word, int bit, unsigned n
     return v;
 }
 
-/* Tile-local coordinates of code (row r, tile column kk): lane, j, e. */
-static void locate(int r, int kk, int *lane, int *j, int *e)
+/* Where code (n, k) lives: byte offset of its tile, then lane, j, e inside the tile. */
+static size_t locate(long n, long k, long K, int bits, int *lane, int *j, int *e)
 {
+    const long KT = K / ORC_GROUP;
+    const size_t tile_bytes = (size_t)16 * ORC_GROUP * (size_t)bits / 8u;
+    const long block = n / ORC_BLOCK_ROWS, kt = k / ORC_GROUP;
+    const int  t = (int)(n % 4), r = (int)((n % ORC_BLOCK_ROWS) / 4);
+    const int  kk = (int)(k % ORC_GROUP);
     *j = kk / 32;
-    int kq = (kk % 32) / 8;
     *e = kk % 8;
-    *lane = 16 * kq + r;
+    *lane = 16 * ((kk % 32) / 8) + r;
+    return (((size_t)block * (size_t)KT + (size_t)kt) * 4u + (size_t)t) * tile_bytes;
 }
 
 int lpq_oracle_pack(const int32_t *codes, int bits, int scheme, long K, long N, uint8_t *packed)
 {
     if (check_desc(bits, scheme, K, N) || scheme == ORC_FP16) return -1;
-    const long KT = K / ORC_GROUP;
-    const size_t tile_bytes = (size_t)ORC_TROWS * ORC_GROUP * (size_t)bits / 8u;
     memset(packed, 0, (size_t)K * (size_t)N * (size_t)bits / 8u);
     for (long n = 0; n < N; ++n) {
         for (long k = 0; k < K; ++k) {
-            uint8_t *tile = packed + ((size_t)(n / ORC_TROWS) * (size_t)KT + (size_t)(k / ORC_GROUP)) * tile_bytes;
-            int lane, j, e; locate((int)(n % ORC_TROWS), (int)(k % ORC_GROUP), &lane, &j, &e);
+            int lane, j, e;
+            uint8_t *tile = packed + locate(n, k, K, bits, &lane, &j, &e);
             int32_t c = codes[n * K + k];
             if (bits == 4) {
                 if (c < 0 || c > 15) return -2;
@@ -242,12 +249,10 @@ int lpq_oracle_pack(const int32_t *codes, int bits, int scheme, long K, long N, 
 int lpq_oracle_unpack(const uint8_t *packed, int bits, int scheme, long K, long N, int32_t *codes)
 {
     if (check_desc(bits, scheme, K, N) || scheme == ORC_FP16) return -1;
-    const long KT = K / ORC_GROUP;
-    const size_t tile_bytes = (size_t)ORC_TROWS * ORC_GROUP * (size_t)bits / 8u;
     for (long n = 0; n < N; ++n) {
         for (long k = 0; k < K; ++k) {
-            const uint8_t *tile = packed + ((size_t)(n / ORC_TROWS) * (size_t)KT + (size_t)(k / ORC_GROUP)) * tile_bytes;
-            int lane, j, e; locate((int)(n % ORC_TROWS), (int)(k % ORC_GROUP), &lane, &j, &e);
+            int lane, j, e;
+            const uint8_t *tile = packed + locate(n, k, K, bits, &lane, &j, &e);
             int32_t c;
             if (bits == 4) {
                 c = (int32_t)get_bits_le32(tile + 16 * lane, j, 4 * (e / 2) + 16 * (e % 2), 4);
@@ -262,6 +267,16 @@ int lpq_oracle_unpack(const uint8_t *packed, int bits, int scheme, long K, long 
             codes[n * K + k] = c;
         }
     }
+    return 0;
+}
+
+/* Natural [N][K/128] order -> stored [K/128][N] order (grouped scheme only). */
+int lpq_oracle_store_scales(const uint16_t *natural, long K, long N, uint16_t *stored)
+{
+    if (K <= 0 || N <= 0 || K % ORC_GROUP) return -1;
+    const long G = K / ORC_GROUP;
+    for (long n = 0; n < N; ++n)
+        for (long g = 0; g < G; ++g) stored[g * N + n] = natural[n * G + g];
     return 0;
 }
 

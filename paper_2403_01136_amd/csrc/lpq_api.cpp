@@ -32,7 +32,7 @@ lpq_status check_desc(const lpq_qdesc* d)
     if (d->scheme != LPQ_FP16 && d->scheme != LPQ_ASYM_GROUP && d->scheme != LPQ_SYM_CHANNEL) return LPQ_ERR_SCHEME;
     if (variant_of(*d) < 0) return LPQ_ERR_SCHEME;
     if (d->scheme == LPQ_ASYM_GROUP ? d->group_size != 128 : (d->group_size != 0 && d->group_size != 128)) return LPQ_ERR_SCHEME;
-    if (d->K <= 0 || d->N <= 0 || d->K % 128 != 0 || d->N % 16 != 0) return LPQ_ERR_SHAPE;
+    if (d->K <= 0 || d->N <= 0 || d->K % 128 != 0 || d->N % 64 != 0) return LPQ_ERR_SHAPE;
     return LPQ_OK;
 }
 
@@ -134,16 +134,17 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
             L.K = w.d.K;
             L.N = w.d.N;
             L.variant = variant_of(w.d);
-            const int rows = decode_rows_per_unit(L.variant);
+            const int rows = decode_rows_per_wave(L.variant);
             const int KT = L.K / 128;
-            const size_t step_bytes = (size_t)rows * 128 * (size_t)w.d.bits / 8;      // one unit, one 128-column tile
+            const size_t step_bytes = (size_t)rows * 128 * (size_t)w.d.bits / 8;      // one wave, one 128-column step
             const int kt_target = (int)std::max<size_t>(1, decode_unit_bytes() / step_bytes);
             int ksplit = std::max(1, (KT + kt_target / 2) / kt_target);
             L.kt_per_split = (KT + ksplit - 1) / ksplit;
             L.ksplit = (KT + L.kt_per_split - 1) / L.kt_per_split;
-            L.row_groups = (L.N + rows - 1) / rows;
+            L.row_blocks = L.N / rows;
+            L.row_superblocks = (L.row_blocks + 3) / 4;
             L.unit_begin = units;
-            units += L.row_groups * L.ksplit;
+            units += L.row_superblocks * L.ksplit;
             L.red_begin = red_blocks[li];
             if (L.ksplit > 1) {
                 partial_off[li].push_back(ws_floats);
@@ -263,7 +264,7 @@ const char* lpq_status_str(lpq_status status)
     case LPQ_ERR_NULL: return "null pointer";
     case LPQ_ERR_BITS: return "bits must be 3, 4, 8 or 16";
     case LPQ_ERR_SCHEME: return "bits / scheme / group_size do not match";
-    case LPQ_ERR_SHAPE: return "bad shape (K % 128, N % 16, M >= 1, descriptor mismatch)";
+    case LPQ_ERR_SHAPE: return "bad shape (K % 128, N % 64, M >= 1, descriptor mismatch)";
     case LPQ_ERR_ALIGN: return "pointer not 16-byte aligned";
     case LPQ_ERR_BUFSIZE: return "workspace allocation failed";
     case LPQ_ERR_DEVICE: return "HIP call failed";

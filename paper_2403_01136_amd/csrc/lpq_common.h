@@ -19,20 +19,21 @@ struct LinDesc {
     int32_t variant;        // V_W3 .. V_F16
     int32_t ksplit;         // number of K ranges
     int32_t kt_per_split;   // 128-column tiles per K range
-    int32_t row_groups;     // ceil(N / rows per unit)
-    int32_t unit_begin;     // first work unit of this linear in the launch
+    int32_t row_blocks;     // N / rows per wave (64; 32 for fp16 weights)
+    int32_t row_superblocks;// ceil(row_blocks / 4): one workgroup each
+    int32_t unit_begin;     // first work unit (workgroup) of this linear in the launch
     int32_t red_begin;      // first reduction block of this linear (split-K only)
 };
 
-enum { MAX_LIN_PER_LAUNCH = 44 };   // keeps DecodeArgs under the 4 KB kernel-argument limit
+enum { MAX_LIN_PER_LAUNCH = 42 };   // keeps DecodeArgs under the 4 KB kernel-argument limit
 
 struct DecodeArgs {
     int32_t n_lin, M, m0, total_units;   // m0: first token row of this pass (M > 64 is run 64 rows at a time)
     LinDesc lin[MAX_LIN_PER_LAUNCH];
 };
 
-// rows of W one decode work unit covers, per variant (16-bit tiles are 4 KB, so fewer rows)
-__host__ __device__ inline int decode_rows_per_unit(int variant) { return variant == 4 ? 32 : 64; }
+// rows of W one decode wavefront covers, per variant (fp16 rows are 4x-16x bigger, so fewer of them)
+__host__ __device__ inline int decode_rows_per_wave(int variant) { return variant == 4 ? 32 : 64; }
 
 int variant_of(const lpq_qdesc& d);           // -1 if the (bits, scheme) pair is not supported
 size_t tile_bytes_of(int variant);

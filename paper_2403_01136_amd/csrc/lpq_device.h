@@ -21,7 +21,7 @@ typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 enum { SCH_FP16 = 0, SCH_ASYM = 1, SCH_SYM = 2 };
-enum { GROUP = 128, TILE_ROWS = 16 };
+enum { GROUP = 128, TILE_ROWS = 16, BLOCK_ROWS = 64 };
 
 // kernel-variant ids: one per (bits, scheme) the library supports
 enum { V_W3 = 0, V_W4 = 1, V_W8 = 2, V_I8 = 3, V_F16 = 4, V_COUNT = 5 };
@@ -46,27 +46,33 @@ template <> struct WRaw<V_W8>  { u32x4 q[2]; };
 template <> struct WRaw<V_I8>  { u32x4 q[2]; };
 template <> struct WRaw<V_F16> { u32x4 q[4]; };
 
-// codes: base of the packed buffer; tile = nt * KT + kt.  For fp16, `codes` is the row-major
-// matrix and the lane reads its four 16-byte pieces of row (16*nt + r).
+// codes: base of the packed buffer.  A 64-row x 128-column block (rb, kt) holds four tiles back
+// to back; tile t has rows 64*rb + 4*r + t.  One wave that owns the block reads 4 * TILE_BYTES
+// contiguous bytes per 128-column step, and consecutive steps are contiguous too.
 template <int V>
-__device__ __forceinline__ WRaw<V> load_tile(const uint8_t* __restrict__ codes, long nt, int KT, int kt, int lane)
+__device__ __forceinline__ WRaw<V> load_tile(const uint8_t* __restrict__ codes, long rb, int KT, int kt, int t, int lane)
 {
+    static_assert(V != V_F16, "fp16 weights are row-major, see load_rows_f16");
     WRaw<V> w;
+    const uint8_t* tile = codes + (((size_t)rb * KT + kt) * 4 + t) * (size_t)VInfo<V>::TILE_BYTES;
     if constexpr (V == V_W3) {
-        const uint32_t* p = reinterpret_cast<const uint32_t*>(codes + ((size_t)nt * KT + kt) * 768 + 12 * lane);
-        w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x3*>(p));
+        w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x3*>(tile + 12 * lane));
     } else if constexpr (V == V_W4) {
-        w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(codes + ((size_t)nt * KT + kt) * 1024 + 16 * lane));
-    } else if constexpr (V == V_W8 || V == V_I8) {
-        const uint8_t* p = codes + ((size_t)nt * KT + kt) * 2048 + 16 * lane;
-        w.q[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-        w.q[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 1024));
+        w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 16 * lane));
     } else {
-        const int r = lane & 15, kq = lane >> 4;
-        const uint8_t* p = codes + (((size_t)nt * 16 + r) * (size_t)KT * 128 + (size_t)kt * 128 + 8 * kq) * 2;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w.q[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 64 * j));
+        w.q[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 16 * lane));
+        w.q[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 1024 + 16 * lane));
     }
+    return w;
+}
+
+// fp16 weights (row-major [N][K]): the lane's four 16-byte pieces of row n in 128-column step kt
+__device__ __forceinline__ WRaw<V_F16> load_rows_f16(const uint8_t* __restrict__ w16, long n, int K, int kt, int lane)
+{
+    WRaw<V_F16> w;
+    const uint8_t* p = w16 + ((size_t)n * (size_t)K + (size_t)kt * 128 + 8 * (lane >> 4)) * 2;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w.q[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 64 * j));
     return w;
 }
 

@@ -4,9 +4,10 @@
 // with q = min; Sec. 4.2: symmetric scaling factor max|w| / (2^(b-1) - 1) for the per-row
 // scheme; Sec. 4.1: dense packing, bit/8 bytes per weight.
 //
-// One wavefront quantises one 16x128 tile.  Lane (r = lane%16, kq = lane/16) reads exactly the
-// 32 weights it owns in the packed format (four 16-byte pieces of row r), so min/max need one
-// exchange across the four kq lanes of a row and the packing itself is lane-local.
+// One wavefront quantises one 16x128 tile (tile t of a 64-row block holds rows 4*r + t).  Lane
+// (r = lane%16, kq = lane/16) reads exactly the 32 weights it owns in the packed format (four
+// 16-byte pieces of its row), so min/max need one exchange across the four kq lanes of a row and
+// the packing itself is lane-local.  The four waves of a workgroup take the four tiles of a block.
 // All fp32 steps use the round-to-nearest intrinsics so the compiler can neither fuse nor
 // reassociate them: the results are bit-exact functions of the input.
 #include "lpq_common.h"
@@ -19,11 +20,11 @@ namespace {
 __device__ __forceinline__ uint16_t f2h_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 __device__ __forceinline__ float h2f_bits(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
 
-// the lane's 32 weights of tile (nt, kt): v[8*j + e] = W[16*nt + r][128*kt + 32*j + 8*kq + e]
-__device__ __forceinline__ void load_owned(const uint16_t* __restrict__ w, long K, long nt, int kt, int lane, float v[32])
+// the lane's 32 weights of its row n in 128-column step kt: v[8*j + e] = W[n][128*kt + 32*j + 8*kq + e]
+__device__ __forceinline__ void load_owned(const uint16_t* __restrict__ w, long K, long n, int kt, int lane, float v[32])
 {
-    const int r = lane & 15, kq = lane >> 4;
-    const uint16_t* p = w + (nt * 16 + r) * K + (long)kt * 128 + 8 * kq;
+    const int kq = lane >> 4;
+    const uint16_t* p = w + n * K + (long)kt * 128 + 8 * kq;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const h8 t = *reinterpret_cast<const h8*>(p + 32 * j);
@@ -82,13 +83,14 @@ __global__ __launch_bounds__(256) void quantize_asym_kernel(const uint16_t* __re
                                                             uint16_t* __restrict__ zeros)
 {
     const int KT = K / 128;
-    const long tile = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long tile = (long)blockIdx.x * 4 + (threadIdx.x >> 6);      // ((rb * KT + kt) * 4 + t)
     if (tile >= NT * KT) return;
-    const int lane = threadIdx.x & 63;
-    const long nt = tile / KT;
-    const int kt = (int)(tile % KT);
+    const int lane = threadIdx.x & 63, t = (int)(tile & 3);
+    const long rb = (tile >> 2) / KT;
+    const int kt = (int)((tile >> 2) % KT);
+    const long n = rb * 64 + 4 * (lane & 15) + t;
     float v[32];
-    load_owned(w, K, nt, kt, lane, v);
+    load_owned(w, K, n, kt, lane, v);
     float lo = v[0], hi = v[0];
 #pragma unroll
     for (int i = 1; i < 32; ++i) { lo = fminf(lo, v[i]); hi = fmaxf(hi, v[i]); }
@@ -108,10 +110,10 @@ __global__ __launch_bounds__(256) void quantize_asym_kernel(const uint16_t* __re
         c[i] = (int)fminf(fmaxf(r, 0.0f), (float)QMAX);
     }
     store_packed<BITS, false>(codes, tile, lane, c);
-    if (lane < 16) {
-        const long n = nt * 16 + lane;
-        scales[n * KT + kt] = sh;
-        zeros[n * KT + kt] = zh;
+    if (lane < 16) {                                   // stored group-major: [K/128][N]
+        const long N = NT * 16;
+        scales[(long)kt * N + n] = sh;
+        zeros[(long)kt * N + n] = zh;
     }
 }
 
@@ -146,12 +148,13 @@ __global__ __launch_bounds__(256) void quantize_sym_kernel(const uint16_t* __res
     const int KT = K / 128;
     const long tile = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (tile >= NT * KT) return;
-    const int lane = threadIdx.x & 63;
-    const long nt = tile / KT;
-    const int kt = (int)(tile % KT);
+    const int lane = threadIdx.x & 63, t = (int)(tile & 3);
+    const long rb = (tile >> 2) / KT;
+    const int kt = (int)((tile >> 2) % KT);
+    const long n = rb * 64 + 4 * (lane & 15) + t;
     float v[32];
-    load_owned(w, K, nt, kt, lane, v);
-    const float sf = h2f_bits(scales[nt * 16 + (lane & 15)]);
+    load_owned(w, K, n, kt, lane, v);
+    const float sf = h2f_bits(scales[n]);
     int c[32];
 #pragma unroll
     for (int i = 0; i < 32; ++i) {
@@ -188,10 +191,11 @@ __global__ __launch_bounds__(256) void unpack_dequant_kernel(const uint8_t* __re
     const int KT = K / 128;
     const long tile = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (tile >= NT * KT) return;
-    const int lane = threadIdx.x & 63, r = lane & 15, kq = lane >> 4;
-    const long nt = tile / KT;
-    const int kt = (int)(tile % KT);
-    const long n = nt * 16 + r;
+    const int lane = threadIdx.x & 63, r = lane & 15, kq = lane >> 4, t = (int)(tile & 3);
+    const long rb = (tile >> 2) / KT;
+    const int kt = (int)((tile >> 2) % KT);
+    const long n = rb * 64 + 4 * r + t;
+    const long N = NT * 16;
     float* o = out + n * K + (long)kt * 128 + 8 * kq;
     if (variant == V_F16) {
         const uint16_t* p = reinterpret_cast<const uint16_t*>(codes) + n * K + (long)kt * 128 + 8 * kq;
@@ -200,13 +204,13 @@ __global__ __launch_bounds__(256) void unpack_dequant_kernel(const uint8_t* __re
         return;
     }
     const size_t tb = variant == V_W3 ? 768 : (variant == V_W4 ? 1024 : 2048);
-    const uint8_t* t = codes + (size_t)tile * tb;
+    const uint8_t* tp = codes + (size_t)tile * tb;
     float s, z;
     if (variant == V_I8) { s = h2f_bits(scales[n]); z = 0.0f; }
-    else { s = h2f_bits(scales[n * KT + kt]); z = h2f_bits(zeros[n * KT + kt]); }
+    else { s = h2f_bits(scales[(long)kt * N + n]); z = h2f_bits(zeros[(long)kt * N + n]); }
     for (int j = 0; j < 4; ++j)
         for (int e = 0; e < 8; ++e) {
-            const float c = (float)extract_code(t, variant, lane, j, e);
+            const float c = (float)extract_code(tp, variant, lane, j, e);
             o[32 * j + e] = __fadd_rn(__fmul_rn(s, c), z);
         }
 }

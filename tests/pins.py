@@ -68,52 +68,48 @@ def pin_fp16_conversions(orc):
 # format's prose description that uses none of the oracle's word arithmetic.
 # ---------------------------------------------------------------------------------------
 
-def spec_bit_positions(bits, r, kk):
-    """Absolute bit positions (LSB first) inside one tile's byte string of the code of
-    tile row r, tile column kk -- read off the format description, one bit at a time."""
+def spec_bit_positions(bits, n, k, K):
+    """Absolute bit positions (LSB first) inside the packed byte string of the code of weight
+    (row n, column k) -- read off the format description, one bit at a time."""
+    KT = K // 128
+    tile_bytes = 16 * 128 * bits // 8
+    block, t, r = n // 64, n % 4, (n % 64) // 4          # tile t of a 64-row block holds rows 4r + t
+    kt, kk = k // 128, k % 128
     j, kq, e = kk // 32, (kk % 32) // 8, kk % 8
     lane = 16 * kq + r
+    tile_bit0 = 8 * tile_bytes * ((block * KT + kt) * 4 + t)
     if bits == 4:
-        base = 8 * 16 * lane + 32 * j
-        start = 4 * (e // 2) + 16 * (e % 2)
-        return [base + start + i for i in range(4)]
+        start = 8 * 16 * lane + 32 * j + 4 * (e // 2) + 16 * (e % 2)
+        return [tile_bit0 + start + i for i in range(4)]
     if bits == 3:
         c = 8 * j + e
         P, h = c // 2, c % 2
-        base = 8 * 12 * lane
+        base = tile_bit0 + 8 * 12 * lane
         if P < 15:
             return [base + 32 * (P // 5) + 16 * h + 3 * (P % 5) + i for i in range(3)]
-        return [base + 32 * t + 16 * h + 15 for t in range(3)]
+        return [base + 32 * i + 16 * h + 15 for i in range(3)]
     if bits == 8:
         byte = 1024 * (j // 2) + 16 * lane + 8 * (j % 2) + e
-        return [8 * byte + i for i in range(8)]
+        return [tile_bit0 + 8 * byte + i for i in range(8)]
     raise ValueError(bits)
 
 
 def spec_pack(codes, bits):
     """Pack int codes [N][K] by setting single bits at spec_bit_positions (slow, tiny inputs)."""
     N, K = codes.shape
-    KT = K // 128
-    tile_bytes = 16 * 128 * bits // 8
     out = np.zeros(N * K * bits // 8, dtype=np.uint8)
     for n in range(N):
         for k in range(K):
-            tile = (n // 16) * KT + k // 128
             c = int(codes[n, k]) & ((1 << bits) - 1)
-            for i, pos in enumerate(spec_bit_positions(bits, n % 16, k % 128)):
+            for i, p in enumerate(spec_bit_positions(bits, n, k, K)):
                 if (c >> i) & 1:
-                    p = 8 * tile_bytes * tile + pos
                     out[p // 8] |= 1 << (p % 8)
     return out
 
 
 def spec_unpack_one(packed, bits, K, n, k, signed=False):
-    KT = K // 128
-    tile_bytes = 16 * 128 * bits // 8
-    tile = (n // 16) * KT + k // 128
     c = 0
-    for i, pos in enumerate(spec_bit_positions(bits, n % 16, k % 128)):
-        p = 8 * tile_bytes * tile + pos
+    for i, p in enumerate(spec_bit_positions(bits, n, k, K)):
         c |= ((int(packed[p // 8]) >> (p % 8)) & 1) << i
     if signed and c >= 128:
         c -= 256
@@ -123,7 +119,7 @@ def spec_unpack_one(packed, bits, K, n, k, signed=False):
 def pin_pack_density_and_roundtrip(orc):
     rng = np.random.default_rng(11)
     for bits, scheme in ((3, ASYM), (4, ASYM), (8, ASYM), (8, SYM)):
-        for (N, K) in ((16, 128), (48, 384)):
+        for (N, K) in ((64, 128), (192, 384)):
             cb, sb, zb = orc.packed_sizes(bits, scheme, K, N)
             assert cb * 8 == K * N * bits                       # Sec. 4.1: bit/8 bytes per weight
             assert sb == (N * (K // 128) * 2 if scheme == ASYM else N * 2)
@@ -136,34 +132,51 @@ def pin_pack_density_and_roundtrip(orc):
                 p = orc.pack(codes, bits, scheme)
                 assert p.dtype == np.uint8 and p.size == cb
                 assert np.array_equal(orc.unpack(p, bits, scheme, K, N), codes)
-    cb, sb, zb = orc.packed_sizes(16, FP16, 256, 32)
-    assert (cb, sb, zb) == (256 * 32 * 2, 0, 0)
+    cb, sb, zb = orc.packed_sizes(16, FP16, 256, 64)
+    assert (cb, sb, zb) == (256 * 64 * 2, 0, 0)
+    for bad_n in (16, 32, 96):
+        try:
+            orc.packed_sizes(4, ASYM, 128, bad_n)
+        except ValueError:
+            continue
+        raise AssertionError("N must be a multiple of 64")
 
 
 def pin_pack_matches_format_description(orc):
     rng = np.random.default_rng(12)
-    N, K = 32, 256
+    N, K = 128, 256
     for bits, scheme in ((3, ASYM), (4, ASYM), (8, ASYM), (8, SYM)):
         lo, hi = (0, (1 << bits) - 1) if scheme == ASYM else (-127, 127)
         codes = rng.integers(lo, hi + 1, (N, K)).astype(np.int32)
         assert np.array_equal(orc.pack(codes, bits, scheme), spec_pack(codes, bits))
-        # every bit of the packed tile is used exactly once (dense, no overlap)
-        seen = np.zeros(16 * 128 * bits, dtype=np.int32)
-        for r in range(16):
-            for kk in range(128):
-                for pos in spec_bit_positions(bits, r, kk):
+        # every bit of the packed buffer is used exactly once (dense, no overlap)
+        seen = np.zeros(N * K * bits, dtype=np.int32)
+        for n in range(N):
+            for k in range(K):
+                for pos in spec_bit_positions(bits, n, k, K):
                     seen[pos] += 1
         assert np.all(seen == 1)
     # one-hot probes: a single code set to all-ones lights exactly its own bits
     for bits in (3, 4, 8):
-        for (n, k) in ((0, 0), (5, 31), (15, 127), (17, 130), (31, 255), (9, 94), (9, 95)):
+        for (n, k) in ((0, 0), (5, 31), (63, 127), (65, 130), (127, 255), (9, 94), (9, 95), (70, 7)):
             codes = np.zeros((N, K), np.int32)
             codes[n, k] = (1 << bits) - 1
             p = orc.pack(codes, bits, ASYM)
             on = np.flatnonzero(np.unpackbits(p, bitorder="little"))
-            tile = (n // 16) * (K // 128) + k // 128
-            want = sorted(8 * (16 * 128 * bits // 8) * tile + q for q in spec_bit_positions(bits, n % 16, k % 128))
-            assert list(on) == want
+            assert list(on) == sorted(spec_bit_positions(bits, n, k, K))
+    # stored order of scales and zeros: group-major, index g * N + n
+    nat = rng.integers(0, 65535, (N, K // 128)).astype(np.uint16)
+    st = orc.store_scales(nat, K)
+    assert st.shape == (K // 128, N)
+    for n in (0, 1, 63, 64, 127):
+        for g in range(K // 128):
+            assert st.reshape(-1)[g * N + n] == nat[n, g]
+    w = synth_w(N, K, 13)
+    packed, s_st, z_st = orc.quantize_pack(w, 4, ASYM)
+    codes, s_nat, z_nat = orc.quantize(w, 4, ASYM)
+    assert np.array_equal(s_st, s_nat.T) and np.array_equal(z_st, z_nat.T) and np.array_equal(packed, orc.pack(codes, 4, ASYM))
+    _, s_row, z_row = orc.quantize_pack(w, 8, SYM)
+    assert s_row.shape == (N,) and z_row is None
 
 
 # ---------------------------------------------------------------------------------------
@@ -178,10 +191,10 @@ def pin_exact_grid_examples(orc, golden_lines=None):
                 continue                     # keep every grid value exactly representable in fp16
             idx = (np.arange(128) * 5 + 3) % (q + 1)
             idx[7], idx[100] = 0, q          # both ends present
-            w = np.tile(f16(lo + idx * step), (16, 1))
+            w = np.tile(f16(lo + idx * step), (64, 1))
             assert np.array_equal(w[0].astype(np.float64), lo + idx * step)
             codes, s, z = orc.quantize(w, bits, ASYM)
-            assert np.array_equal(codes, np.tile(idx, (16, 1)))
+            assert np.array_equal(codes, np.tile(idx, (64, 1)))
             assert np.all(as_f16(s) == np.float16(step)) and np.all(as_f16(z) == np.float16(lo))
             d = orc.dequant(codes, s, z, bits, ASYM)
             assert np.array_equal(d.astype(np.float64), w.astype(np.float64))
@@ -194,7 +207,7 @@ def pin_exact_grid_examples(orc, golden_lines=None):
             want = np.array([int(t) for t in codes.split()])
             scale, zero = [float(t) for t in sz.split()]
             reps = 128 // len(vals)
-            w = np.tile(f16(np.tile(vals, reps)), (16, 1))
+            w = np.tile(f16(np.tile(vals, reps)), (64, 1))
             c, s, z = orc.quantize(w, bits, ASYM)
             assert np.array_equal(c[3], np.tile(want, reps))
             assert float(as_f16(s)[3, 0]) == scale and float(as_f16(z)[3, 0]) == zero
@@ -208,8 +221,9 @@ def pin_rtn_against_exact_arithmetic(orc):
     """Scale, zero and codes against Fractions: scale is the fp16 nearest to
     (max-min)/(2^b-1), zero is the minimum, each code is a nearest integer of
     (w-zero)/scale (Sec. 2.4), dequant is scale*code+zero to fp32 accuracy."""
-    N, K = 16, 256
+    N, K = 64, 256
     w = synth_w(N, K, 21)
+    check_rows = (0, 1, 2, 3, 17, 42, 63)
     wf = w.astype(np.float64)
     for bits in ASYM_BITS:
         q = (1 << bits) - 1
@@ -217,7 +231,7 @@ def pin_rtn_against_exact_arithmetic(orc):
         sf, zf = as_f16(s).astype(np.float64), as_f16(z).astype(np.float64)
         deq = orc.dequant(codes, s, z, bits, ASYM).astype(np.float64)
         assert codes.min() >= 0 and codes.max() <= q
-        for n in range(N):
+        for n in check_rows:
             for g in range(K // 128):
                 grp = wf[n, 128 * g:128 * g + 128]
                 lo, hi = grp.min(), grp.max()
@@ -268,7 +282,7 @@ def pin_error_bound_half_scale(orc):
 
 def pin_degenerate_groups(orc):
     """Flat groups (max == min): scale 1, codes 0, dequant exact; -0 and +0 give zero +0."""
-    w = np.zeros((16, 384), np.float16)
+    w = np.zeros((64, 384), np.float16)
     w[:, 128:256] = np.float16(0.37)
     w[:, 256:] = np.float16(-0.0)
     w[3, 256] = np.float16(0.0)
@@ -278,16 +292,16 @@ def pin_degenerate_groups(orc):
         assert np.all(z[:, 0] == 0) and np.all(as_f16(z)[:, 1] == np.float16(0.37)) and np.all(z[:, 2] == 0)
         d = orc.dequant(codes, s, z, bits, ASYM)
         assert np.array_equal(d, w.astype(np.float32))
-    codes, s, _ = orc.quantize(np.zeros((16, 128), np.float16), 8, SYM)
+    codes, s, _ = orc.quantize(np.zeros((64, 128), np.float16), 8, SYM)
     assert np.all(codes == 0) and np.all(s == 0x3C00)
     # tiny range whose scale underflows fp16 entirely -> treated as flat
-    w = np.zeros((16, 128), np.float16)
+    w = np.zeros((64, 128), np.float16)
     w[:, 5] = np.float16(2.0 ** -24)
     codes, s, z = orc.quantize(w, 8, ASYM)          # 2^-24/255 rounds to 0 in fp16
     assert np.all(s == 0x3C00) and np.all(codes == 0)
     # range so small that the fp16 scale is a subnormal rounded down: (w - zero) / scale
     # overshoots 2^b - 1 and the code must be clamped to the top of the range
-    w = np.zeros((16, 128), np.float16)
+    w = np.zeros((64, 128), np.float16)
     w[:, 9] = as_f16(np.uint16(9))                  # 9 * 2^-24
     codes, s, z = orc.quantize(w, 3, ASYM)          # 9/7 * 2^-24 -> fp16 subnormal 1 * 2^-24
     assert np.all(s == 1) and np.all(codes[:, 9] == 7) and codes.max() == 7 and codes.min() == 0
@@ -296,7 +310,7 @@ def pin_degenerate_groups(orc):
 def pin_scale_invariance(orc):
     """P8: multiplying the weights by 2^k leaves the codes unchanged and multiplies scale
     and zero by 2^k exactly (all formulas are homogeneous; rounding is scale-free)."""
-    w = synth_w(32, 256, 41, outliers=False)
+    w = synth_w(64, 256, 41, outliers=False)
     for bits, scheme in ((3, ASYM), (4, ASYM), (8, ASYM), (8, SYM)):
         c0, s0, z0 = orc.quantize(w, bits, scheme)
         for k in (1, 3, 5, 9):
@@ -312,27 +326,27 @@ def pin_scale_invariance(orc):
 def pin_groups_and_rows_are_independent(orc):
     """Granularity: one (row, 128-column) group for the grouped scheme, one row for the per-row
     scheme.  Changing one group / row must not change any other group's / row's result."""
-    w = synth_w(32, 384, 51)
+    w = synth_w(128, 384, 51)
     for bits in ASYM_BITS:
         c0, s0, z0 = orc.quantize(w, bits, ASYM)
         w2 = w.copy()
         w2[7, 128:256] = (w2[7, 128:256].astype(np.float32) * 3 + 0.1).astype(np.float16)
         c, s, z = orc.quantize(w2, bits, ASYM)
-        keep = np.ones((32, 384), bool)
+        keep = np.ones((128, 384), bool)
         keep[7, 128:256] = False
         assert np.array_equal(c[keep], c0[keep])
-        gk = np.ones((32, 3), bool)
+        gk = np.ones((128, 3), bool)
         gk[7, 1] = False
         assert np.array_equal(s[gk], s0[gk]) and np.array_equal(z[gk], z0[gk])
         assert not np.array_equal(s[7, 1], s0[7, 1])
         # shifting the group boundary matters: the statistics really are per 128 columns
-        sub = orc.quantize(np.ascontiguousarray(w[:16, 128:256]), bits, ASYM)
-        assert np.array_equal(sub[0], c0[:16, 128:256]) and np.array_equal(sub[1][:, 0], s0[:16, 1])
+        sub = orc.quantize(np.ascontiguousarray(w[:64, 128:256]), bits, ASYM)
+        assert np.array_equal(sub[0], c0[:64, 128:256]) and np.array_equal(sub[1][:, 0], s0[:64, 1])
     c0, s0, _ = orc.quantize(w, 8, SYM)
     w2 = w.copy()
     w2[9] = (w2[9].astype(np.float32) * 2.5).astype(np.float16)
     c, s, _ = orc.quantize(w2, 8, SYM)
-    keep = np.arange(32) != 9
+    keep = np.arange(128) != 9
     assert np.array_equal(c[keep], c0[keep]) and np.array_equal(s[keep], s0[keep]) and s[9] != s0[9]
 
 
@@ -342,7 +356,7 @@ def pin_groups_and_rows_are_independent(orc):
 
 def pin_fp16_path_is_plain_matmul(orc):
     rng = np.random.default_rng(61)
-    for (M, K, N) in ((1, 128, 16), (5, 256, 48), (17, 384, 32)):
+    for (M, K, N) in ((1, 128, 64), (5, 256, 192), (17, 384, 128)):
         w = synth_w(N, K, 62 + M)
         x = rng.standard_normal((M, K)).astype(np.float16)
         want = x.astype(np.float64) @ w.astype(np.float64).T
@@ -355,7 +369,7 @@ def pin_fp16_path_is_plain_matmul(orc):
         gotb = orc.matmul(x, orc.fp16_to_f32(w), bias)
         assert np.allclose(gotb, want + bias.astype(np.float64)[None, :], rtol=1e-12, atol=1e-12)
     # a non-symmetric probe that a transposed operand or swapped index cannot survive
-    M, K, N = 3, 128, 16
+    M, K, N = 3, 128, 64
     x = np.zeros((M, K), np.float16)
     w = np.zeros((N, K), np.float16)
     x[2, 5] = 2.0
@@ -370,7 +384,7 @@ def pin_fp16_path_is_plain_matmul(orc):
 
 def pin_brute_force_tiny(orc):
     rng = np.random.default_rng(71)
-    for (M, K, N) in ((1, 128, 16), (3, 256, 16), (5, 128, 32)):
+    for (M, K, N) in ((1, 128, 64), (3, 256, 64), (5, 128, 128)):
         w = synth_w(N, K, 72 + M + K)
         x = rng.standard_normal((M, K)).astype(np.float16)
         for bits, scheme in ((3, ASYM), (4, ASYM), (8, ASYM), (8, SYM)):
@@ -384,7 +398,8 @@ def pin_brute_force_tiny(orc):
                 for k in range(K):
                     c = spec_unpack_one(packed, bits, K, n, k, signed=(scheme == SYM))
                     if scheme == ASYM:
-                        wt[k] = sf[n, k // 128] * c + zf[n, k // 128]
+                        g = k // 128          # stored order of scales and zeros: g * N + n
+                        wt[k] = sf.reshape(-1)[g * N + n] * c + zf.reshape(-1)[g * N + n]
                     else:
                         wt[k] = sf[n] * c
                 for m in range(M):
@@ -400,7 +415,7 @@ def pin_brute_force_tiny(orc):
 
 def pin_output_error_bound(orc):
     rng = np.random.default_rng(81)
-    M, K, N = 4, 512, 32
+    M, K, N = 4, 512, 64
     w = synth_w(N, K, 82)
     x = rng.standard_normal((M, K)).astype(np.float16)
     x[:, [3, 200]] *= np.float16(30)
@@ -427,7 +442,7 @@ def pin_matmul_linearity_and_freivalds(orc):
     """O5 by properties: linear in x, and the random-projection identity
     sum_n y[m,n] r[n] == x[m,:] . (W~^T r) computed with numpy in float64 (P9)."""
     rng = np.random.default_rng(91)
-    M, K, N = 6, 384, 48
+    M, K, N = 6, 384, 64
     w = synth_w(N, K, 92)
     x = rng.standard_normal((M, K)).astype(np.float16)
     for bits, scheme in ((4, ASYM), (3, ASYM), (8, SYM)):

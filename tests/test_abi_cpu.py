@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 def test_packed_sizes_are_dense():
     # Sec. 4.1: bytes = weights * bit / 8; scale and zero are fp16 per (row, 128 columns)
     for bits, scheme in ((3, 1), (4, 1), (8, 1), (8, 2), (16, 0)):
-        for K, N in ((128, 16), (5120, 15360), (57344, 14336)):
+        for K, N in ((128, 64), (5120, 15360), (57344, 14336)):
             c, s, z = lpq.lpq_packed_sizes(bits, scheme, K, N)
             assert c * 8 == K * N * bits
             assert s == (N * (K // 128) * 2 if scheme == 1 else (N * 2 if scheme == 2 else 0))
@@ -36,8 +36,8 @@ def test_packed_sizes_are_dense():
 
 
 @pytest.mark.parametrize("bits,scheme,K,N,status", [
-    (5, 1, 128, 16, 2), (2, 1, 128, 16, 2), (4, 7, 128, 16, 3), (16, 1, 128, 16, 3), (3, 2, 128, 16, 3), (4, 0, 128, 16, 3),
-    (4, 1, 100, 16, 4), (4, 1, 128, 24, 4), (4, 1, 0, 16, 4), (4, 1, 128, -16, 4),
+    (5, 1, 128, 64, 2), (2, 1, 128, 64, 2), (4, 7, 128, 64, 3), (16, 1, 128, 64, 3), (3, 2, 128, 64, 3), (4, 0, 128, 64, 3),
+    (4, 1, 100, 64, 4), (4, 1, 128, 16, 4), (4, 1, 128, 96, 4), (4, 1, 0, 64, 4), (4, 1, 128, -64, 4),
 ])
 def test_bad_descriptors(bits, scheme, K, N, status):
     with pytest.raises(lpq.LpqError) as e:
@@ -48,16 +48,16 @@ def test_bad_descriptors(bits, scheme, K, N, status):
 def test_group_size_must_be_128_for_grouped_scheme():
     lib = lpq.load_library()
     c = ctypes.c_size_t()
-    d = lpq.lpq_qdesc(4, 1, 64, 128, 16)
+    d = lpq.lpq_qdesc(4, 1, 64, 128, 64)
     assert lib.lpq_packed_sizes(ctypes.byref(d), ctypes.byref(c), ctypes.byref(c), ctypes.byref(c)) == 3
     assert lib.lpq_packed_sizes(None, ctypes.byref(c), ctypes.byref(c), ctypes.byref(c)) == 1
-    d = lpq.lpq_qdesc(4, 1, 128, 128, 16)
+    d = lpq.lpq_qdesc(4, 1, 128, 128, 64)
     assert lib.lpq_packed_sizes(ctypes.byref(d), None, ctypes.byref(c), ctypes.byref(c)) == 1
 
 
 def test_entry_points_validate_before_touching_the_device():
     lib = lpq.load_library()
-    d = lpq.make_desc(4, 1, 128, 16)
+    d = lpq.make_desc(4, 1, 128, 64)
     fake = 0x10000          # never dereferenced: every call below must fail validation first
     good = lpq.lpq_qweight(d, fake, fake, fake, None)
     # NULL pointers
@@ -77,10 +77,10 @@ def test_entry_points_validate_before_touching_the_device():
     assert lib.lpq_qlinear_prefill(ctypes.byref(odd), fake, 1, fake, None) == 5
     assert lib.lpq_quantize_pack(fake + 4, ctypes.byref(d), ctypes.byref(good), None) == 5
     # descriptor mismatch between desc and out
-    d2 = lpq.make_desc(3, 1, 128, 16)
+    d2 = lpq.make_desc(3, 1, 128, 64)
     assert lib.lpq_quantize_pack(fake, ctypes.byref(d2), ctypes.byref(good), None) == 4
     # bad bits inside a weight
-    bad = lpq.lpq_qweight(lpq.lpq_qdesc(5, 1, 128, 128, 16), fake, fake, fake, None)
+    bad = lpq.lpq_qweight(lpq.lpq_qdesc(5, 1, 128, 128, 64), fake, fake, fake, None)
     assert lib.lpq_qlinear_decode(ctypes.byref(bad), fake, 1, fake, None) == 2
     # stage: bad layer count, bad phase, one bad layer rejects the whole call
     layers = (lpq.lpq_layer * 1)()

@@ -2,8 +2,7 @@
 
 Bit-exact for codes, scales, zeros, packed words and the fp32 dequantised weights; fp16 outputs
 within rel-L2 <= 1e-3 and max-abs <= 1e-2 * max|ref| of the oracle's fp64 result.
-Shapes span several 16x128 tiles, ragged row blocks (N not a multiple of the kernels' row
-blocks), ragged token counts, split-K, and the first configuration at full size."""
+Shapes span several 64x128 blocks, ragged row blocks (N not a multiple of the workgroups' 256 rows), ragged token counts, split-K, and the first configuration at full size."""
 import numpy as np
 import pytest
 
@@ -24,7 +23,7 @@ def _need_gpu():
 # ---- a1 + a2: quantise and pack ---------------------------------------------------------
 
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
-@pytest.mark.parametrize("N,K", [(16, 128), (48, 384), (208, 1280)])
+@pytest.mark.parametrize("N,K", [(64, 128), (192, 384), (320, 1280)])
 def test_quantize_pack_bit_exact(orc, bits, scheme, N, K):
     w = wl.weight_np(N, K, "qp", bits, scheme, N, K)
     qw = lpq.lpq_quantize_pack(to_dev(w), bits, scheme)
@@ -38,7 +37,7 @@ def test_quantize_pack_edge_groups(orc, bits, scheme):
     """Flat groups, -0/+0, exact grids, ranges whose fp16 scale is subnormal or underflows,
     large magnitudes: bit-equality with the oracle is all that is asked here."""
     rng = np.random.default_rng(5)
-    N, K = 32, 1024
+    N, K = 64, 1024
     w = wl.weight_np(N, K, "edge", bits, scheme).astype(np.float32)
     w[:, 0:128] = 0.0
     w[:, 128:256] = 0.37
@@ -63,7 +62,7 @@ def test_quantize_pack_edge_groups(orc, bits, scheme):
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("M", [1, 2, 5, 16, 17, 33, 64])
 def test_decode_small(orc, bits, scheme, M):
-    N, K = 80, 640          # 5 row tiles: ragged against both 64- and 32-row blocks
+    N, K = 320, 640         # 5 (fp16: 10) row blocks: the last workgroup has idle waves
     w = wl.weight_np(N, K, "dec", bits, scheme)
     x = wl.act_np(M, K, True, "dec", M)
     qw = lpq.lpq_quantize_pack(to_dev(w), bits, scheme)
@@ -76,7 +75,7 @@ def test_decode_small(orc, bits, scheme, M):
 def test_decode_split_k_and_many_rows(orc, bits, scheme, M):
     """K long enough that the work is cut into several K ranges (fp32 partial sums + reduction);
     M > 64 runs in several passes; a bias is added exactly once."""
-    N, K = 96, 16384
+    N, K = 192, 16384
     w = wl.weight_np(N, K, "decsk", bits, scheme)
     x = wl.act_np(M, K, True, "decsk", M)
     bias = (np.arange(N) % 7 - 3).astype(np.float16)
@@ -92,7 +91,7 @@ def test_decode_split_k_and_many_rows(orc, bits, scheme, M):
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("M", [1, 7, 128, 130, 300])
 def test_prefill_small(orc, bits, scheme, M):
-    N, K = 336, 640         # 21 row tiles: ragged against the 256-row block and the 64-row wave slice
+    N, K = 320, 640         # 5 row blocks: the second workgroup has one active wave
     w = wl.weight_np(N, K, "pre", bits, scheme)
     x = wl.act_np(M, K, True, "pre", M)
     bias = (np.arange(N) % 5 - 2).astype(np.float16) if M == 7 else None

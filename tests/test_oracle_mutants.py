@@ -21,7 +21,10 @@ MUTANTS = [
     ("matmul_swapped_output_index", "y[m * N + n] = acc;", "y[(M - 1 - m) * N + n] = acc;", 1),
     ("nibble_order_sequential", "4 * (e / 2) + 16 * (e % 2)", "4 * e", 2),
     ("three_bit_fields_reversed", "16 * h + 3 * (P % 5)", "16 * h + 3 * (4 - P % 5)", 2),
-    ("lane_uses_kq_major_rows", "*lane = 16 * kq + r;", "*lane = 4 * r + kq;", 1),
+    ("lane_uses_kq_major_rows", "*lane = 16 * ((kk % 32) / 8) + r;", "*lane = 4 * r + (kk % 32) / 8;", 1),
+    ("rows_of_a_tile_consecutive", "t = (int)(n % 4), r = (int)((n % ORC_BLOCK_ROWS) / 4);", "t = (int)((n % ORC_BLOCK_ROWS) / 16), r = (int)(n % 16);", 1),
+    ("tiles_ordered_by_tile_then_k", "(((size_t)block * (size_t)KT + (size_t)kt) * 4u + (size_t)t)", "(((size_t)block * 4u + (size_t)t) * (size_t)KT + (size_t)kt)", 1),
+    ("scales_stored_row_major", "stored[g * N + n] = natural[n * G + g];", "stored[n * G + g] = natural[n * G + g];", 1),
     ("byte_order_of_8bit", "8 * (j % 2) + e]", "8 * (j % 2) + (7 - e)]", 2),
     ("sym_divides_by_128", "a / 127.0f", "a / 128.0f", 1),
     ("f2h_ties_away", "double r = nearbyint(q);", "double r = floor(q + 0.5);", 1),

@@ -40,7 +40,8 @@
  *     bits 8:  2048-byte tile; 32 B per lane as two 16-byte pieces; piece p (j = 2p, 2p+1) at
  *              1024*p + 16*lane; byte 8*(j%2) + e.  Unsigned for LPQ_ASYM_GROUP, two's
  *              complement in [-127, 127] for LPQ_SYM_CHANNEL.
- *     bits 16: the row-major fp16 matrix itself (a byte copy of W).
+ *     bits 16: 4096-byte tile of the unchanged fp16 weights; 64 B per lane as four 16-byte pieces,
+ *              piece j at 1024*j + 16*lane, element e at byte 2*e.
  *   scales, zeros: fp16 [K/128][N], group-major (index g*N + n) for LPQ_ASYM_GROUP; scales fp16
  *   [N] and no zeros for LPQ_SYM_CHANNEL; neither for LPQ_FP16.  "zero" is the group minimum, a
  *   floating offset.
@@ -124,7 +125,7 @@ lpq_status lpq_packed_sizes(const lpq_qdesc *desc, size_t *code_bytes, size_t *s
  *   LPQ_ASYM_GROUP  scale = fp16((max - min) / (2^b - 1)) (1.0 if that is zero),
  *                   zero = min, code = clamp(rint((w - zero) / scale), 0, 2^b - 1)
  *   LPQ_SYM_CHANNEL scale = fp16(max|w| / 127) (1.0 if zero), code = clamp(rint(w / scale), +-127)
- *   LPQ_FP16        codes = copy of w.
+ *   LPQ_FP16        codes = the fp16 values of w, unchanged, in tile order.
  * Weights must be finite.  Errors: NULL, BITS, SCHEME, SHAPE, ALIGN, DEVICE. */
 lpq_status lpq_quantize_pack(const void *w_fp16, const lpq_qdesc *desc, lpq_qweight *out, void *hip_stream);
 

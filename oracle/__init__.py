@@ -74,6 +74,8 @@ class Oracle:
         L.lpq_oracle_pack.argtypes = [vp, i, i, l, l, vp]
         L.lpq_oracle_unpack.argtypes = [vp, i, i, l, l, vp]
         L.lpq_oracle_store_scales.argtypes = [vp, l, l, vp]
+        L.lpq_oracle_pack_fp16.argtypes = [vp, l, l, vp]
+        L.lpq_oracle_unpack_fp16.argtypes = [vp, l, l, vp]
         L.lpq_oracle_dequant.argtypes = [vp, vp, vp, i, i, l, l, vp]
         L.lpq_oracle_fp16_to_f32.argtypes = [vp, l, vp]
         L.lpq_oracle_matmul.argtypes = [vp, vp, l, l, l, vp, vp]
@@ -171,12 +173,31 @@ class Oracle:
             raise ValueError("lpq_oracle_store_scales rc=%d" % rc)
         return out
 
+    def pack_fp16(self, w):
+        """16-bit layers: fp16 [N][K] -> the same values in stored (tile) order, as bytes."""
+        w = _u16(w)
+        N, K = w.shape
+        out = np.empty((N * K * 2,), np.uint8)
+        rc = self._L.lpq_oracle_pack_fp16(_ptr(w), K, N, _ptr(out))
+        if rc:
+            raise ValueError("lpq_oracle_pack_fp16 rc=%d" % rc)
+        return out
+
+    def unpack_fp16(self, packed, K, N):
+        packed = np.ascontiguousarray(packed, np.uint8)
+        assert packed.size == N * K * 2
+        out = np.empty((N, K), np.uint16)
+        rc = self._L.lpq_oracle_unpack_fp16(_ptr(packed), K, N, _ptr(out))
+        if rc:
+            raise ValueError("lpq_oracle_unpack_fp16 rc=%d" % rc)
+        return out
+
     def quantize_pack(self, w, bits, scheme):
         """O1-O3 in one call, everything in stored order: (packed uint8, scales uint16 | None,
         zeros uint16 | None); grouped scales and zeros are [K/128][N], per-row scales [N]."""
         w = _u16(w)
         if scheme == FP16:
-            return w.reshape(-1).view(np.uint8).copy(), None, None
+            return self.pack_fp16(w), None, None
         codes, scales, zeros = self.quantize(w, bits, scheme)
         if scheme == ASYM_GROUP:
             K = w.shape[1]
@@ -221,6 +242,8 @@ quantize = _forward('quantize')
 pack = _forward('pack')
 unpack = _forward('unpack')
 store_scales = _forward('store_scales')
+pack_fp16 = _forward('pack_fp16')
+unpack_fp16 = _forward('unpack_fp16')
 dequant = _forward('dequant')
 fp16_to_f32 = _forward('fp16_to_f32')
 matmul = _forward('matmul')

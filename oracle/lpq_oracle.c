@@ -45,7 +45,8 @@
  *     8-bit: 2048-byte tile; 32 bytes per lane in two 16-byte pieces: piece p (j = 2p, 2p+1) at
  *            1024*p + 16*lane; byte 8*(j%2) + e holds code (j, e).  Signed codes are two's
  *            complement.
- *     16-bit: the packed buffer is the row-major fp16 matrix itself.
+ *     16-bit: 4096-byte tile of unchanged fp16 weights; 64 bytes per lane as four 16-byte pieces:
+ *            piece j at 1024*j + 16*lane, element e (2 bytes, little-endian) at byte 2*e.
  *   scales (and zeros) as stored: fp16 [K/128][N] (group-major: index g*N + n); per-row
  *   scheme: scales fp16 [N], no zeros.  lpq_oracle_quantize returns them in the natural
  *   [N][K/128] order; lpq_oracle_store_scales rearranges them into the stored order.
@@ -265,6 +266,35 @@ int lpq_oracle_unpack(const uint8_t *packed, int bits, int scheme, long K, long 
                 c = (scheme == ORC_SYM_CHANNEL) ? (int32_t)(int8_t)b : (int32_t)b;
             }
             codes[n * K + k] = c;
+        }
+    }
+    return 0;
+}
+
+/* 16-bit layers: the fp16 weights are stored unchanged, but in the same tile order. */
+int lpq_oracle_pack_fp16(const uint16_t *w, long K, long N, uint8_t *packed)
+{
+    if (check_desc(16, ORC_FP16, K, N)) return -1;
+    for (long n = 0; n < N; ++n) {
+        for (long k = 0; k < K; ++k) {
+            int lane, j, e;
+            uint8_t *tile = packed + locate(n, k, K, 16, &lane, &j, &e);
+            uint16_t v = w[n * K + k];
+            tile[1024 * j + 16 * lane + 2 * e]     = (uint8_t)(v & 0xffu);
+            tile[1024 * j + 16 * lane + 2 * e + 1] = (uint8_t)(v >> 8);
+        }
+    }
+    return 0;
+}
+
+int lpq_oracle_unpack_fp16(const uint8_t *packed, long K, long N, uint16_t *w)
+{
+    if (check_desc(16, ORC_FP16, K, N)) return -1;
+    for (long n = 0; n < N; ++n) {
+        for (long k = 0; k < K; ++k) {
+            int lane, j, e;
+            const uint8_t *tile = packed + locate(n, k, K, 16, &lane, &j, &e);
+            w[n * K + k] = (uint16_t)(tile[1024 * j + 16 * lane + 2 * e] | (tile[1024 * j + 16 * lane + 2 * e + 1] << 8));
         }
     }
     return 0;

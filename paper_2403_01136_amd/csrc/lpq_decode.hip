@@ -63,12 +63,12 @@ __device__ __forceinline__ void run_unit(const LinDesc& L, int M, int m0, int un
     Stage st[STAGES];
     auto issue = [&](Stage& b, int kt) {
         kt = min(kt, kt_end - 1);
-        if constexpr (V == V_F16) {
-#pragma unroll
-            for (int t = 0; t < RT; ++t) b.w[t] = load_rows_f16(L.codes, rbc * 32 + 2 * r + t, L.K, kt, lane);
-        } else {
+        if constexpr (RT == 4) {
 #pragma unroll
             for (int t = 0; t < RT; ++t) b.w[t] = load_tile<V>(L.codes, rbc, KT, kt, t, lane);
+        } else {   // half a 64-row block per wave: tiles 2*(rbc%2) + t
+#pragma unroll
+            for (int t = 0; t < RT; ++t) b.w[t] = load_tile<V>(L.codes, rbc >> 1, KT, kt, 2 * (int)(rbc & 1) + t, lane);
         }
         if constexpr (SCHEME == SCH_ASYM) {
             const size_t idx = (size_t)kt * L.N + rbc * 64 + 4 * r;
@@ -76,26 +76,83 @@ __device__ __forceinline__ void run_unit(const LinDesc& L, int M, int m0, int un
             b.z = *reinterpret_cast<const u32x2*>(L.zeros + idx);
         }
     };
+    // Two ways to fold scale and zero in.  POST (few tokens): multiply raw codes on the matrix
+    // cores per 128-column group, then acc += scale * (codes . x) + zero * sum(x) in fp32, with
+    // sum(x) from one extra MFMA against a block of ones -- the scale costs 8 fp32 FMAs per tile
+    // instead of 16 packed FMAs plus the int -> fp16 conversions.  Otherwise (many tokens, where the
+    // fp32 work would grow with M): dequantise each weight to fp16 once, w~ = scale * code + zero.
+    constexpr bool POST = (MT <= 2) && V != V_F16;
+    f4 xsum[MT];                      // per-row scheme only: sum of x over the whole K range
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) xsum[mt] = f4{0, 0, 0, 0};
     auto compute = [&](Stage& b, int buf, int step) {
         h8 wb[RT][4];
+        if constexpr (POST) {
 #pragma unroll
-        for (int t = 0; t < RT; ++t) {
-            unpack_codes<V>(b.w[t], wb[t]);
+            for (int t = 0; t < RT; ++t) unpack_subnormal<V>(b.w[t], wb[t]);
+            const _Float16 one = (_Float16)1.0f;
+            const h8 ones = {one, one, one, one, one, one, one, one};
             if constexpr (SCHEME == SCH_ASYM) {
-                const uint32_t sp = b.s[t >> 1], zp = b.z[t >> 1];
-                const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
-                const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
-                apply_scale_zero(wb[t], __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
+                f4 d[RT][MT], xs[MT];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    xs[mt] = f4{0, 0, 0, 0};
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) d[t][mt] = f4{0, 0, 0, 0};
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const h8 a = *reinterpret_cast<const h8*>(&sm.x[buf][16 * mt + r][step * 128 + 32 * j + 8 * kq]);
+                        xs[mt] = mfma16(a, ones, xs[mt]);
+#pragma unroll
+                        for (int t = 0; t < RT; ++t) d[t][mt] = mfma16(a, wb[t][j], d[t][mt]);
+                    }
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    const uint32_t sp = b.s[t >> 1], zp = b.z[t >> 1];
+                    const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
+                    const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
+                    const float sf = (float)__builtin_bit_cast(_Float16, sh) * 16777216.0f;     // scale * 2^24
+                    const float zf = (float)__builtin_bit_cast(_Float16, zh);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            acc[t][mt][v] = __builtin_fmaf(sf, d[t][mt][v], __builtin_fmaf(zf, xs[mt][v], acc[t][mt][v]));
+                }
+            } else {   // per-row scheme: one scale per row, applied in the epilogue
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const h8 a = *reinterpret_cast<const h8*>(&sm.x[buf][16 * mt + r][step * 128 + 32 * j + 8 * kq]);
+                        xsum[mt] = mfma16(a, ones, xsum[mt]);
+#pragma unroll
+                        for (int t = 0; t < RT; ++t) acc[t][mt] = mfma16(a, wb[t][j], acc[t][mt]);
+                    }
             }
+        } else {
+#pragma unroll
+            for (int t = 0; t < RT; ++t) {
+                unpack_codes<V>(b.w[t], wb[t]);
+                if constexpr (SCHEME == SCH_ASYM) {
+                    const uint32_t sp = b.s[t >> 1], zp = b.z[t >> 1];
+                    const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
+                    const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
+                    apply_scale_zero(wb[t], __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const h8 a = *reinterpret_cast<const h8*>(&sm.x[buf][16 * mt + r][step * 128 + 32 * j + 8 * kq]);
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) acc[t][mt] = mfma16(a, wb[t][j], acc[t][mt]);
+                }
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const h8 a = *reinterpret_cast<const h8*>(&sm.x[buf][16 * mt + r][step * 128 + 32 * j + 8 * kq]);
-#pragma unroll
-                for (int t = 0; t < RT; ++t) acc[t][mt] = mfma16(a, wb[t][j], acc[t][mt]);
-            }
     };
 
     // ---- activation staging: chunk c covers steps [kt_begin + c*CHUNK, +CHUNK)
@@ -144,8 +201,8 @@ __device__ __forceinline__ void run_unit(const LinDesc& L, int M, int m0, int un
     }
     if (!active) return;
 
-    // ---- epilogue: lane holds tokens 4*kq + v of rows base + RT*r + t (RT consecutive rows)
-    const long nbase = rb * (16 * RT) + RT * r;
+    // ---- epilogue: lane holds tokens 4*kq + v of RT consecutive rows starting at nbase
+    const long nbase = (RT == 4) ? rb * 64 + 4 * r : (rb >> 1) * 64 + 4 * r + 2 * (rb & 1);
     float post[RT], bias[RT];
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
@@ -161,7 +218,11 @@ __device__ __forceinline__ void run_unit(const LinDesc& L, int M, int m0, int un
             if (tok >= M) continue;
             float val[RT];
 #pragma unroll
-            for (int t = 0; t < RT; ++t) val[t] = acc[t][mt][v] * post[t];
+            for (int t = 0; t < RT; ++t) {
+                float a = acc[t][mt][v];
+                if constexpr (POST && SCHEME == SCH_SYM) a = a * 16777216.0f - 128.0f * xsum[mt][v];   // undo 2^-24 and the +128 offset
+                val[t] = a * post[t];
+            }
             if (L.ksplit == 1) {
                 typedef _Float16 hv __attribute__((ext_vector_type(RT)));
                 hv o;

@@ -52,27 +52,19 @@ template <> struct WRaw<V_F16> { u32x4 q[4]; };
 template <int V>
 __device__ __forceinline__ WRaw<V> load_tile(const uint8_t* __restrict__ codes, long rb, int KT, int kt, int t, int lane)
 {
-    static_assert(V != V_F16, "fp16 weights are row-major, see load_rows_f16");
     WRaw<V> w;
     const uint8_t* tile = codes + (((size_t)rb * KT + kt) * 4 + t) * (size_t)VInfo<V>::TILE_BYTES;
     if constexpr (V == V_W3) {
         w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x3*>(tile + 12 * lane));
     } else if constexpr (V == V_W4) {
         w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 16 * lane));
-    } else {
+    } else if constexpr (V == V_W8 || V == V_I8) {
         w.q[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 16 * lane));
         w.q[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 1024 + 16 * lane));
-    }
-    return w;
-}
-
-// fp16 weights (row-major [N][K]): the lane's four 16-byte pieces of row n in 128-column step kt
-__device__ __forceinline__ WRaw<V_F16> load_rows_f16(const uint8_t* __restrict__ w16, long n, int K, int kt, int lane)
-{
-    WRaw<V_F16> w;
-    const uint8_t* p = w16 + ((size_t)n * (size_t)K + (size_t)kt * 128 + 8 * (lane >> 4)) * 2;
+    } else {   // fp16 weights: piece j is the operand of MFMA step j as it stands
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w.q[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 64 * j));
+        for (int j = 0; j < 4; ++j) w.q[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 1024 * j + 16 * lane));
+    }
     return w;
 }
 
@@ -139,6 +131,54 @@ __device__ __forceinline__ void unpack_codes(const WRaw<V>& w, h8 out[4])
             h2 p3 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00070006u)) - splat(off);
             h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
             out[j] = o;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = __builtin_bit_cast(h8, w.q[j]);
+    }
+}
+
+// ---- unpack to fp16 SUBNORMALS whose value is code * 2^-24 ------------------------------
+// A code field moved to mantissa bits 0.. of a half-word with a zero exponent IS the fp16
+// subnormal code * 2^-24, so one AND per pair of codes yields an MFMA operand (the matrix cores
+// take fp16 subnormals at full precision).  The factor 2^24 is folded into the group scale, which
+// is applied in fp32 after the 128-column partial product.  Signed 8-bit codes come out offset by
+// +128 (two's complement with the top bit flipped); the caller removes 128 * sum(x).
+template <int V>
+__device__ __forceinline__ void unpack_subnormal(const WRaw<V>& w, h8 out[4])
+{
+    if constexpr (V == V_W4) {
+        constexpr uint32_t M4 = 0x000F000Fu;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t q = w.q[j];
+            const u32x4 o = {q & M4, (q >> 4) & M4, (q >> 8) & M4, (q >> 12) & M4};
+            out[j] = __builtin_bit_cast(h8, o);
+        }
+    } else if constexpr (V == V_W3) {
+        constexpr uint32_t M3 = 0x00070007u;
+        uint32_t pr[16];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const uint32_t q = w.q[i];
+#pragma unroll
+            for (int f = 0; f < 5; ++f) pr[5 * i + f] = (q >> (3 * f)) & M3;
+        }
+        pr[15] = ((w.q[0] >> 15) & 0x00010001u) | ((w.q[1] >> 14) & 0x00020002u) | ((w.q[2] >> 13) & 0x00040004u);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32x4 o = {pr[4 * j], pr[4 * j + 1], pr[4 * j + 2], pr[4 * j + 3]};
+            out[j] = __builtin_bit_cast(h8, o);
+        }
+    } else if constexpr (V == V_W8 || V == V_I8) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t a = w.q[j >> 1][2 * (j & 1)], b = w.q[j >> 1][2 * (j & 1) + 1];
+            if constexpr (V == V_I8) { a ^= 0x80808080u; b ^= 0x80808080u; }
+            // selector bytes: 4..7 = bytes of the first operand, 0x0c = constant zero
+            const u32x4 o = {__builtin_amdgcn_perm(a, 0u, 0x0c050c04u), __builtin_amdgcn_perm(a, 0u, 0x0c070c06u),
+                             __builtin_amdgcn_perm(b, 0u, 0x0c050c04u), __builtin_amdgcn_perm(b, 0u, 0x0c070c06u)};
+            out[j] = __builtin_bit_cast(h8, o);
         }
     } else {
 #pragma unroll

@@ -69,13 +69,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint8_t* __restrict_
     WRaw<V> wraw[NW];
     u32x2 ws, wz;                                    // fp16 scale / zero of the lane's four rows 4r..4r+3
     auto load_w = [&](int kt) {
-        if constexpr (V == V_F16) {
 #pragma unroll
-            for (int t = 0; t < NW; ++t) wraw[t] = load_rows_f16(codes, rbc * 64 + 4 * r + t, K, kt, lane);
-        } else {
-#pragma unroll
-            for (int t = 0; t < NW; ++t) wraw[t] = load_tile<V>(codes, rbc, KT, kt, t, lane);
-        }
+        for (int t = 0; t < NW; ++t) wraw[t] = load_tile<V>(codes, rbc, KT, kt, t, lane);
         if constexpr (SCHEME == SCH_ASYM) {
             const size_t idx = (size_t)kt * N + rbc * 64 + 4 * r;
             ws = *reinterpret_cast<const u32x2*>(scales + idx);

@@ -164,6 +164,22 @@ __global__ __launch_bounds__(256) void quantize_sym_kernel(const uint16_t* __res
     store_packed<8, true>(codes, tile, lane, c);
 }
 
+// 16-bit layers: the fp16 weights unchanged, reordered into tiles (piece j of a lane = operand of MFMA step j)
+__global__ __launch_bounds__(256) void pack_fp16_kernel(const uint16_t* __restrict__ w, int K, long NT, uint8_t* __restrict__ codes)
+{
+    const int KT = K / 128;
+    const long tile = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= NT * KT) return;
+    const int lane = threadIdx.x & 63, t = (int)(tile & 3);
+    const long rb = (tile >> 2) / KT;
+    const int kt = (int)((tile >> 2) % KT);
+    const long n = rb * 64 + 4 * (lane & 15) + t;
+    const uint16_t* p = w + n * K + (long)kt * 128 + 8 * (lane >> 4);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        *reinterpret_cast<u32x4*>(codes + tile * 4096 + 1024 * j + 16 * lane) = *reinterpret_cast<const u32x4*>(p + 32 * j);
+}
+
 // ---- test helper: packed buffers -> fp32 weights, one code at a time from the format ----
 // (kept separate from the matmul kernels' fast unpacking on purpose)
 __device__ __forceinline__ int extract_code(const uint8_t* __restrict__ tile, int variant, int lane, int j, int e)
@@ -198,9 +214,9 @@ __global__ __launch_bounds__(256) void unpack_dequant_kernel(const uint8_t* __re
     const long N = NT * 16;
     float* o = out + n * K + (long)kt * 128 + 8 * kq;
     if (variant == V_F16) {
-        const uint16_t* p = reinterpret_cast<const uint16_t*>(codes) + n * K + (long)kt * 128 + 8 * kq;
+        const uint16_t* p = reinterpret_cast<const uint16_t*>(codes + (size_t)tile * 4096);
         for (int j = 0; j < 4; ++j)
-            for (int e = 0; e < 8; ++e) o[32 * j + e] = h2f_bits(p[32 * j + e]);
+            for (int e = 0; e < 8; ++e) o[32 * j + e] = h2f_bits(p[512 * j + 8 * lane + e]);
         return;
     }
     const size_t tb = variant == V_W3 ? 768 : (variant == V_W4 ? 1024 : 2048);
@@ -235,8 +251,7 @@ hipError_t launch_quantize_pack(const void* w, const lpq_qdesc& d, const lpq_qwe
         row_absmax_scale_kernel<<<(unsigned)d.N, 256, 0, s>>>(wp, d.K, sc);
         quantize_sym_kernel<<<blocks, 256, 0, s>>>(wp, d.K, NT, codes, sc);
         break;
-    case V_F16:
-        return hipMemcpyAsync(codes, w, (size_t)d.K * (size_t)d.N * 2, hipMemcpyDeviceToDevice, s);
+    case V_F16: pack_fp16_kernel<<<blocks, 256, 0, s>>>(wp, d.K, NT, codes); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -91,6 +91,9 @@ def spec_bit_positions(bits, n, k, K):
     if bits == 8:
         byte = 1024 * (j // 2) + 16 * lane + 8 * (j % 2) + e
         return [tile_bit0 + 8 * byte + i for i in range(8)]
+    if bits == 16:
+        byte = 1024 * j + 16 * lane + 2 * e
+        return [tile_bit0 + 8 * byte + i for i in range(16)]
     raise ValueError(bits)
 
 
@@ -177,6 +180,11 @@ def pin_pack_matches_format_description(orc):
     assert np.array_equal(s_st, s_nat.T) and np.array_equal(z_st, z_nat.T) and np.array_equal(packed, orc.pack(codes, 4, ASYM))
     _, s_row, z_row = orc.quantize_pack(w, 8, SYM)
     assert s_row.shape == (N,) and z_row is None
+    # 16-bit layers: the fp16 bit patterns, unchanged, at the positions the description gives
+    p16 = orc.pack_fp16(w)
+    assert np.array_equal(p16, spec_pack(w.view(np.uint16).astype(np.int64), 16))
+    assert np.array_equal(orc.unpack_fp16(p16, K, N), w.view(np.uint16))
+    assert np.array_equal(np.sort(p16.view(np.uint16)), np.sort(w.view(np.uint16).reshape(-1)))
 
 
 # ---------------------------------------------------------------------------------------
@@ -364,7 +372,7 @@ def pin_fp16_path_is_plain_matmul(orc):
         assert got.shape == (M, N)
         assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
         p, s, z = orc.quantize_pack(w, 16, FP16)
-        assert s is None and z is None and p.tobytes() == w.tobytes()
+        assert s is None and z is None and np.array_equal(orc.unpack_fp16(p, K, N), w.view(np.uint16))
         bias = rng.standard_normal(N).astype(np.float16)
         gotb = orc.matmul(x, orc.fp16_to_f32(w), bias)
         assert np.allclose(gotb, want + bias.astype(np.float64)[None, :], rtol=1e-12, atol=1e-12)

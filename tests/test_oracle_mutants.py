@@ -26,6 +26,7 @@ MUTANTS = [
     ("tiles_ordered_by_tile_then_k", "(((size_t)block * (size_t)KT + (size_t)kt) * 4u + (size_t)t)", "(((size_t)block * 4u + (size_t)t) * (size_t)KT + (size_t)kt)", 1),
     ("scales_stored_row_major", "stored[g * N + n] = natural[n * G + g];", "stored[n * G + g] = natural[n * G + g];", 1),
     ("byte_order_of_8bit", "8 * (j % 2) + e]", "8 * (j % 2) + (7 - e)]", 2),
+    ("fp16_pieces_per_lane_contiguous", "1024 * j + 16 * lane + 2 * e", "64 * lane + 16 * j + 2 * e", 4),
     ("sym_divides_by_128", "a / 127.0f", "a / 128.0f", 1),
     ("f2h_ties_away", "double r = nearbyint(q);", "double r = floor(q + 0.5);", 1),
     ("scale_from_max_only", "volatile float range = hi - lo;", "volatile float range = hi;", 1),

@@ -87,14 +87,46 @@ lpq_status workspace(size_t need, float** out)
     return LPQ_OK;
 }
 
-size_t decode_unit_bytes()
+int env_int(const char* name, int fallback)
 {
-    static const size_t v = [] {
-        const char* e = std::getenv("LPQ_DECODE_UNIT_KB");
-        long kb = e ? std::atol(e) : 0;
-        return (size_t)(kb > 0 ? kb : 128) << 10;
-    }();
+    const char* e = std::getenv(name);
+    return (e && *e) ? std::atoi(e) : fallback;
+}
+
+// Wavefronts per decode workgroup (4 or 8) and workgroups per launch as a multiple of what the chip
+// holds at once; both can be overridden for experiments.
+int decode_waves()
+{
+    static const int v = env_int("LPQ_DECODE_WAVES", 4) == 8 ? 8 : 4;
     return v;
+}
+
+lpq_status decode_block_count(int waves, int* out)
+{
+    static std::mutex mu;
+    static int cus[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return LPQ_ERR_DEVICE;
+        cus[dev] = n;
+    }
+    static const int per_cu_x4 = std::max(1, env_int("LPQ_DECODE_BLOCKS_PER_CU_X4", 0));   // quarter workgroups per CU
+    const int resident = cus[dev] * (8 / waves);           // two waves per SIMD
+    *out = env_int("LPQ_DECODE_BLOCKS_PER_CU_X4", 0) > 0 ? std::max(1, cus[dev] * per_cu_x4 / 4) : resident;
+    return LPQ_OK;
+}
+
+// relative cost of streaming one byte of each variant (x16), used to weight the even-share split
+uint32_t variant_cost_x16(int variant)
+{
+    // measured on MI355X: bytes of 3- and 4-bit codes take longer to stream because unpacking them is
+    // ALU work per byte; 8-bit codes and fp16 weights run at the memory system's pace
+    static const int c[5] = {env_int("LPQ_COST_W3", 26), env_int("LPQ_COST_W4", 21), env_int("LPQ_COST_W8", 17),
+                             env_int("LPQ_COST_I8", 17), env_int("LPQ_COST_F16", 16)};
+    return (uint32_t)std::max(1, c[variant]);
 }
 
 struct LinearCall {
@@ -104,23 +136,32 @@ struct LinearCall {
 };
 
 // Decode-phase dispatch of a list of independent linears: grouped launches of at most
-// MAX_LIN_PER_LAUNCH linears, 64 token rows per pass.
+// MAX_LIN_PER_LAUNCH linears, 64 token rows per pass, each launch one round of equally loaded
+// workgroups (see lpq_decode.hip).
 lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream)
 {
     const size_t n = calls.size();
     const size_t n_launch = (n + MAX_LIN_PER_LAUNCH - 1) / MAX_LIN_PER_LAUNCH;
     const size_t per_launch = (n + n_launch - 1) / n_launch;
-    // plan every launch first so the workspace is sized (and possibly reallocated) once
-    std::vector<DecodeArgs> plans(n_launch);
-    std::vector<int> red_blocks(n_launch, 0);
-    std::vector<std::vector<size_t>> partial_off(n_launch);
-    size_t ws_floats = 0;
+    const int waves = decode_waves();
+    int n_blocks = 0;
+    lpq_status st = decode_block_count(waves, &n_blocks);
+    if (st != LPQ_OK) return st;
+    const int tok_rows = std::min(64, (M + 15) / 16 * 16);
+    const int slot_floats = tok_rows * waves * 64;
+    float* ws = nullptr;
+    st = workspace((size_t)2 * n_blocks * slot_floats * sizeof(float), &ws);
+    if (st != LPQ_OK) return st;
     for (size_t li = 0; li < n_launch; ++li) {
-        DecodeArgs& a = plans[li];
+        DecodeArgs a;
         a.M = M;
         a.m0 = 0;
         a.n_lin = 0;
-        int units = 0;
+        a.waves = waves;
+        a.n_blocks = n_blocks;
+        a.slot_floats = slot_floats;
+        a.partial = ws;
+        uint64_t total = 0;
         for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c) {
             const lpq_qweight& w = *calls[c].w;
             LinDesc& L = a.lin[a.n_lin++];
@@ -130,45 +171,22 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
             L.x = static_cast<const uint16_t*>(calls[c].x);
             L.y = static_cast<uint16_t*>(calls[c].y);
             L.bias = static_cast<const uint16_t*>(w.bias);
-            L.partial = nullptr;
             L.K = w.d.K;
             L.N = w.d.N;
             L.variant = variant_of(w.d);
             const int rows = decode_rows_per_wave(L.variant);
-            const int KT = L.K / 128;
-            const size_t step_bytes = (size_t)rows * 128 * (size_t)w.d.bits / 8;      // one wave, one 128-column step
-            const int kt_target = (int)std::max<size_t>(1, decode_unit_bytes() / step_bytes);
-            int ksplit = std::max(1, (KT + kt_target / 2) / kt_target);
-            L.kt_per_split = (KT + ksplit - 1) / ksplit;
-            L.ksplit = (KT + L.kt_per_split - 1) / L.kt_per_split;
             L.row_blocks = L.N / rows;
-            L.row_superblocks = (L.row_blocks + 3) / 4;
-            L.unit_begin = units;
-            units += L.row_superblocks * L.ksplit;
-            L.red_begin = red_blocks[li];
-            if (L.ksplit > 1) {
-                partial_off[li].push_back(ws_floats);
-                ws_floats += (size_t)L.ksplit * (size_t)M * (size_t)L.N;
-                const int m_cnt = std::min(M, 64);
-                red_blocks[li] += (int)(((size_t)(L.N / 4) * m_cnt + 255) / 256);
-            } else {
-                partial_off[li].push_back((size_t)-1);
-            }
+            L.row_superblocks = (L.row_blocks + waves - 1) / waves;
+            const uint32_t step_bytes = (uint32_t)(waves * rows) * (128u * (uint32_t)w.d.bits / 8u + (w.d.scheme == LPQ_ASYM_GROUP ? 4u : 0u));
+            L.step_weight = step_bytes * variant_cost_x16(L.variant);
+            L.cum_weight = total;
+            total += (uint64_t)L.step_weight * (uint64_t)L.row_superblocks * (uint64_t)(L.K / 128);
         }
-        a.total_units = units;
-    }
-    float* ws = nullptr;
-    if (ws_floats) {
-        lpq_status st = workspace(ws_floats * sizeof(float), &ws);
-        if (st != LPQ_OK) return st;
-    }
-    for (size_t li = 0; li < n_launch; ++li) {
-        DecodeArgs& a = plans[li];
-        for (int i = 0; i < a.n_lin; ++i)
-            if (a.lin[i].ksplit > 1) a.lin[i].partial = ws + partial_off[li][i];
+        if (total >= ((uint64_t)1 << 50)) return LPQ_ERR_UNSUPPORTED;
+        a.total_weight = total;
         for (int m0 = 0; m0 < M; m0 += 64) {
             a.m0 = m0;
-            if (launch_decode(a, red_blocks[li], stream) != hipSuccess) return LPQ_ERR_DEVICE;
+            if (launch_decode(a, stream) != hipSuccess) return LPQ_ERR_DEVICE;
         }
     }
     return LPQ_OK;

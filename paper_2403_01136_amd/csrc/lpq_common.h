@@ -6,7 +6,10 @@
 
 namespace lpq {
 
-// One linear as the grouped kernels see it (passed by value in the kernel arguments).
+// One linear as the grouped decode kernels see it (passed by value in the kernel arguments).
+// Its work is steps = row_superblocks * (K/128) "block steps" (one 128-column step of the
+// WAVES row blocks a workgroup owns), each of weight `step_weight` (bytes streamed, scaled by a
+// per-variant cost factor); `cum_weight` is the total weight of the linears before it.
 struct LinDesc {
     const uint8_t* codes;
     const uint16_t* scales;
@@ -14,21 +17,25 @@ struct LinDesc {
     const uint16_t* x;      // fp16 [M][K]
     uint16_t* y;            // fp16 [M][N]
     const uint16_t* bias;   // fp16 [N] or null
-    float* partial;         // split-K partial sums [ksplit][M][N] (null when ksplit == 1)
+    uint64_t cum_weight;
+    uint32_t step_weight;
     int32_t K, N;
     int32_t variant;        // V_W3 .. V_F16
-    int32_t ksplit;         // number of K ranges
-    int32_t kt_per_split;   // 128-column tiles per K range
     int32_t row_blocks;     // N / rows per wave (64; 32 for fp16 weights)
-    int32_t row_superblocks;// ceil(row_blocks / 4): one workgroup each
-    int32_t unit_begin;     // first work unit (workgroup) of this linear in the launch
-    int32_t red_begin;      // first reduction block of this linear (split-K only)
+    int32_t row_superblocks;// ceil(row_blocks / waves per workgroup)
 };
 
-enum { MAX_LIN_PER_LAUNCH = 42 };   // keeps DecodeArgs under the 4 KB kernel-argument limit
+enum { MAX_LIN_PER_LAUNCH = 44 };   // keeps DecodeArgs under the 4 KB kernel-argument limit
 
+// Even-share decomposition: the launch's total weight is cut into n_blocks equal ranges; workgroup
+// b streams the steps whose start offset falls in [b, b+1) * total / n_blocks.  A (linear, row
+// superblock) unit that a range boundary cuts is finished by the fix-up kernel from the fp32
+// partial tiles the workgroups leave in `partial` (two slots per workgroup).
 struct DecodeArgs {
-    int32_t n_lin, M, m0, total_units;   // m0: first token row of this pass (M > 64 is run 64 rows at a time)
+    int32_t n_lin, M, m0, waves;         // m0: first token row of this pass (M > 64 is run 64 rows at a time)
+    int32_t n_blocks, slot_floats;       // slot_floats: floats per partial tile = 64 tokens x rows per workgroup
+    uint64_t total_weight;
+    float* partial;
     LinDesc lin[MAX_LIN_PER_LAUNCH];
 };
 
@@ -41,7 +48,7 @@ size_t tile_bytes_of(int variant);
 // launchers (each returns a hipError_t from the launch)
 hipError_t launch_quantize_pack(const void* w, const lpq_qdesc& d, const lpq_qweight& out, hipStream_t s);
 hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s);
-hipError_t launch_decode(const DecodeArgs& a, int n_red_blocks, hipStream_t s);
+hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_prefill(const lpq_qweight& w, const void* x, int M, void* y, hipStream_t s);
 
 }  // namespace lpq

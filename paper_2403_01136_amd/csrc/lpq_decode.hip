@@ -2,16 +2,19 @@
 // arXiv 2403.01136, Sec. 4.1 "Latency Cost Model": the decode phase is bound by the bytes it
 // streams; Sec. 4.3: M = xi, one token per sequence).
 //
-// One grouped launch covers every linear of a stage.  A work unit is (linear, K range, 4
-// consecutive row blocks); one workgroup of four wavefronts owns a unit and each wave owns one
-// row block (64 rows of W; 32 for fp16 weights).  A wave streams its block's packed tiles from
-// HBM as one sequential stream of 16-byte (12-byte for 3-bit) per-lane loads that are contiguous
-// across the wave, keeps several 128-column steps in flight in registers, unpacks them there into
-// MFMA B operands and multiplies them with the activations (MFMA A operands).  The activations of
-// the unit's K range are staged once per workgroup through a double-buffered LDS slab, so they
-// cost a quarter of the global loads they would cost per wave.  Units whose K range is the whole
-// of K write fp16 outputs directly; otherwise they write fp32 partial sums and a second small
-// kernel adds them in a fixed order (deterministic results).
+// One grouped launch covers every linear of a stage, as one round of equally loaded workgroups.
+// The launch's work is the list of (linear, 4 or 8 consecutive row blocks, 128-column step) items,
+// each weighted by the bytes it streams; the list is cut into as many equal ranges as workgroups
+// fit on the chip, and workgroup b streams range b.  Within a range a workgroup meets whole
+// (linear, rows) units, which it finishes and stores as fp16, and at most two cut ones (its first
+// and its last), whose fp32 partial tiles it leaves for a small fix-up kernel that adds the pieces
+// of each cut unit in a fixed order (deterministic results).
+//
+// Inside a workgroup each wave owns one row block (64 rows of W; 32 for fp16 weights).  It streams
+// its block's packed tiles from HBM as one sequential stream of 16-byte (12-byte for 3-bit)
+// per-lane loads that are contiguous across the wave, keeps several 128-column steps in flight in
+// registers, unpacks them there into MFMA B operands and multiplies them with the activations
+// (MFMA A operands), which the workgroup stages once through a double-buffered LDS slab.
 #include "lpq_common.h"
 #include "lpq_device.h"
 
@@ -27,33 +30,63 @@ template <int V> struct DecodeCfg { enum { RT = (V == V_F16) ? 2 : 4, DEPTH = (V
 template <int MT> struct PipeCfg {
     enum { CHUNK = (MT == 1) ? 8 : (MT == 2) ? 4 : 2 };
     enum { ROW_HALVES = CHUNK * 128 + 8 };          // +16 bytes: conflict-free 16-byte operand reads
-    enum { PIECES = MT * CHUNK };                   // 16-byte pieces of a chunk per thread (256 threads)
+    enum { PIECES256 = MT * CHUNK };                // 16-byte pieces of a chunk per thread at 256 threads
 };
 
 template <int MT> struct DecodeSmem { uint16_t x[2][16 * MT][PipeCfg<MT>::ROW_HALVES]; };
 
-template <int V, int MT>
-__device__ __forceinline__ void run_unit(const LinDesc& L, int M, int m0, int unit, DecodeSmem<MT>& sm)
+// A chunk: up to CHUNK consecutive 128-column steps of one (linear, row superblock) unit.
+struct Chunk {
+    int sb, kt0, n;      // row superblock, first step, number of steps (0 = none)
+};
+
+// The workgroup's share of one linear: block steps [s_begin, s_end) of L (step = sb * KT + kt), which
+// may span several (linear, rows) units.  The weight pipeline runs on across unit boundaries; at
+// the end of a unit the accumulators are stored -- as fp16 if the unit's whole K range lay inside
+// [s_begin, s_end), else as an fp32 partial tile in slot_first (the unit this range entered mid-way)
+// or slot_last (the unit it leaves mid-way) -- and cleared.
+template <int V, int MT, int WAVES>
+__device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long s_begin, long s_end,
+                                          float* __restrict__ slot_first, float* __restrict__ slot_last, DecodeSmem<MT>& sm)
 {
     constexpr int RT = DecodeCfg<V>::RT;
     constexpr int SCHEME = VInfo<V>::SCHEME;
-    constexpr int CHUNK = PipeCfg<MT>::CHUNK, PIECES = PipeCfg<MT>::PIECES;
+    constexpr int CHUNK = PipeCfg<MT>::CHUNK, PIECES = PipeCfg<MT>::PIECES256 * 4 / WAVES, THREADS = 64 * WAVES;
     constexpr int STAGES = DecodeCfg<V>::DEPTH < CHUNK ? DecodeCfg<V>::DEPTH : CHUNK;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, kq = lane >> 4;
     const int KT = L.K / 128;
-    const int sb = unit % L.row_superblocks, split = unit / L.row_superblocks;
-    const long rb = (long)sb * 4 + wave;                  // this wave's row block
-    const bool active = rb < L.row_blocks;                // idle waves still stage activations
-    const long rbc = active ? rb : L.row_blocks - 1;
-    const int kt_begin = split * L.kt_per_split;
-    const int kt_end = min(KT, kt_begin + L.kt_per_split);
+
+    auto first_chunk = [&](long s) {
+        Chunk c;
+        c.sb = (int)(s / KT);
+        c.kt0 = (int)(s % KT);
+        c.n = (int)min((long)min(CHUNK, KT - c.kt0), s_end - s);
+        return c;
+    };
+    auto next_chunk = [&](const Chunk& c) {
+        Chunk d;
+        d.sb = c.sb;
+        d.kt0 = c.kt0 + c.n;
+        if (d.kt0 == KT) { d.kt0 = 0; ++d.sb; }
+        const long left = s_end - ((long)d.sb * KT + d.kt0);
+        d.n = (c.n == 0 || left <= 0) ? 0 : (int)min((long)min(CHUNK, KT - d.kt0), left);
+        return d;
+    };
+    // the wave's row block in a unit; waves past the end of W idle but still stage activations
+    auto row_block = [&](int sb) { return (long)sb * WAVES + wave; };
 
     f4 acc[RT][MT];
+    f4 xsum[MT];                      // per-row scheme only: sum of x over the unit's K range
+    auto clear_acc = [&]() {
 #pragma unroll
-    for (int t = 0; t < RT; ++t)
+        for (int mt = 0; mt < MT; ++mt) {
+            xsum[mt] = f4{0, 0, 0, 0};
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[t][mt] = f4{0, 0, 0, 0};
+            for (int t = 0; t < RT; ++t) acc[t][mt] = f4{0, 0, 0, 0};
+        }
+    };
+    clear_acc();
 
     // ---- weight pipeline: one Stage = everything one 128-column step needs from global memory
     struct Stage {
@@ -61,8 +94,8 @@ __device__ __forceinline__ void run_unit(const LinDesc& L, int M, int m0, int un
         u32x2 s, z;          // fp16 scale / zero of the lane's four rows (tiles 0..3), grouped scheme only
     };
     Stage st[STAGES];
-    auto issue = [&](Stage& b, int kt) {
-        kt = min(kt, kt_end - 1);
+    auto issue = [&](Stage& b, int sb, int kt) {
+        const long rbc = min(row_block(sb), (long)L.row_blocks - 1);
         if constexpr (RT == 4) {
 #pragma unroll
             for (int t = 0; t < RT; ++t) b.w[t] = load_tile<V>(L.codes, rbc, KT, kt, t, lane);
@@ -82,9 +115,6 @@ __device__ __forceinline__ void run_unit(const LinDesc& L, int M, int m0, int un
     // instead of 16 packed FMAs plus the int -> fp16 conversions.  Otherwise (many tokens, where the
     // fp32 work would grow with M): dequantise each weight to fp16 once, w~ = scale * code + zero.
     constexpr bool POST = (MT <= 2) && V != V_F16;
-    f4 xsum[MT];                      // per-row scheme only: sum of x over the whole K range
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) xsum[mt] = f4{0, 0, 0, 0};
     auto compute = [&](Stage& b, int buf, int step) {
         h8 wb[RT][4];
         if constexpr (POST) {
@@ -94,20 +124,15 @@ __device__ __forceinline__ void run_unit(const LinDesc& L, int M, int m0, int un
             const h8 ones = {one, one, one, one, one, one, one, one};
             if constexpr (SCHEME == SCH_ASYM) {
                 f4 d[RT][MT], xs[MT];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    xs[mt] = f4{0, 0, 0, 0};
-#pragma unroll
-                    for (int t = 0; t < RT; ++t) d[t][mt] = f4{0, 0, 0, 0};
-                }
+                const f4 zero4 = {0, 0, 0, 0};
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
                         const h8 a = *reinterpret_cast<const h8*>(&sm.x[buf][16 * mt + r][step * 128 + 32 * j + 8 * kq]);
-                        xs[mt] = mfma16(a, ones, xs[mt]);
+                        xs[mt] = mfma16(a, ones, j == 0 ? zero4 : xs[mt]);
 #pragma unroll
-                        for (int t = 0; t < RT; ++t) d[t][mt] = mfma16(a, wb[t][j], d[t][mt]);
+                        for (int t = 0; t < RT; ++t) d[t][mt] = mfma16(a, wb[t][j], j == 0 ? zero4 : d[t][mt]);
                     }
 #pragma unroll
                 for (int t = 0; t < RT; ++t) {
@@ -155,156 +180,239 @@ __device__ __forceinline__ void run_unit(const LinDesc& L, int M, int m0, int un
         }
     };
 
-    // ---- activation staging: chunk c covers steps [kt_begin + c*CHUNK, +CHUNK)
+    // ---- activation staging: the x columns of one chunk, shared by the workgroup through LDS
     u32x4 xr[PIECES];
-    auto load_x_chunk = [&](int kt0) {
+    auto load_x_chunk = [&](const Chunk& c) {
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) {
-            const int p = tid + 256 * i, row = p / (CHUNK * 16), c16 = p % (CHUNK * 16);
-            const int tok = m0 + row, col = kt0 * 128 + c16 * 8;
+            const int p = tid + THREADS * i, row = p / (CHUNK * 16), c16 = p % (CHUNK * 16);
+            const int tok = m0 + row;
             u32x4 v = {0, 0, 0, 0};
-            if (tok < M && col < kt_end * 128) v = *reinterpret_cast<const u32x4*>(L.x + (size_t)tok * L.K + col);
+            if (tok < M && c16 < c.n * 16) v = *reinterpret_cast<const u32x4*>(L.x + (size_t)tok * L.K + c.kt0 * 128 + c16 * 8);
             xr[i] = v;
         }
     };
     auto store_x_chunk = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) {
-            const int p = tid + 256 * i, row = p / (CHUNK * 16), c16 = p % (CHUNK * 16);
+            const int p = tid + THREADS * i, row = p / (CHUNK * 16), c16 = p % (CHUNK * 16);
             *reinterpret_cast<u32x4*>(&sm.x[buf][row][c16 * 8]) = xr[i];
         }
     };
 
-    load_x_chunk(kt_begin);
-    if (active) {
+    // ---- end of a unit: lane holds tokens 4*kq + v of RT consecutive rows starting at nbase
+    auto finish_unit = [&](int sb, float* __restrict__ partial) {
+        const long rb = row_block(sb);
+        if (rb < L.row_blocks) {
+            const long nbase = (RT == 4) ? rb * 64 + 4 * r : (rb >> 1) * 64 + 4 * r + 2 * (rb & 1);
+            float post[RT], bias[RT];
 #pragma unroll
-        for (int s = 0; s < STAGES; ++s) issue(st[s], kt_begin + s);
-    }
+            for (int t = 0; t < RT; ++t) {
+                post[t] = 1.0f;
+                if constexpr (SCHEME == SCH_SYM) post[t] = (float)__builtin_bit_cast(_Float16, L.scales[nbase + t]);
+                bias[t] = (L.bias && !partial) ? (float)__builtin_bit_cast(_Float16, L.bias[nbase + t]) : 0.0f;
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int tok = m0 + 16 * mt + 4 * kq + v;
+                    if (tok >= M) continue;
+                    float val[RT];
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) {
+                        float a = acc[t][mt][v];
+                        if constexpr (POST && SCHEME == SCH_SYM) a = a * 16777216.0f - 128.0f * xsum[mt][v];   // undo 2^-24 and the +128 offset
+                        val[t] = a * post[t];
+                    }
+                    if (!partial) {
+                        typedef _Float16 hv __attribute__((ext_vector_type(RT)));
+                        hv o;
+#pragma unroll
+                        for (int t = 0; t < RT; ++t) o[t] = (_Float16)(val[t] + bias[t]);
+                        *reinterpret_cast<hv*>(L.y + (size_t)tok * L.N + nbase) = o;
+                    } else {
+                        typedef float fv __attribute__((ext_vector_type(RT)));
+                        fv o;
+#pragma unroll
+                        for (int t = 0; t < RT; ++t) o[t] = val[t];
+                        *reinterpret_cast<fv*>(partial + (size_t)(tok - m0) * (WAVES * 64) + (nbase - (long)sb * (WAVES * 16 * RT))) = o;
+                    }
+                }
+        }
+        clear_acc();
+    };
+
+    // ---- main loop over chunks; loads for slot i + STAGES are issued right after slot i is consumed,
+    // whether that slot lies in this chunk or in the next one (possibly of the next unit)
+    Chunk cur = first_chunk(s_begin), nxt = next_chunk(cur);
+    load_x_chunk(cur);
+#pragma unroll
+    for (int i = 0; i < STAGES; ++i)
+        if (i < cur.n) issue(st[i], cur.sb, cur.kt0 + i);      // slots past a short chunk stay empty
     store_x_chunk(0);
     __syncthreads();
     int buf = 0;
-    for (int kt = kt_begin; kt < kt_end; kt += CHUNK) {
-        const bool more = kt + CHUNK < kt_end;
-        if (more) load_x_chunk(kt + CHUNK);
-        if (active) {
+    while (cur.n > 0) {
+        if (nxt.n > 0) load_x_chunk(nxt);
+        const bool active = row_block(cur.sb) < L.row_blocks;
+        if (cur.n == CHUNK && active && nxt.n >= STAGES) {
+            // steady state: a full chunk followed by enough steps to refill every slot -- no
+            // per-step conditions, so the whole chunk is one schedulable block
 #pragma unroll
-            for (int s = 0; s < CHUNK; ++s) {
-                if (kt + s < kt_end) {
-                    compute(st[s % STAGES], buf, s);
-                    issue(st[s % STAGES], kt + s + STAGES);
-                }
+            for (int i = 0; i < CHUNK; ++i) {
+                compute(st[i % STAGES], buf, i);
+                const int q = i + STAGES;                   // slot to refill
+                if (q < CHUNK) issue(st[i % STAGES], cur.sb, cur.kt0 + q);
+                else           issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - CHUNK));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CHUNK; ++i) {
+                if (i < cur.n && active) compute(st[i % STAGES], buf, i);
+                const int q = i + STAGES;
+                if (q < CHUNK) { if (q < cur.n) issue(st[i % STAGES], cur.sb, cur.kt0 + q); }
+                else           { if (q - CHUNK < nxt.n) issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - CHUNK)); }
             }
         }
-        if (more) store_x_chunk(buf ^ 1);
+        const bool unit_ends = cur.kt0 + cur.n == KT || nxt.n == 0;
+        if (unit_ends) {
+            const long u0 = (long)cur.sb * KT;               // the unit's first step
+            const bool whole = u0 >= s_begin && u0 + KT <= s_end;
+            finish_unit(cur.sb, whole ? nullptr : (u0 < s_begin ? slot_first : slot_last));
+        }
+        if (nxt.n > 0) store_x_chunk(buf ^ 1);
         __syncthreads();
         buf ^= 1;
+        cur = nxt;
+        nxt = next_chunk(nxt);
     }
-    if (!active) return;
-
-    // ---- epilogue: lane holds tokens 4*kq + v of RT consecutive rows starting at nbase
-    const long nbase = (RT == 4) ? rb * 64 + 4 * r : (rb >> 1) * 64 + 4 * r + 2 * (rb & 1);
-    float post[RT], bias[RT];
-#pragma unroll
-    for (int t = 0; t < RT; ++t) {
-        post[t] = 1.0f;
-        if constexpr (SCHEME == SCH_SYM) post[t] = (float)__builtin_bit_cast(_Float16, L.scales[nbase + t]);
-        bias[t] = (L.bias && L.ksplit == 1) ? (float)__builtin_bit_cast(_Float16, L.bias[nbase + t]) : 0.0f;
-    }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int tok = m0 + 16 * mt + 4 * kq + v;
-            if (tok >= M) continue;
-            float val[RT];
-#pragma unroll
-            for (int t = 0; t < RT; ++t) {
-                float a = acc[t][mt][v];
-                if constexpr (POST && SCHEME == SCH_SYM) a = a * 16777216.0f - 128.0f * xsum[mt][v];   // undo 2^-24 and the +128 offset
-                val[t] = a * post[t];
-            }
-            if (L.ksplit == 1) {
-                typedef _Float16 hv __attribute__((ext_vector_type(RT)));
-                hv o;
-#pragma unroll
-                for (int t = 0; t < RT; ++t) o[t] = (_Float16)(val[t] + bias[t]);
-                *reinterpret_cast<hv*>(L.y + (size_t)tok * L.N + nbase) = o;
-            } else {
-                typedef float fv __attribute__((ext_vector_type(RT)));
-                fv o;
-#pragma unroll
-                for (int t = 0; t < RT; ++t) o[t] = val[t];
-                *reinterpret_cast<fv*>(L.partial + ((size_t)split * M + tok) * L.N + nbase) = o;
-            }
-        }
 }
 
-template <int MT>
-__global__ __launch_bounds__(256, 2) void decode_kernel(const DecodeArgs a)
+// Position of a workgroup's range in the weighted step list.
+struct Cursor {
+    int li;          // linear
+    long step;       // block step inside the linear: sb * KT + kt
+};
+
+// first step whose start offset is >= pos (pos <= total weight)
+__device__ __forceinline__ Cursor first_step_at(const DecodeArgs& a, uint64_t pos)
+{
+    int li = 0;
+    while (li + 1 < a.n_lin && a.lin[li + 1].cum_weight <= pos) ++li;
+    const LinDesc& L = a.lin[li];
+    const uint64_t off = pos - L.cum_weight;
+    Cursor c = {li, (long)((off + L.step_weight - 1) / L.step_weight)};
+    return c;
+}
+
+__device__ __forceinline__ uint64_t range_begin(const DecodeArgs& a, int b)
+{
+    return a.total_weight * (uint64_t)b / (uint64_t)a.n_blocks;      // total_weight < 2^50, b < 2^13
+}
+
+template <int MT, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const DecodeArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     DecodeSmem<MT>& sm = *reinterpret_cast<DecodeSmem<MT>*>(smem_raw);
-    const int unit_global = blockIdx.x;
-    int li = 0;
-    while (li + 1 < a.n_lin && a.lin[li + 1].unit_begin <= unit_global) ++li;
-    const LinDesc& L = a.lin[li];
-    const int unit = unit_global - L.unit_begin;
-    switch (L.variant) {
-    case V_W3: run_unit<V_W3, MT>(L, a.M, a.m0, unit, sm); break;
-    case V_W4: run_unit<V_W4, MT>(L, a.M, a.m0, unit, sm); break;
-    case V_W8: run_unit<V_W8, MT>(L, a.M, a.m0, unit, sm); break;
-    case V_I8: run_unit<V_I8, MT>(L, a.M, a.m0, unit, sm); break;
-    default:   run_unit<V_F16, MT>(L, a.M, a.m0, unit, sm); break;
+    const int b = blockIdx.x;
+    const uint64_t lo = range_begin(a, b), hi = range_begin(a, b + 1);
+    Cursor c = first_step_at(a, lo);
+    float* slot_first = a.partial + (size_t)(2 * b) * a.slot_floats;
+    float* slot_last = slot_first + a.slot_floats;
+    while (c.li < a.n_lin) {
+        const LinDesc& L = a.lin[c.li];
+        const long steps = (long)L.row_superblocks * (L.K / 128);
+        if (c.step >= steps) { ++c.li; c.step = 0; continue; }
+        const uint64_t start = L.cum_weight + (uint64_t)c.step * L.step_weight;
+        if (start >= hi) break;
+        const long budget = (long)((hi - start + L.step_weight - 1) / L.step_weight);      // steps of this range from here
+        const long s_end = min(steps, c.step + budget);
+        switch (L.variant) {
+        case V_W3: run_range<V_W3, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        case V_W4: run_range<V_W4, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        case V_W8: run_range<V_W8, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        case V_I8: run_range<V_I8, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        default:   run_range<V_F16, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        }
+        c.step = s_end;
     }
 }
 
-// y[m][n] = fp16(sum_s partial[s][m][n] + bias[n]), s ascending; 256 threads x 4 columns per block
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const DecodeArgs a)
+// Fix-up: workgroup b looks at the boundary between ranges b and b+1.  If it is the first boundary
+// that cuts a unit, this workgroup adds that unit's pieces (range b's last segment, then the first
+// segments of ranges b+1, b+2, ... until the unit ends), adds the bias and stores fp16.
+__global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
 {
-    int li = -1;
-    for (int i = 0; i < a.n_lin; ++i)
-        if (a.lin[i].ksplit > 1 && a.lin[i].red_begin <= (int)blockIdx.x) li = i;
-    if (li < 0) return;
-    const LinDesc& L = a.lin[li];
-    const int m_lo = a.m0, m_cnt = min(64, a.M - a.m0);
-    const long per_row = L.N / 4;
-    const long idx = ((long)blockIdx.x - L.red_begin) * 256 + threadIdx.x;
-    if (idx >= per_row * m_cnt) return;
-    const int tok = m_lo + (int)(idx / per_row);
-    const long n = (idx % per_row) * 4;
-    f4 s = {0, 0, 0, 0};
-    for (int k = 0; k < L.ksplit; ++k) s += *reinterpret_cast<const f4*>(L.partial + ((size_t)k * a.M + tok) * L.N + n);
-    if (L.bias)
+    const int b = blockIdx.x;                       // 0 .. n_blocks - 2
+    const uint64_t X = range_begin(a, b + 1);
+    const Cursor c = first_step_at(a, X);
+    const LinDesc& L = a.lin[c.li];
+    const int KT = L.K / 128;
+    const long steps = (long)L.row_superblocks * KT;
+    if (c.step >= steps || c.step % KT == 0) return;            // boundary falls between units
+    const int sb = (int)(c.step / KT);
+    const uint64_t unit_begin = L.cum_weight + (uint64_t)sb * KT * L.step_weight;
+    if (range_begin(a, b) > unit_begin) return;                 // an earlier boundary already cuts this unit
+    const uint64_t unit_end = unit_begin + (uint64_t)KT * L.step_weight;     // start offset of the next unit
+    // pieces: slot 2b+1, then slot 2b' for b' = b+1 .. while range b' starts before the unit's last step ends
+    const int rows_wg = a.waves * decode_rows_per_wave(L.variant);      // rows of W per workgroup in this linear
+    const int stride = a.waves * 64;                                    // floats per token row of a partial tile
+    const long nbase = (long)sb * rows_wg;
+    const int m_cnt = min(64, a.M - a.m0);
+    for (int idx = threadIdx.x; idx < m_cnt * (rows_wg / 4); idx += 256) {
+        const int tok = idx / (rows_wg / 4), n4 = (idx % (rows_wg / 4)) * 4;
+        if (nbase + n4 >= L.N) continue;
+        const size_t o = (size_t)tok * stride + n4;
+        f4 s = *reinterpret_cast<const f4*>(a.partial + (size_t)(2 * b + 1) * a.slot_floats + o);
+        for (int bb = b + 1; bb < a.n_blocks; ++bb) {
+            const uint64_t lo = range_begin(a, bb);
+            // range bb holds a piece of this unit iff its first step starts before the unit's end
+            const uint64_t first = L.cum_weight + (uint64_t)((lo - L.cum_weight + L.step_weight - 1) / L.step_weight) * L.step_weight;
+            if (first >= unit_end) break;
+            if (first >= range_begin(a, bb + 1)) continue;      // empty range: it wrote nothing
+            s += *reinterpret_cast<const f4*>(a.partial + (size_t)(2 * bb) * a.slot_floats + o);
+        }
+        if (L.bias)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) s[v] += (float)__builtin_bit_cast(_Float16, L.bias[n + v]);
-    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-    h4 o = {(_Float16)s[0], (_Float16)s[1], (_Float16)s[2], (_Float16)s[3]};
-    *reinterpret_cast<h4*>(L.y + (size_t)tok * L.N + n) = o;
+            for (int v = 0; v < 4; ++v) s[v] += (float)__builtin_bit_cast(_Float16, L.bias[nbase + n4 + v]);
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        h4 out = {(_Float16)s[0], (_Float16)s[1], (_Float16)s[2], (_Float16)s[3]};
+        *reinterpret_cast<h4*>(L.y + (size_t)(a.m0 + tok) * L.N + nbase + n4) = out;
+    }
 }
 
 }  // namespace
 
-template <int MT>
+template <int MT, int WAVES>
 static hipError_t launch_mt(const DecodeArgs& a, hipStream_t s)
 {
     static bool attr_set = false;      // the slab is just over the 64 KB that needs no opt-in
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<MT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<MT, WAVES>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(DecodeSmem<MT>));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    decode_kernel<MT><<<(unsigned)a.total_units, 256, sizeof(DecodeSmem<MT>), s>>>(a);
+    decode_kernel<MT, WAVES><<<(unsigned)a.n_blocks, 64 * WAVES, sizeof(DecodeSmem<MT>), s>>>(a);
     return hipGetLastError();
 }
 
-hipError_t launch_decode(const DecodeArgs& a, int n_red_blocks, hipStream_t s)
+template <int WAVES>
+static hipError_t launch_waves(const DecodeArgs& a, hipStream_t s)
 {
     const int rows = a.M - a.m0;
-    hipError_t e = rows <= 16 ? launch_mt<1>(a, s) : rows <= 32 ? launch_mt<2>(a, s) : rows <= 48 ? launch_mt<3>(a, s) : launch_mt<4>(a, s);
+    return rows <= 16 ? launch_mt<1, WAVES>(a, s) : rows <= 32 ? launch_mt<2, WAVES>(a, s)
+         : rows <= 48 ? launch_mt<3, WAVES>(a, s) : launch_mt<4, WAVES>(a, s);
+}
+
+hipError_t launch_decode(const DecodeArgs& a, hipStream_t s)
+{
+    hipError_t e = a.waves == 8 ? launch_waves<8>(a, s) : launch_waves<4>(a, s);
     if (e != hipSuccess) return e;
-    if (n_red_blocks > 0) {
-        splitk_reduce_kernel<<<(unsigned)n_red_blocks, 256, 0, s>>>(a);
+    if (a.n_blocks > 1) {
+        decode_fixup_kernel<<<(unsigned)(a.n_blocks - 1), 256, 0, s>>>(a);
         e = hipGetLastError();
     }
     return e;

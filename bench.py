@@ -118,6 +118,18 @@ def cpu_baseline(cfg, M, budget_rows=20480):
                       % (budget_rows, K, len(cfg["layers"]), M)}
 
 
+def traffic_from_profiles(cfg, M):
+    """HBM bytes per decode launch as measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
+    the copy calibration) and recorded in profiles/decode_traffic.json for this workload; None if absent."""
+    path = os.path.join(ROOT, "profiles", "decode_traffic.json")
+    try:
+        rec = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    key = "%s/M=%d" % (cfg["name"], M)
+    return rec.get(key)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -127,6 +139,8 @@ def main():
     ap.add_argument("--decode-m", type=int, default=None)
     ap.add_argument("--only", choices=["all", "decode", "prefill"], default="all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy 3 times, so a --pmc run can scale FETCH_SIZE / WRITE_SIZE by it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (pipeline stages are independent units; "
@@ -178,6 +192,17 @@ def main():
         if args.only == "prefill":
             out.update({"metric": "prefill TFLOP/s", "unit": "TFLOP/s", "value": out["prefill"]["value"],
                         "ms_per_step": ms, "steps": psteps, "warmup": pwarm, "roofline": out["prefill"]["roofline"]})
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=device).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 3}
+    measured = traffic_from_profiles(cfg, Md)
+    if measured and "roofline" in out and out["roofline"]["kernel"] == "decode_kernel":
+        out["roofline"]["traffic"] = measured["bytes_per_launch"]
+        out["roofline"]["traffic_source"] = measured["source"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, Md)
     print(json.dumps(out))

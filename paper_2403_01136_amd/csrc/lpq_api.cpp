@@ -192,6 +192,46 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
     return LPQ_OK;
 }
 
+// Prefill-phase dispatch of a list of independent linears: one grouped launch per storage variant
+// (and per MAX_PREFILL_LIN linears), tiles of the longest-K linears first.
+lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream)
+{
+    const int BM = prefill_tokens_per_tile();
+    const int m_blocks = (M + BM - 1) / BM;
+    for (int variant = 0; variant < 5; ++variant) {
+        std::vector<const LinearCall*> mine;
+        for (const LinearCall& c : calls)
+            if (variant_of(c.w->d) == variant) mine.push_back(&c);
+        std::stable_sort(mine.begin(), mine.end(), [](const LinearCall* a, const LinearCall* b) { return a->w->d.K > b->w->d.K; });
+        for (size_t first = 0; first < mine.size(); first += MAX_PREFILL_LIN) {
+            PrefillArgs a;
+            a.M = M;
+            a.n_lin = 0;
+            a.pad = 0;
+            long tiles = 0;
+            for (size_t i = first; i < std::min(mine.size(), first + (size_t)MAX_PREFILL_LIN); ++i) {
+                const lpq_qweight& w = *mine[i]->w;
+                PrefillLin& L = a.lin[a.n_lin++];
+                L.codes = static_cast<const uint8_t*>(w.codes);
+                L.scales = static_cast<const uint16_t*>(w.scales);
+                L.zeros = static_cast<const uint16_t*>(w.zeros);
+                L.x = static_cast<const uint16_t*>(mine[i]->x);
+                L.y = static_cast<uint16_t*>(mine[i]->y);
+                L.bias = static_cast<const uint16_t*>(w.bias);
+                L.K = w.d.K;
+                L.N = w.d.N;
+                L.n_blocks = (w.d.N + 255) / 256;
+                L.tile_begin = (int32_t)tiles;
+                tiles += (long)L.n_blocks * m_blocks;
+            }
+            if (tiles > 0x7fffffffL) return LPQ_ERR_UNSUPPORTED;
+            a.total_tiles = (int32_t)tiles;
+            if (launch_prefill(variant, a, stream) != hipSuccess) return LPQ_ERR_DEVICE;
+        }
+    }
+    return LPQ_OK;
+}
+
 }  // namespace
 }  // namespace lpq
 
@@ -239,7 +279,8 @@ lpq_status lpq_qlinear_prefill(const lpq_qweight* w, const void* x, int32_t M, v
 {
     lpq_status st = check_linear(w, x, M, y);
     if (st != LPQ_OK) return st;
-    return launch_prefill(*w, x, M, y, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPQ_OK : LPQ_ERR_DEVICE;
+    std::vector<LinearCall> calls(1, LinearCall{w, x, y});
+    return run_prefill(calls, M, static_cast<hipStream_t>(hip_stream));
 }
 
 lpq_status lpq_qlinear_decode(const lpq_qweight* w, const void* x, int32_t M, void* y, void* hip_stream)
@@ -269,10 +310,7 @@ lpq_status lpq_stage_linears(const lpq_layer* layers, int32_t n_layers, lpq_phas
         }
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (phase == LPQ_DECODE) return run_decode(calls, M, stream);
-    for (const LinearCall& c : calls)
-        if (launch_prefill(*c.w, c.x, M, c.y, stream) != hipSuccess) return LPQ_ERR_DEVICE;
-    return LPQ_OK;
+    return phase == LPQ_DECODE ? run_decode(calls, M, stream) : run_prefill(calls, M, stream);
 }
 
 const char* lpq_status_str(lpq_status status)

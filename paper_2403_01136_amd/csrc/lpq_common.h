@@ -39,6 +39,27 @@ struct DecodeArgs {
     LinDesc lin[MAX_LIN_PER_LAUNCH];
 };
 
+// One linear of a grouped prefill launch: its output is cut into tiles of BM tokens x 256 rows of W,
+// numbered tile_begin + mb * n_blocks + nb (row blocks fastest, so neighbours share activations).
+struct PrefillLin {
+    const uint8_t* codes;
+    const uint16_t* scales;
+    const uint16_t* zeros;
+    const uint16_t* x;
+    uint16_t* y;
+    const uint16_t* bias;
+    int32_t K, N;
+    int32_t tile_begin;     // first tile (workgroup) of this linear in the launch
+    int32_t n_blocks;       // ceil(N / 256)
+};
+
+enum { MAX_PREFILL_LIN = 60 };
+
+struct PrefillArgs {
+    int32_t n_lin, M, total_tiles, pad;
+    PrefillLin lin[MAX_PREFILL_LIN];
+};
+
 // rows of W one decode wavefront covers, per variant (fp16 rows are 4x-16x bigger, so fewer of them)
 __host__ __device__ inline int decode_rows_per_wave(int variant) { return variant == 4 ? 32 : 64; }
 
@@ -49,6 +70,7 @@ size_t tile_bytes_of(int variant);
 hipError_t launch_quantize_pack(const void* w, const lpq_qdesc& d, const lpq_qweight& out, hipStream_t s);
 hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
-hipError_t launch_prefill(const lpq_qweight& w, const void* x, int M, void* y, hipStream_t s);
+hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);
+int prefill_tokens_per_tile();
 
 }  // namespace lpq

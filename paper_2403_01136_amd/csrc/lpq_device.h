@@ -81,19 +81,30 @@ __device__ __forceinline__ h2 magic_to_int(uint32_t biased, int log2c)
     return pk_fma(as_h2(biased), splat(inv), splat(off));
 }
 
+// (x & mask) | magic in one VALU op.  The compiler splits this into v_and + v_or when both constants
+// are literals; with the mask in an SGPR and the magic in a VGPR it is a single v_and_or_b32.
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic_vgpr)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(magic_vgpr));
+    return r;
+}
+
 // out[j] = the lane's 8 operand values of MFMA step j, as integer-valued fp16 codes
 template <int V>
 __device__ __forceinline__ void unpack_codes(const WRaw<V>& w, h8 out[4])
 {
     constexpr uint32_t MAGIC = 0x64006400u;
+    uint32_t magic_v;                                   // the magic constant held in a VGPR (see and_or)
+    asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
     if constexpr (V == V_W4) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t q = w.q[j], t = q >> 8;
-            h2 p0 = magic_to_int((q & 0x000F000Fu) | MAGIC, 0);
-            h2 p1 = magic_to_int((q & 0x00F000F0u) | MAGIC, 4);
-            h2 p2 = magic_to_int((t & 0x000F000Fu) | MAGIC, 0);
-            h2 p3 = magic_to_int((t & 0x00F000F0u) | MAGIC, 4);
+            h2 p0 = magic_to_int(and_or(q, 0x000F000Fu, magic_v), 0);
+            h2 p1 = magic_to_int(and_or(q, 0x00F000F0u, magic_v), 4);
+            h2 p2 = magic_to_int(and_or(t, 0x000F000Fu, magic_v), 0);
+            h2 p3 = magic_to_int(and_or(t, 0x00F000F0u, magic_v), 4);
             h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
             out[j] = o;
         }
@@ -102,15 +113,15 @@ __device__ __forceinline__ void unpack_codes(const WRaw<V>& w, h8 out[4])
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
             const uint32_t q = w.q[i], t = q >> 9;
-            pr[5 * i + 0] = magic_to_int((q & 0x00070007u) | MAGIC, 0);
-            pr[5 * i + 1] = magic_to_int((q & 0x00380038u) | MAGIC, 3);
-            pr[5 * i + 2] = magic_to_int((q & 0x01C001C0u) | MAGIC, 6);
-            pr[5 * i + 3] = magic_to_int((t & 0x00070007u) | MAGIC, 0);
-            pr[5 * i + 4] = magic_to_int((t & 0x00380038u) | MAGIC, 3);
+            pr[5 * i + 0] = magic_to_int(and_or(q, 0x00070007u, magic_v), 0);
+            pr[5 * i + 1] = magic_to_int(and_or(q, 0x00380038u, magic_v), 3);
+            pr[5 * i + 2] = magic_to_int(and_or(q, 0x01C001C0u, magic_v), 6);
+            pr[5 * i + 3] = magic_to_int(and_or(t, 0x00070007u, magic_v), 0);
+            pr[5 * i + 4] = magic_to_int(and_or(t, 0x00380038u, magic_v), 3);
         }
-        uint32_t u = ((w.q[0] >> 15) & 0x00010001u) | MAGIC;
-        u |= (w.q[1] >> 14) & 0x00020002u;
-        u |= (w.q[2] >> 13) & 0x00040004u;
+        uint32_t u = and_or(w.q[0] >> 15, 0x00010001u, magic_v);
+        u = and_or(w.q[1] >> 14, 0x00020002u, u);
+        u = and_or(w.q[2] >> 13, 0x00040004u, u);
         pr[15] = magic_to_int(u, 0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -195,5 +206,25 @@ __device__ __forceinline__ void apply_scale_zero(h8 v[4], _Float16 s, _Float16 z
 }
 
 __device__ __forceinline__ f4 mfma16(h8 a, h8 b, f4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+
+// 32x32x16 runs the matrix cores at twice the rate of 16x16x32 (measured: 2.4 vs 1.2 PFLOP/s), so the
+// compute-bound kernels use it.  Its B operand wants lane = row % 32 + 32 * (k half); two tiles in
+// the 16x16x32 layout (lane = row % 16 + 16 * kq) become two such operands with one
+// v_permlane16_swap per register: afterwards `lo` holds {tile a kq0, tile b kq0, tile a kq2, tile b kq2}
+// and `hi` holds {tile a kq1, tile b kq1, tile a kq3, tile b kq3}, i.e. 32 rows x (k slots kq, kq+2).
+typedef float f16x __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ f16x mfma32(h8 a, h8 b, f16x c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ void pair_tiles_for_mfma32(h8& a, h8& b)
+{
+    u32x4 ua = __builtin_bit_cast(u32x4, a), ub = __builtin_bit_cast(u32x4, b);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const u32x2 s = __builtin_amdgcn_permlane16_swap(ua[i], ub[i], false, false);
+        ua[i] = s[0];
+        ub[i] = s[1];
+    }
+    a = __builtin_bit_cast(h8, ua);
+    b = __builtin_bit_cast(h8, ub);
+}
 
 }  // namespace lpq

@@ -2,11 +2,23 @@
 // arXiv 2403.01136, Sec. 4.1 "Latency Cost Model": the prefill phase is bound by FLOPs;
 // Sec. 4.3: prefill micro-batch eta, prompt length s).
 //
+// One launch covers every linear of a stage that shares a storage variant: the launch's workgroups
+// are the BM x 256 output tiles of all those linears, longest K first, so the chip stays full until
+// the last few tiles instead of draining at the end of every linear.
+//
 // A workgroup of four wavefronts computes a BM x 256 block of y.  Each wave owns one 64-row
 // block of W (four 16-row tiles) for all BM tokens, so packed weight tiles go straight from
 // global memory into that wave's registers in MFMA operand order, are dequantised there once per
 // 128-column step (scale * code + zero, one fp16 rounding) and never touch LDS.  The activations
-// of the block are shared by the four waves through a double-buffered, padded LDS slab.
+// of the block are shared by the four waves through a double-buffered LDS slab that is filled by
+// direct global-to-LDS loads (no staging registers, no LDS store instructions); rows are 256 bytes
+// apart and the 16-byte column index is XOR-ed with the row index, so the 16-byte operand reads
+// of 16 consecutive token rows fall on 16 different bank groups.  The matrix instruction is
+// v_mfma_f32_32x32x16_f16 (twice the rate of 16x16x32 on this chip): tiles t and t+2 of the wave's
+// block are paired into 32-row operands with v_permlane16_swap after dequantisation, so a lane ends
+// up with two consecutive output rows per token.  Registers are kept under 256
+// per lane so that two workgroups share a CU and one's barrier and dequantisation overlap the
+// other's matrix instructions.
 #include "lpq_common.h"
 #include "lpq_device.h"
 
@@ -15,154 +27,178 @@ namespace lpq {
 namespace {
 
 template <int BM> struct PrefillSmem {
-    enum { ROW_HALVES = 128 + 8 };                 // +16 bytes per row: conflict-free 16-byte operand reads
-    uint16_t x[2][BM][ROW_HALVES];
+    uint16_t x[2][BM][128];        // [buffer][token row][column, 16-byte groups swizzled by row & 15]
 };
 
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
 template <int V, int BM>
-__global__ __launch_bounds__(256) void prefill_kernel(const uint8_t* __restrict__ codes, const uint16_t* __restrict__ scales,
-                                                      const uint16_t* __restrict__ zeros, const uint16_t* __restrict__ x,
-                                                      uint16_t* __restrict__ y, const uint16_t* __restrict__ bias,
-                                                      int M, int K, int N)
+__global__ __launch_bounds__(256, (V == V_F16) ? 1 : 2)
+void prefill_kernel(const PrefillArgs a)
 {
+    int li = 0;
+    while (li + 1 < a.n_lin && a.lin[li + 1].tile_begin <= (int)blockIdx.x) ++li;
+    const PrefillLin& L = a.lin[li];
+    const uint8_t* __restrict__ codes = L.codes;
+    const uint16_t* __restrict__ scales = L.scales;
+    const uint16_t* __restrict__ zeros = L.zeros;
+    const uint16_t* __restrict__ x = L.x;
+    uint16_t* __restrict__ y = L.y;
+    const uint16_t* __restrict__ bias = L.bias;
+    const int M = a.M, K = L.K, N = L.N;
+    const int tile = (int)blockIdx.x - L.tile_begin;
+    const int tile_m = tile / L.n_blocks, tile_n = tile % L.n_blocks;
     constexpr int SCHEME = VInfo<V>::SCHEME;
     constexpr int NW = 4;                           // 16-row tiles per wave = one 64-row block
-    constexpr int MTB = BM / 16;                    // token tiles per block
-    constexpr int XV = BM * 128 / 8 / 256;          // 16-byte pieces of the x slab per thread
+    constexpr int MTB = BM / 32;                    // 32-token tiles per block
+    constexpr int XQ = BM / 16;                     // 1 KB global-to-LDS loads per wave and slab (4 rows each)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     PrefillSmem<BM>& sm = *reinterpret_cast<PrefillSmem<BM>*>(smem_raw);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = lane & 15, kq = lane >> 4;
+    const int r = lane & 15;
     const int KT = K / 128;
     const long RB = N / 64;                          // 64-row blocks of W
-    const int m0 = blockIdx.y * BM;
-    const long rb = (long)blockIdx.x * 4 + wave;     // this wave's row block
+    const int m0 = tile_m * BM;
+    const long rb = (long)tile_n * 4 + wave;         // this wave's row block
     const bool active = rb < RB;                     // idle waves still stage activations
     const long rbc = active ? rb : RB - 1;
 
-    f4 acc[NW][MTB];
+    f16x acc[2][MTB];                                // [tile pair (t, t+2)][token tile]
 #pragma unroll
-    for (int t = 0; t < NW; ++t)
+    for (int p = 0; p < 2; ++p)
 #pragma unroll
-        for (int mt = 0; mt < MTB; ++mt) acc[t][mt] = f4{0, 0, 0, 0};
+        for (int mt = 0; mt < MTB; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[p][mt][v] = 0.0f;
 
-    // x slab: piece p = tid + 256*i covers token row p/16, 8 halves at column 8*(p%16)
-    u32x4 xr[XV];
-    auto load_x_slab = [&](int kt) {
+    // slab fill: wave-load q of this wave covers token rows 4*(XQ*wave + q) .. +3; lane (row = lane/16,
+    // slot = lane%16) fetches the 16-byte column group that belongs in that slot after swizzling.
+    // Token rows past M are clamped to row M-1: they only feed outputs that are never stored.
+    auto fill_x_slab = [&](int kt, int buf) {
 #pragma unroll
-        for (int i = 0; i < XV; ++i) {
-            const int p = tid + 256 * i, row = p >> 4, col = (p & 15) * 8;
-            const int tok = m0 + row;
-            u32x4 v = {0, 0, 0, 0};
-            if (tok < M) v = *reinterpret_cast<const u32x4*>(x + (long)tok * K + (long)kt * 128 + col);
-            xr[i] = v;
+        for (int q = 0; q < XQ; ++q) {
+            const int row0 = 4 * (XQ * wave + q), row = row0 + (lane >> 4);
+            const int c16 = (lane & 15) ^ (row & 15);
+            const int tok = min(m0 + row, M - 1);
+            const uint16_t* g = x + (size_t)tok * K + (size_t)kt * 128 + c16 * 8;
+            __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)&sm.x[buf][row0][0], 16, 0, 0);
         }
     };
-    auto store_x_slab = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < XV; ++i) {
-            const int p = tid + 256 * i, row = p >> 4, col = (p & 15) * 8;
-            *reinterpret_cast<u32x4*>(&sm.x[buf][row][col]) = xr[i];
-        }
+    struct WStep {
+        WRaw<V> raw[NW];
+        u32x2 s, z;                                  // fp16 scale / zero of the lane's four rows 4r..4r+3
     };
-    WRaw<V> wraw[NW];
-    u32x2 ws, wz;                                    // fp16 scale / zero of the lane's four rows 4r..4r+3
-    auto load_w = [&](int kt) {
+    auto load_w = [&](WStep& w, int kt) {
 #pragma unroll
-        for (int t = 0; t < NW; ++t) wraw[t] = load_tile<V>(codes, rbc, KT, kt, t, lane);
+        for (int t = 0; t < NW; ++t) w.raw[t] = load_tile<V>(codes, rbc, KT, kt, t, lane);
         if constexpr (SCHEME == SCH_ASYM) {
             const size_t idx = (size_t)kt * N + rbc * 64 + 4 * r;
-            ws = *reinterpret_cast<const u32x2*>(scales + idx);
-            wz = *reinterpret_cast<const u32x2*>(zeros + idx);
+            w.s = *reinterpret_cast<const u32x2*>(scales + idx);
+            w.z = *reinterpret_cast<const u32x2*>(zeros + idx);
         }
     };
 
-    load_x_slab(0);
-    load_w(0);
-    store_x_slab(0);
+    WStep wcur, wnext;
+    load_w(wcur, 0);
+    fill_x_slab(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the slab (and the first weights) have landed
     __syncthreads();
 
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
-        // dequantise this step's weight tiles, then start the next step's loads
+        // start the next step's loads before anything else (weights first, the slab last, so that the
+        // single wait before the barrier is also the wait the next step needs), then dequantise this
+        // step's tiles while they are in flight
+        if (kt + 1 < KT) { load_w(wnext, kt + 1); fill_x_slab(kt + 1, buf ^ 1); }
         h8 wb[NW][4];
 #pragma unroll
         for (int t = 0; t < NW; ++t) {
-            unpack_codes<V>(wraw[t], wb[t]);
+            unpack_codes<V>(wcur.raw[t], wb[t]);
             if constexpr (SCHEME == SCH_ASYM) {
-                const uint32_t sp = ws[t >> 1], zp = wz[t >> 1];
+                const uint32_t sp = wcur.s[t >> 1], zp = wcur.z[t >> 1];
                 const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
                 const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
                 apply_scale_zero(wb[t], __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
             }
         }
-        if (kt + 1 < KT) { load_x_slab(kt + 1); load_w(kt + 1); }
+        // pair tiles (0,2) and (1,3): wb[p][j] then covers k slots (kq 0, kq 2), wb[p+2][j] slots (kq 1, kq 3)
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pair_tiles_for_mfma32(wb[p][j], wb[p + 2][j]);
+        const int arow = lane & 31, ahalf = lane >> 5;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int mt = 0; mt < MTB; ++mt) {
-                const h8 a = *reinterpret_cast<const h8*>(&sm.x[buf][16 * mt + r][32 * j + 8 * kq]);
+                const int row = 32 * mt + arow;
+                const h8 a0 = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf) ^ (row & 15))]);
+                const h8 a1 = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf + 1) ^ (row & 15))]);
 #pragma unroll
-                for (int t = 0; t < NW; ++t) acc[t][mt] = mfma16(a, wb[t][j], acc[t][mt]);
+                for (int p = 0; p < 2; ++p) {
+                    acc[p][mt] = mfma32(a0, wb[p][j], acc[p][mt]);
+                    acc[p][mt] = mfma32(a1, wb[p + 2][j], acc[p][mt]);
+                }
             }
-        if (kt + 1 < KT) store_x_slab(buf ^ 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): next slab written before anyone reads it
         __syncthreads();
+        wcur = wnext;
     }
 
     if (!active) return;
-    // epilogue: lane holds tokens 4*kq + v of the four consecutive rows 64*rb + 4*r + t
-    const long nbase = rb * 64 + 4 * r;
-    float post[NW], bs[NW];
+    // epilogue: lane (n = lane%32, half = lane/32) holds, for pair p, output row 64*rb + 4*(n%16) + 2*(n/16) + p
+    // and tokens 32*mt + 8*(v/4) + 4*half + v%4: two consecutive rows per token -> 4-byte stores
+    const int ncol = lane & 31, thalf = lane >> 5;
+    const long nbase = rb * 64 + 4 * (ncol & 15) + 2 * (ncol >> 4);
+    float post[2], bs[2];
 #pragma unroll
-    for (int t = 0; t < NW; ++t) {
-        post[t] = 1.0f;
-        if constexpr (SCHEME == SCH_SYM) post[t] = (float)__builtin_bit_cast(_Float16, scales[nbase + t]);
-        bs[t] = bias ? (float)__builtin_bit_cast(_Float16, bias[nbase + t]) : 0.0f;
+    for (int p = 0; p < 2; ++p) {
+        post[p] = 1.0f;
+        if constexpr (SCHEME == SCH_SYM) post[p] = (float)__builtin_bit_cast(_Float16, scales[nbase + p]);
+        bs[p] = bias ? (float)__builtin_bit_cast(_Float16, bias[nbase + p]) : 0.0f;
     }
-    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 #pragma unroll
     for (int mt = 0; mt < MTB; ++mt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int tok = m0 + 16 * mt + 4 * kq + v;
+        for (int v = 0; v < 16; ++v) {
+            const int tok = m0 + 32 * mt + 8 * (v / 4) + 4 * thalf + (v % 4);
             if (tok >= M) continue;
-            h4 o;
-#pragma unroll
-            for (int t = 0; t < NW; ++t) o[t] = (_Float16)(acc[t][mt][v] * post[t] + bs[t]);
-            *reinterpret_cast<h4*>(y + (size_t)tok * N + nbase) = o;
+            const h2 o = {(_Float16)(acc[0][mt][v] * post[0] + bs[0]), (_Float16)(acc[1][mt][v] * post[1] + bs[1])};
+            *reinterpret_cast<h2*>(y + (size_t)tok * N + nbase) = o;
         }
 }
 
+constexpr int PREFILL_BM = 128;
+
 template <int V>
-hipError_t launch_variant(const lpq_qweight& w, const void* x, int M, void* y, hipStream_t s)
+hipError_t launch_variant(const PrefillArgs& a, hipStream_t s)
 {
-    constexpr int BM = 128, BN = 256;
-    const dim3 grid((unsigned)((w.d.N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
-    const size_t smem = sizeof(PrefillSmem<BM>);
+    const size_t smem = sizeof(PrefillSmem<PREFILL_BM>);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<V, BM>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<V, PREFILL_BM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    prefill_kernel<V, BM><<<grid, 256, smem, s>>>(
-        static_cast<const uint8_t*>(w.codes), static_cast<const uint16_t*>(w.scales), static_cast<const uint16_t*>(w.zeros),
-        static_cast<const uint16_t*>(x), static_cast<uint16_t*>(y), static_cast<const uint16_t*>(w.bias), M, w.d.K, w.d.N);
+    prefill_kernel<V, PREFILL_BM><<<(unsigned)a.total_tiles, 256, smem, s>>>(a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_prefill(const lpq_qweight& w, const void* x, int M, void* y, hipStream_t s)
+int prefill_tokens_per_tile() { return PREFILL_BM; }
+
+hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s)
 {
-    switch (variant_of(w.d)) {
-    case V_W3: return launch_variant<V_W3>(w, x, M, y, s);
-    case V_W4: return launch_variant<V_W4>(w, x, M, y, s);
-    case V_W8: return launch_variant<V_W8>(w, x, M, y, s);
-    case V_I8: return launch_variant<V_I8>(w, x, M, y, s);
-    case V_F16: return launch_variant<V_F16>(w, x, M, y, s);
+    switch (variant) {
+    case V_W3: return launch_variant<V_W3>(a, s);
+    case V_W4: return launch_variant<V_W4>(a, s);
+    case V_W8: return launch_variant<V_W8>(a, s);
+    case V_I8: return launch_variant<V_I8>(a, s);
+    case V_F16: return launch_variant<V_F16>(a, s);
     default: return hipErrorInvalidValue;
     }
 }

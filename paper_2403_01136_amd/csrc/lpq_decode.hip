@@ -298,8 +298,11 @@ struct Cursor {
 // first step whose start offset is >= pos (pos <= total weight)
 __device__ __forceinline__ Cursor first_step_at(const DecodeArgs& a, uint64_t pos)
 {
-    int li = 0;
-    while (li + 1 < a.n_lin && a.lin[li + 1].cum_weight <= pos) ++li;
+    int li = 0, hi = a.n_lin - 1;                    // last linear whose cum_weight <= pos
+    while (li < hi) {
+        const int mid = (li + hi + 1) >> 1;
+        if (a.lin[mid].cum_weight <= pos) li = mid; else hi = mid - 1;
+    }
     const LinDesc& L = a.lin[li];
     const uint64_t off = pos - L.cum_weight;
     Cursor c = {li, (long)((off + L.step_weight - 1) / L.step_weight)};
@@ -356,30 +359,55 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
     const uint64_t unit_begin = L.cum_weight + (uint64_t)sb * KT * L.step_weight;
     if (range_begin(a, b) > unit_begin) return;                 // an earlier boundary already cuts this unit
     const uint64_t unit_end = unit_begin + (uint64_t)KT * L.step_weight;     // start offset of the next unit
-    // pieces: slot 2b+1, then slot 2b' for b' = b+1 .. while range b' starts before the unit's last step ends
+    // pieces: slot 2b+1, then slot 2b' for every later non-empty range b' whose first step lies in this unit
     const int rows_wg = a.waves * decode_rows_per_wave(L.variant);      // rows of W per workgroup in this linear
     const int stride = a.waves * 64;                                    // floats per token row of a partial tile
     const long nbase = (long)sb * rows_wg;
     const int m_cnt = min(64, a.M - a.m0);
-    for (int idx = threadIdx.x; idx < m_cnt * (rows_wg / 4); idx += 256) {
-        const int tok = idx / (rows_wg / 4), n4 = (idx % (rows_wg / 4)) * 4;
-        if (nbase + n4 >= L.N) continue;
-        const size_t o = (size_t)tok * stride + n4;
-        f4 s = *reinterpret_cast<const f4*>(a.partial + (size_t)(2 * b + 1) * a.slot_floats + o);
+    constexpr int PER_THREAD = 16;                                      // groups of 4 consecutive rows per thread and pass
+    const int n_items = m_cnt * (rows_wg / 4);
+    for (int base = 0; base < n_items; base += 256 * PER_THREAD) {
+        f4 sum[PER_THREAD];
+        size_t off[PER_THREAD];
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int idx = base + threadIdx.x + 256 * i;
+            const int tok = idx / (rows_wg / 4), n4 = (idx % (rows_wg / 4)) * 4;
+            off[i] = (size_t)tok * stride + n4;
+            sum[i] = f4{0, 0, 0, 0};
+        }
+        auto add_piece = [&](int slot) {       // all of a piece's loads are issued before the first add
+            const float* p = a.partial + (size_t)slot * a.slot_floats;
+            f4 v[PER_THREAD];
+#pragma unroll
+            for (int i = 0; i < PER_THREAD; ++i)
+                if (base + threadIdx.x + 256 * i < n_items) v[i] = *reinterpret_cast<const f4*>(p + off[i]);
+#pragma unroll
+            for (int i = 0; i < PER_THREAD; ++i)
+                if (base + threadIdx.x + 256 * i < n_items) sum[i] += v[i];
+        };
+        add_piece(2 * b + 1);
         for (int bb = b + 1; bb < a.n_blocks; ++bb) {
             const uint64_t lo = range_begin(a, bb);
-            // range bb holds a piece of this unit iff its first step starts before the unit's end
             const uint64_t first = L.cum_weight + (uint64_t)((lo - L.cum_weight + L.step_weight - 1) / L.step_weight) * L.step_weight;
             if (first >= unit_end) break;
             if (first >= range_begin(a, bb + 1)) continue;      // empty range: it wrote nothing
-            s += *reinterpret_cast<const f4*>(a.partial + (size_t)(2 * bb) * a.slot_floats + o);
+            add_piece(2 * bb);
         }
-        if (L.bias)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) s[v] += (float)__builtin_bit_cast(_Float16, L.bias[nbase + n4 + v]);
         typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-        h4 out = {(_Float16)s[0], (_Float16)s[1], (_Float16)s[2], (_Float16)s[3]};
-        *reinterpret_cast<h4*>(L.y + (size_t)(a.m0 + tok) * L.N + nbase + n4) = out;
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int idx = base + threadIdx.x + 256 * i;
+            if (idx >= n_items) continue;
+            const int tok = idx / (rows_wg / 4), n4 = (idx % (rows_wg / 4)) * 4;
+            if (nbase + n4 >= L.N) continue;
+            f4 sv = sum[i];
+            if (L.bias)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sv[v] += (float)__builtin_bit_cast(_Float16, L.bias[nbase + n4 + v]);
+            const h4 out = {(_Float16)sv[0], (_Float16)sv[1], (_Float16)sv[2], (_Float16)sv[3]};
+            *reinterpret_cast<h4*>(L.y + (size_t)(a.m0 + tok) * L.N + nbase + n4) = out;
+        }
     }
 }
 

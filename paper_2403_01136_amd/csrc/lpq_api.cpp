@@ -196,9 +196,9 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
 // (and per MAX_PREFILL_LIN linears), tiles of the longest-K linears first.
 lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream)
 {
-    const int BM = prefill_tokens_per_tile();
-    const int m_blocks = (M + BM - 1) / BM;
     for (int variant = 0; variant < 5; ++variant) {
+        const int BM = prefill_tokens_per_tile(variant);
+        const int m_blocks = (M + BM - 1) / BM;
         std::vector<const LinearCall*> mine;
         for (const LinearCall& c : calls)
             if (variant_of(c.w->d) == variant) mine.push_back(&c);

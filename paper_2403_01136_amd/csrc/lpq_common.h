@@ -71,6 +71,6 @@ hipError_t launch_quantize_pack(const void* w, const lpq_qdesc& d, const lpq_qwe
 hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);
-int prefill_tokens_per_tile();
+int prefill_tokens_per_tile(int variant);
 
 }  // namespace lpq

@@ -197,6 +197,26 @@ __device__ __forceinline__ void unpack_subnormal(const WRaw<V>& w, h8 out[4])
     }
 }
 
+// 8-bit codes: the operands of steps j = 2*half, 2*half + 1 come from one 16-byte piece
+template <int V>
+__device__ __forceinline__ void unpack_codes_half8(const WRaw<V>& w, int half, h8 out[2])
+{
+    static_assert(V == V_W8 || V == V_I8, "8-bit variants only");
+    constexpr uint32_t M8 = 0x64646464u;
+    const _Float16 off = (V == V_I8) ? (_Float16)1152.0f : (_Float16)1024.0f;   // 1024 (+128 for signed)
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+        uint32_t a = w.q[half][2 * jj], b = w.q[half][2 * jj + 1];
+        if constexpr (V == V_I8) { a ^= 0x80808080u; b ^= 0x80808080u; }
+        h2 p0 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00050004u)) - splat(off);
+        h2 p1 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00070006u)) - splat(off);
+        h2 p2 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00050004u)) - splat(off);
+        h2 p3 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00070006u)) - splat(off);
+        h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+        out[jj] = o;
+    }
+}
+
 // w~ = scale * code + zero with one fp16 rounding per weight (packed fma)
 __device__ __forceinline__ void apply_scale_zero(h8 v[4], _Float16 s, _Float16 z)
 {

@@ -34,7 +34,7 @@ typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 template <int V, int BM>
-__global__ __launch_bounds__(256, (V == V_F16) ? 1 : 2)
+__global__ __launch_bounds__(256, BM > 128 ? 1 : 2)
 void prefill_kernel(const PrefillArgs a)
 {
     int li = 0;
@@ -47,8 +47,23 @@ void prefill_kernel(const PrefillArgs a)
     uint16_t* __restrict__ y = L.y;
     const uint16_t* __restrict__ bias = L.bias;
     const int M = a.M, K = L.K, N = L.N;
+    // Tile order inside a linear: consecutive workgroup ids land on consecutive XCDs (8 of them, each
+    // with its own L2), so workgroup id % 8 picks the token block within a group of 8 and id / 8 walks
+    // the row blocks: every XCD then re-reads one token block's activations (which fit its L2) while
+    // streaming different weights, instead of all XCDs sharing all token blocks.
     const int tile = (int)blockIdx.x - L.tile_begin;
-    const int tile_m = tile / L.n_blocks, tile_n = tile % L.n_blocks;
+    const int m_blocks = (M + BM - 1) / BM;
+    int tile_m, tile_n;
+    const int grouped = (m_blocks / 8) * 8 * L.n_blocks;         // tiles of the full groups of 8 token blocks
+    if (tile < grouped) {
+        const int g = tile / (8 * L.n_blocks), q = tile % (8 * L.n_blocks);
+        tile_m = 8 * g + (q & 7);
+        tile_n = q >> 3;
+    } else {
+        const int q = tile - grouped;
+        tile_m = (m_blocks / 8) * 8 + q / L.n_blocks;
+        tile_n = q % L.n_blocks;
+    }
     constexpr int SCHEME = VInfo<V>::SCHEME;
     constexpr int NW = 4;                           // 16-row tiles per wave = one 64-row block
     constexpr int MTB = BM / 32;                    // 32-token tiles per block
@@ -86,62 +101,120 @@ void prefill_kernel(const PrefillArgs a)
             __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)&sm.x[buf][row0][0], 16, 0, 0);
         }
     };
+    // Packed weights of one 128-column step (3/4-bit codes) or of one 64-column half step (8-bit codes
+    // and fp16 weights, whose tiles split into per-half pieces and are two to four times the size), as
+    // loaded from global memory one (half) step ahead of their use.
+    constexpr bool HALF_LOADS = (V == V_F16 || V == V_W8 || V == V_I8);
     struct WStep {
-        WRaw<V> raw[NW];
+        WRaw<V> raw[NW];                             // HALF_LOADS: fp16 uses q[0], q[1]; 8-bit uses q[0]
         u32x2 s, z;                                  // fp16 scale / zero of the lane's four rows 4r..4r+3
     };
-    auto load_w = [&](WStep& w, int kt) {
+    auto load_w = [&](WStep& w, int kt, int half) {
+        if constexpr (V == V_F16) {
 #pragma unroll
-        for (int t = 0; t < NW; ++t) w.raw[t] = load_tile<V>(codes, rbc, KT, kt, t, lane);
-        if constexpr (SCHEME == SCH_ASYM) {
-            const size_t idx = (size_t)kt * N + rbc * 64 + 4 * r;
-            w.s = *reinterpret_cast<const u32x2*>(scales + idx);
-            w.z = *reinterpret_cast<const u32x2*>(zeros + idx);
+            for (int t = 0; t < NW; ++t) {
+                const uint8_t* tile = codes + (((size_t)rbc * KT + kt) * 4 + t) * 4096 + 2048 * half + 16 * lane;
+                w.raw[t].q[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile));
+                w.raw[t].q[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile + 1024));
+            }
+        } else if constexpr (HALF_LOADS) {           // 8-bit: piece `half` of each tile
+#pragma unroll
+            for (int t = 0; t < NW; ++t) {
+                const uint8_t* tile = codes + (((size_t)rbc * KT + kt) * 4 + t) * 2048 + 1024 * half + 16 * lane;
+                w.raw[t].q[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tile));
+            }
+            if constexpr (SCHEME == SCH_ASYM) {      // same group for both halves
+                const size_t idx = (size_t)kt * N + rbc * 64 + 4 * r;
+                w.s = *reinterpret_cast<const u32x2*>(scales + idx);
+                w.z = *reinterpret_cast<const u32x2*>(zeros + idx);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < NW; ++t) w.raw[t] = load_tile<V>(codes, rbc, KT, kt, t, lane);
+            if constexpr (SCHEME == SCH_ASYM) {
+                const size_t idx = (size_t)kt * N + rbc * 64 + 4 * r;
+                w.s = *reinterpret_cast<const u32x2*>(scales + idx);
+                w.z = *reinterpret_cast<const u32x2*>(zeros + idx);
+            }
+        }
+    };
+    // MFMA operands of steps j = 2*half, 2*half + 1 of tile t (the unused half of the unpacking is dead code)
+    auto operands = [&](const WStep& w, int t, int half, h8 out[2]) {
+        if constexpr (V == V_F16) {
+            out[0] = __builtin_bit_cast(h8, w.raw[t].q[0]);
+            out[1] = __builtin_bit_cast(h8, w.raw[t].q[1]);
+        } else if constexpr (V == V_W8 || V == V_I8) {
+            unpack_codes_half8<V>(w.raw[t], 0, out);
+            if constexpr (SCHEME == SCH_ASYM) {
+                const uint32_t sp = w.s[t >> 1], zp = w.z[t >> 1];
+                const _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu)));
+                const _Float16 zh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu)));
+                const h8 s8 = {sh, sh, sh, sh, sh, sh, sh, sh}, z8 = {zh, zh, zh, zh, zh, zh, zh, zh};
+                out[0] = __builtin_elementwise_fma(out[0], s8, z8);
+                out[1] = __builtin_elementwise_fma(out[1], s8, z8);
+            }
+        } else {
+            h8 all[4];
+            unpack_codes<V>(w.raw[t], all);
+            if constexpr (SCHEME == SCH_ASYM) {
+                const uint32_t sp = w.s[t >> 1], zp = w.z[t >> 1];
+                const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
+                const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
+                apply_scale_zero(all, __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
+            }
+            out[0] = all[2 * half];
+            out[1] = all[2 * half + 1];
         }
     };
 
     WStep wcur, wnext;
-    load_w(wcur, 0);
+    load_w(wcur, 0, 0);
     fill_x_slab(0, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the slab (and the first weights) have landed
     __syncthreads();
 
+    const int arow = lane & 31, ahalf = lane >> 5;
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
         // start the next step's loads before anything else (weights first, the slab last, so that the
-        // single wait before the barrier is also the wait the next step needs), then dequantise this
-        // step's tiles while they are in flight
-        if (kt + 1 < KT) { load_w(wnext, kt + 1); fill_x_slab(kt + 1, buf ^ 1); }
-        h8 wb[NW][4];
+        // single wait before the barrier is also the wait the next step needs); they land while this
+        // step's tiles are dequantised and multiplied
+        if constexpr (!HALF_LOADS) { if (kt + 1 < KT) load_w(wnext, kt + 1, 0); }
+        if (kt + 1 < KT) fill_x_slab(kt + 1, buf ^ 1);
 #pragma unroll
-        for (int t = 0; t < NW; ++t) {
-            unpack_codes<V>(wcur.raw[t], wb[t]);
-            if constexpr (SCHEME == SCH_ASYM) {
-                const uint32_t sp = wcur.s[t >> 1], zp = wcur.z[t >> 1];
-                const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
-                const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
-                apply_scale_zero(wb[t], __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
+        for (int half = 0; half < 2; ++half) {
+            if constexpr (HALF_LOADS) {
+                if (half == 0) load_w(wnext, kt, 1);
+                else if (kt + 1 < KT) load_w(wnext, kt + 1, 0);
             }
-        }
-        // pair tiles (0,2) and (1,3): wb[p][j] then covers k slots (kq 0, kq 2), wb[p+2][j] slots (kq 1, kq 3)
+            // dequantise two steps of each tile, pair tiles (0,2) and (1,3) into 32-row operands:
+            // wb[p] then covers k slots (kq 0, kq 2) and wb[p+2] slots (kq 1, kq 3)
+            h8 wb[NW][2];
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
+            for (int t = 0; t < NW; ++t) operands(wcur, t, half, wb[t]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) pair_tiles_for_mfma32(wb[p][j], wb[p + 2][j]);
-        const int arow = lane & 31, ahalf = lane >> 5;
+            for (int p = 0; p < 2; ++p)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+                for (int jj = 0; jj < 2; ++jj) pair_tiles_for_mfma32(wb[p][jj], wb[p + 2][jj]);
 #pragma unroll
-            for (int mt = 0; mt < MTB; ++mt) {
-                const int row = 32 * mt + arow;
-                const h8 a0 = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf) ^ (row & 15))]);
-                const h8 a1 = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf + 1) ^ (row & 15))]);
+            for (int jj = 0; jj < 2; ++jj) {
+                const int j = 2 * half + jj;
 #pragma unroll
-                for (int p = 0; p < 2; ++p) {
-                    acc[p][mt] = mfma32(a0, wb[p][j], acc[p][mt]);
-                    acc[p][mt] = mfma32(a1, wb[p + 2][j], acc[p][mt]);
+                for (int mt = 0; mt < MTB; ++mt) {
+                    const int row = 32 * mt + arow;
+                    const h8 a0 = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf) ^ (row & 15))]);
+                    const h8 a1 = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf + 1) ^ (row & 15))]);
+#pragma unroll
+                    for (int p = 0; p < 2; ++p) {
+                        acc[p][mt] = mfma32(a0, wb[p][jj], acc[p][mt]);
+                        acc[p][mt] = mfma32(a1, wb[p + 2][jj], acc[p][mt]);
+                    }
                 }
             }
+            if constexpr (HALF_LOADS) {
+                if (half == 0) { __builtin_amdgcn_s_waitcnt(0x0F70); wcur = wnext; }     // second half of this step
+            }
+        }
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): next slab written before anyone reads it
         __syncthreads();
         wcur = wnext;
@@ -170,26 +243,39 @@ void prefill_kernel(const PrefillArgs a)
         }
 }
 
-constexpr int PREFILL_BM = 128;
+// Tokens per tile.  Weight bytes are re-read from L2 once per token block, so the variants with the
+// most bytes per weight (8-bit codes, fp16) take 256-token tiles (one workgroup per CU, 256
+// accumulator registers); the others stay at 128 tokens and two workgroups per CU.
+template <int V> struct PrefillTile { enum { BM = (V == V_W3 || V == V_W4) ? 128 : 256 }; };
 
 template <int V>
 hipError_t launch_variant(const PrefillArgs& a, hipStream_t s)
 {
-    const size_t smem = sizeof(PrefillSmem<PREFILL_BM>);
+    constexpr int BM = PrefillTile<V>::BM;
+    const size_t smem = sizeof(PrefillSmem<BM>);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<V, PREFILL_BM>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<V, BM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    prefill_kernel<V, PREFILL_BM><<<(unsigned)a.total_tiles, 256, smem, s>>>(a);
+    prefill_kernel<V, BM><<<(unsigned)a.total_tiles, 256, smem, s>>>(a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-int prefill_tokens_per_tile() { return PREFILL_BM; }
+int prefill_tokens_per_tile(int variant)
+{
+    switch (variant) {
+    case V_W3: return PrefillTile<V_W3>::BM;
+    case V_W4: return PrefillTile<V_W4>::BM;
+    case V_W8: return PrefillTile<V_W8>::BM;
+    case V_I8: return PrefillTile<V_I8>::BM;
+    default: return PrefillTile<V_F16>::BM;
+    }
+}
 
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s)
 {

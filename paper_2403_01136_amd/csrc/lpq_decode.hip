@@ -26,14 +26,16 @@ namespace {
 // 3-4 KB per wave for 3/4-bit codes and 8 KB for 8-bit codes and fp16 rows, so 12-16 KB either way).
 template <int V> struct DecodeCfg { enum { RT = (V == V_F16) ? 2 : 4, DEPTH = (V == V_W3 || V == V_W4) ? 4 : 2 }; };
 
-// activation staging: CHUNK 128-column steps per LDS buffer
-template <int MT> struct PipeCfg {
-    enum { CHUNK = (MT == 1) ? 8 : (MT == 2) ? 4 : 2 };
+// A launch is specialised on TOK, the token rows it covers: 16 (M <= 16: 16x16x32 MFMA, scale and
+// zero applied after the matrix cores), 32 or 64 (32x32x16 MFMA at twice the matrix-core rate,
+// weights dequantised to fp16 in registers).  Activation staging: CHUNK 128-column steps per LDS buffer.
+template <int TOK> struct PipeCfg {
+    enum { CHUNK = (TOK == 16) ? 8 : (TOK == 32) ? 4 : 2 };
     enum { ROW_HALVES = CHUNK * 128 + 8 };          // +16 bytes: conflict-free 16-byte operand reads
-    enum { PIECES256 = MT * CHUNK };                // 16-byte pieces of a chunk per thread at 256 threads
+    enum { PIECES256 = TOK / 16 * CHUNK };          // 16-byte pieces of a chunk per thread at 256 threads
 };
 
-template <int MT> struct DecodeSmem { uint16_t x[2][16 * MT][PipeCfg<MT>::ROW_HALVES]; };
+template <int TOK> struct DecodeSmem { uint16_t x[2][TOK][PipeCfg<TOK>::ROW_HALVES]; };
 
 // A chunk: up to CHUNK consecutive 128-column steps of one (linear, row superblock) unit.
 struct Chunk {
@@ -45,13 +47,16 @@ struct Chunk {
 // the end of a unit the accumulators are stored -- as fp16 if the unit's whole K range lay inside
 // [s_begin, s_end), else as an fp32 partial tile in slot_first (the unit this range entered mid-way)
 // or slot_last (the unit it leaves mid-way) -- and cleared.
-template <int V, int MT, int WAVES>
+template <int V, int TOK, int WAVES>
 __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long s_begin, long s_end,
-                                          float* __restrict__ slot_first, float* __restrict__ slot_last, DecodeSmem<MT>& sm)
+                                          float* __restrict__ slot_first, float* __restrict__ slot_last, DecodeSmem<TOK>& sm)
 {
     constexpr int RT = DecodeCfg<V>::RT;
     constexpr int SCHEME = VInfo<V>::SCHEME;
-    constexpr int CHUNK = PipeCfg<MT>::CHUNK, PIECES = PipeCfg<MT>::PIECES256 * 4 / WAVES, THREADS = 64 * WAVES;
+    constexpr bool WIDE = TOK > 16;                 // 32x32x16 path
+    constexpr int MT = 1;                           // narrow path: one 16-token tile
+    constexpr int NP = RT / 2, MT2 = WIDE ? TOK / 32 : 1;      // wide path: tile pairs and 32-token tiles
+    constexpr int CHUNK = PipeCfg<TOK>::CHUNK, PIECES = PipeCfg<TOK>::PIECES256 * 4 / WAVES, THREADS = 64 * WAVES;
     constexpr int STAGES = DecodeCfg<V>::DEPTH < CHUNK ? DecodeCfg<V>::DEPTH : CHUNK;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, kq = lane >> 4;
@@ -76,8 +81,9 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     // the wave's row block in a unit; waves past the end of W idle but still stage activations
     auto row_block = [&](int sb) { return (long)sb * WAVES + wave; };
 
-    f4 acc[RT][MT];
-    f4 xsum[MT];                      // per-row scheme only: sum of x over the unit's K range
+    f4 acc[RT][MT];                   // narrow path
+    f4 xsum[MT];                      // narrow path, per-row scheme only: sum of x over the unit's K range
+    f16x accw[NP][MT2];               // wide path: [tile pair][32-token tile]
     auto clear_acc = [&]() {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -85,6 +91,12 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
 #pragma unroll
             for (int t = 0; t < RT; ++t) acc[t][mt] = f4{0, 0, 0, 0};
         }
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+            for (int m2 = 0; m2 < MT2; ++m2)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) accw[p][m2][v] = 0.0f;
     };
     clear_acc();
 
@@ -114,8 +126,47 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     // sum(x) from one extra MFMA against a block of ones -- the scale costs 8 fp32 FMAs per tile
     // instead of 16 packed FMAs plus the int -> fp16 conversions.  Otherwise (many tokens, where the
     // fp32 work would grow with M): dequantise each weight to fp16 once, w~ = scale * code + zero.
-    constexpr bool POST = (MT <= 2) && V != V_F16;
+    constexpr bool POST = !WIDE && V != V_F16;
     auto compute = [&](Stage& b, int buf, int step) {
+        if constexpr (WIDE) {
+            // dequantise two MFMA steps of every tile at a time, pair tiles (p, p + NP) into 32-row
+            // operands (wb[p] then holds k slots kq 0 and 2, wb[p + NP] slots kq 1 and 3), multiply
+            const int arow = lane & 31, ahalf = lane >> 5;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                h8 wb[RT][2];
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    unpack_codes_half<V>(b.w[t], half, wb[t]);
+                    if constexpr (SCHEME == SCH_ASYM) {
+                        const uint32_t sp = b.s[t >> 1], zp = b.z[t >> 1];
+                        const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
+                        const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
+                        apply_scale_zero_half(wb[t], __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
+                    }
+                }
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj) pair_tiles_for_mfma32(wb[p][jj], wb[p + NP][jj]);
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = 2 * half + jj;
+#pragma unroll
+                    for (int m2 = 0; m2 < MT2; ++m2) {
+                        const uint16_t* xrow = &sm.x[buf][32 * m2 + arow][step * 128 + 32 * j + 16 * ahalf];
+                        const h8 a0 = *reinterpret_cast<const h8*>(xrow);
+                        const h8 a1 = *reinterpret_cast<const h8*>(xrow + 8);
+#pragma unroll
+                        for (int p = 0; p < NP; ++p) {
+                            accw[p][m2] = mfma32(a0, wb[p][jj], accw[p][m2]);
+                            accw[p][m2] = mfma32(a1, wb[p + NP][jj], accw[p][m2]);
+                        }
+                    }
+                }
+            }
+            return;
+        }
         h8 wb[RT][4];
         if constexpr (POST) {
 #pragma unroll
@@ -203,7 +254,41 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     // ---- end of a unit: lane holds tokens 4*kq + v of RT consecutive rows starting at nbase
     auto finish_unit = [&](int sb, float* __restrict__ partial) {
         const long rb = row_block(sb);
-        if (rb < L.row_blocks) {
+        if (WIDE && rb < L.row_blocks) {
+            // lane (n = lane%32, half = lane/32) holds tokens 32*m2 + 8*(v/4) + 4*half + v%4 of NP consecutive rows:
+            // tile pair p of a 4-tile block is tiles (p, p+2), i.e. rows 4r + p (n < 16) and 4r + 2 + p (n >= 16)
+            const int ncol = lane & 31, thalf = lane >> 5;
+            const long nbase = (RT == 4) ? rb * 64 + 4 * (ncol & 15) + 2 * (ncol >> 4)
+                                         : (rb >> 1) * 64 + 4 * (ncol & 15) + 2 * (rb & 1) + (ncol >> 4);
+            float post[NP], bias[NP];
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                post[p] = 1.0f;
+                if constexpr (SCHEME == SCH_SYM) post[p] = (float)__builtin_bit_cast(_Float16, L.scales[nbase + p]);
+                bias[p] = (L.bias && !partial) ? (float)__builtin_bit_cast(_Float16, L.bias[nbase + p]) : 0.0f;
+            }
+#pragma unroll
+            for (int m2 = 0; m2 < MT2; ++m2)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int tok = m0 + 32 * m2 + 8 * (v / 4) + 4 * thalf + (v % 4);
+                    if (tok >= M) continue;
+                    if (!partial) {
+                        typedef _Float16 hv __attribute__((ext_vector_type(NP)));
+                        hv o;
+#pragma unroll
+                        for (int p = 0; p < NP; ++p) o[p] = (_Float16)(accw[p][m2][v] * post[p] + bias[p]);
+                        *reinterpret_cast<hv*>(L.y + (size_t)tok * L.N + nbase) = o;
+                    } else {
+                        typedef float fv __attribute__((ext_vector_type(NP)));
+                        fv o;
+#pragma unroll
+                        for (int p = 0; p < NP; ++p) o[p] = accw[p][m2][v] * post[p];
+                        *reinterpret_cast<fv*>(partial + (size_t)(tok - m0) * (WAVES * 64) + (nbase - (long)sb * (WAVES * 16 * RT))) = o;
+                    }
+                }
+        }
+        if (!WIDE && rb < L.row_blocks) {
             const long nbase = (RT == 4) ? rb * 64 + 4 * r : (rb >> 1) * 64 + 4 * r + 2 * (rb & 1);
             float post[RT], bias[RT];
 #pragma unroll
@@ -314,11 +399,11 @@ __device__ __forceinline__ uint64_t range_begin(const DecodeArgs& a, int b)
     return a.total_weight * (uint64_t)b / (uint64_t)a.n_blocks;      // total_weight < 2^50, b < 2^13
 }
 
-template <int MT, int WAVES>
+template <int TOK, int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const DecodeArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-    DecodeSmem<MT>& sm = *reinterpret_cast<DecodeSmem<MT>*>(smem_raw);
+    DecodeSmem<TOK>& sm = *reinterpret_cast<DecodeSmem<TOK>*>(smem_raw);
     const int b = blockIdx.x;
     const uint64_t lo = range_begin(a, b), hi = range_begin(a, b + 1);
     Cursor c = first_step_at(a, lo);
@@ -333,11 +418,11 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const Dec
         const long budget = (long)((hi - start + L.step_weight - 1) / L.step_weight);      // steps of this range from here
         const long s_end = min(steps, c.step + budget);
         switch (L.variant) {
-        case V_W3: run_range<V_W3, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
-        case V_W4: run_range<V_W4, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
-        case V_W8: run_range<V_W8, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
-        case V_I8: run_range<V_I8, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
-        default:   run_range<V_F16, MT, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        case V_W3: run_range<V_W3, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        case V_W4: run_range<V_W4, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        case V_W8: run_range<V_W8, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        case V_I8: run_range<V_I8, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        default:   run_range<V_F16, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
         }
         c.step = s_end;
     }
@@ -413,17 +498,17 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
 
 }  // namespace
 
-template <int MT, int WAVES>
-static hipError_t launch_mt(const DecodeArgs& a, hipStream_t s)
+template <int TOK, int WAVES>
+static hipError_t launch_tok(const DecodeArgs& a, hipStream_t s)
 {
     static bool attr_set = false;      // the slab is just over the 64 KB that needs no opt-in
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<MT, WAVES>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(DecodeSmem<MT>));
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<TOK, WAVES>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(DecodeSmem<TOK>));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    decode_kernel<MT, WAVES><<<(unsigned)a.n_blocks, 64 * WAVES, sizeof(DecodeSmem<MT>), s>>>(a);
+    decode_kernel<TOK, WAVES><<<(unsigned)a.n_blocks, 64 * WAVES, sizeof(DecodeSmem<TOK>), s>>>(a);
     return hipGetLastError();
 }
 
@@ -431,8 +516,7 @@ template <int WAVES>
 static hipError_t launch_waves(const DecodeArgs& a, hipStream_t s)
 {
     const int rows = a.M - a.m0;
-    return rows <= 16 ? launch_mt<1, WAVES>(a, s) : rows <= 32 ? launch_mt<2, WAVES>(a, s)
-         : rows <= 48 ? launch_mt<3, WAVES>(a, s) : launch_mt<4, WAVES>(a, s);
+    return rows <= 16 ? launch_tok<16, WAVES>(a, s) : rows <= 32 ? launch_tok<32, WAVES>(a, s) : launch_tok<64, WAVES>(a, s);
 }
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s)

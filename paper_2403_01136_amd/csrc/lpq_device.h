@@ -197,24 +197,76 @@ __device__ __forceinline__ void unpack_subnormal(const WRaw<V>& w, h8 out[4])
     }
 }
 
-// 8-bit codes: the operands of steps j = 2*half, 2*half + 1 come from one 16-byte piece
+// The same for two MFMA steps only (j = 2*half, 2*half + 1): the compute-bound kernels build their
+// operands half a 128-column step at a time to keep 32 instead of 64 operand registers live.
+// `piece8`: for the 8-bit variants, which of w.q[] holds the 16-byte piece of this half (callers that
+// load one piece at a time keep it in q[0]).
 template <int V>
-__device__ __forceinline__ void unpack_codes_half8(const WRaw<V>& w, int half, h8 out[2])
+__device__ __forceinline__ void unpack_codes_half(const WRaw<V>& w, int half, h8 out[2], int piece8 = -1)
 {
-    static_assert(V == V_W8 || V == V_I8, "8-bit variants only");
-    constexpr uint32_t M8 = 0x64646464u;
-    const _Float16 off = (V == V_I8) ? (_Float16)1152.0f : (_Float16)1024.0f;   // 1024 (+128 for signed)
+    constexpr uint32_t MAGIC = 0x64006400u;
+    uint32_t magic_v;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
+    if constexpr (V == V_W4) {
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj) {
-        uint32_t a = w.q[half][2 * jj], b = w.q[half][2 * jj + 1];
-        if constexpr (V == V_I8) { a ^= 0x80808080u; b ^= 0x80808080u; }
-        h2 p0 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00050004u)) - splat(off);
-        h2 p1 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00070006u)) - splat(off);
-        h2 p2 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00050004u)) - splat(off);
-        h2 p3 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00070006u)) - splat(off);
-        h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
-        out[jj] = o;
+        for (int jj = 0; jj < 2; ++jj) {
+            const uint32_t q = w.q[2 * half + jj], t = q >> 8;
+            h2 p0 = magic_to_int(and_or(q, 0x000F000Fu, magic_v), 0);
+            h2 p1 = magic_to_int(and_or(q, 0x00F000F0u, magic_v), 4);
+            h2 p2 = magic_to_int(and_or(t, 0x000F000Fu, magic_v), 0);
+            h2 p3 = magic_to_int(and_or(t, 0x00F000F0u, magic_v), 4);
+            h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+            out[jj] = o;
+        }
+    } else if constexpr (V == V_W3) {
+        h2 pr[8];                                   // pairs P = 8*half .. 8*half + 7
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int P = 8 * half + k;
+            if (P < 15) {
+                const int i = P / 5, f = P % 5, ff = f % 3;        // fields 3, 4 sit at bits 9, 12: shift them down first
+                const uint32_t src = (f >= 3) ? (w.q[i] >> 9) : w.q[i];
+                pr[k] = magic_to_int(and_or(src, 0x00070007u << (3 * ff), magic_v), 3 * ff);
+            } else {
+                uint32_t u = and_or(w.q[0] >> 15, 0x00010001u, magic_v);
+                u = and_or(w.q[1] >> 14, 0x00020002u, u);
+                u = and_or(w.q[2] >> 13, 0x00040004u, u);
+                pr[k] = magic_to_int(u, 0);
+            }
+        }
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            h8 o = {pr[4 * jj][0], pr[4 * jj][1], pr[4 * jj + 1][0], pr[4 * jj + 1][1],
+                    pr[4 * jj + 2][0], pr[4 * jj + 2][1], pr[4 * jj + 3][0], pr[4 * jj + 3][1]};
+            out[jj] = o;
+        }
+    } else if constexpr (V == V_W8 || V == V_I8) {
+        constexpr uint32_t M8 = 0x64646464u;
+        const _Float16 off = (V == V_I8) ? (_Float16)1152.0f : (_Float16)1024.0f;   // 1024 (+128 for signed)
+        const u32x4 piece = w.q[piece8 < 0 ? half : piece8];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            uint32_t a = piece[2 * jj], b = piece[2 * jj + 1];
+            if constexpr (V == V_I8) { a ^= 0x80808080u; b ^= 0x80808080u; }
+            h2 p0 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00050004u)) - splat(off);
+            h2 p1 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00070006u)) - splat(off);
+            h2 p2 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00050004u)) - splat(off);
+            h2 p3 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00070006u)) - splat(off);
+            h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+            out[jj] = o;
+        }
+    } else {
+        out[0] = __builtin_bit_cast(h8, w.q[2 * half]);
+        out[1] = __builtin_bit_cast(h8, w.q[2 * half + 1]);
     }
+}
+
+// w~ = scale * code + zero for the two operands of a half step
+__device__ __forceinline__ void apply_scale_zero_half(h8 v[2], _Float16 s, _Float16 z)
+{
+    const h8 s8 = {s, s, s, s, s, s, s, s}, z8 = {z, z, z, z, z, z, z, z};
+    v[0] = __builtin_elementwise_fma(v[0], s8, z8);
+    v[1] = __builtin_elementwise_fma(v[1], s8, z8);
 }
 
 // w~ = scale * code + zero with one fp16 rounding per weight (packed fma)

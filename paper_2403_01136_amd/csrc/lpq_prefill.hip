@@ -143,27 +143,14 @@ void prefill_kernel(const PrefillArgs a)
         if constexpr (V == V_F16) {
             out[0] = __builtin_bit_cast(h8, w.raw[t].q[0]);
             out[1] = __builtin_bit_cast(h8, w.raw[t].q[1]);
-        } else if constexpr (V == V_W8 || V == V_I8) {
-            unpack_codes_half8<V>(w.raw[t], 0, out);
-            if constexpr (SCHEME == SCH_ASYM) {
-                const uint32_t sp = w.s[t >> 1], zp = w.z[t >> 1];
-                const _Float16 sh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu)));
-                const _Float16 zh = __builtin_bit_cast(_Float16, (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu)));
-                const h8 s8 = {sh, sh, sh, sh, sh, sh, sh, sh}, z8 = {zh, zh, zh, zh, zh, zh, zh, zh};
-                out[0] = __builtin_elementwise_fma(out[0], s8, z8);
-                out[1] = __builtin_elementwise_fma(out[1], s8, z8);
-            }
         } else {
-            h8 all[4];
-            unpack_codes<V>(w.raw[t], all);
+            unpack_codes_half<V>(w.raw[t], half, out, 0);        // 8-bit pieces are loaded one at a time into q[0]
             if constexpr (SCHEME == SCH_ASYM) {
                 const uint32_t sp = w.s[t >> 1], zp = w.z[t >> 1];
                 const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
                 const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
-                apply_scale_zero(all, __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
+                apply_scale_zero_half(out, __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
             }
-            out[0] = all[2 * half];
-            out[1] = all[2 * half + 1];
         }
     };
 

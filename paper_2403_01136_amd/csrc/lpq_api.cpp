@@ -93,12 +93,14 @@ int env_int(const char* name, int fallback)
     return (e && *e) ? std::atoi(e) : fallback;
 }
 
-// Wavefronts per decode workgroup (4 or 8) and workgroups per launch as a multiple of what the chip
-// holds at once; both can be overridden for experiments.
-int decode_waves()
+// Wavefronts per decode workgroup: 4 for up to 16 token rows; 8 beyond, where the activation slab
+// is several times larger and one workgroup per CU shares it among twice the weight rows.  The
+// workgroups per launch are what the chip holds at once.  Both can be overridden for experiments.
+int decode_waves(int M)
 {
-    static const int v = env_int("LPQ_DECODE_WAVES", 4) == 8 ? 8 : 4;
-    return v;
+    static const int narrow = env_int("LPQ_DECODE_WAVES", 4) == 8 ? 8 : 4;
+    static const int wide = env_int("LPQ_DECODE_WAVES_WIDE", 8) == 4 ? 4 : 8;
+    return M <= 16 ? narrow : wide;
 }
 
 lpq_status decode_block_count(int waves, int* out)
@@ -143,7 +145,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
     const size_t n = calls.size();
     const size_t n_launch = (n + MAX_LIN_PER_LAUNCH - 1) / MAX_LIN_PER_LAUNCH;
     const size_t per_launch = (n + n_launch - 1) / n_launch;
-    const int waves = decode_waves();
+    const int waves = decode_waves(M);
     int n_blocks = 0;
     lpq_status st = decode_block_count(waves, &n_blocks);
     if (st != LPQ_OK) return st;

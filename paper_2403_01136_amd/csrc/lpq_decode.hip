@@ -28,14 +28,29 @@ template <int V> struct DecodeCfg { enum { RT = (V == V_F16) ? 2 : 4, DEPTH = (V
 
 // A launch is specialised on TOK, the token rows it covers: 16 (M <= 16: 16x16x32 MFMA, scale and
 // zero applied after the matrix cores), 32 or 64 (32x32x16 MFMA at twice the matrix-core rate,
-// weights dequantised to fp16 in registers).  Activation staging: CHUNK 128-column steps per LDS buffer.
-template <int TOK> struct PipeCfg {
-    enum { CHUNK = (TOK == 16) ? 8 : (TOK == 32) ? 4 : 2 };
-    enum { ROW_HALVES = CHUNK * 128 + 8 };          // +16 bytes: conflict-free 16-byte operand reads
-    enum { PIECES256 = TOK / 16 * CHUNK };          // 16-byte pieces of a chunk per thread at 256 threads
+// weights dequantised to fp16 in registers).  Activation staging: CHUNK 128-column steps per LDS
+// buffer, sized so that two buffers of every workgroup resident on a CU fill 128 KB of its LDS.
+template <int TOK, int WAVES> struct PipeCfg {
+    enum { FIT = 32 * WAVES / TOK, CHUNK = FIT < 8 ? FIT : 8 };
+    enum { ROW_HALVES = CHUNK * 128 };
+    enum { XQ = TOK * CHUNK / 4 / WAVES };          // 1 KB global-to-LDS loads per wave and chunk
 };
 
-template <int TOK> struct DecodeSmem { uint16_t x[2][TOK][PipeCfg<TOK>::ROW_HALVES]; };
+// Token row `row` keeps the 16-byte column group c16 of each of its 128-column steps in slot
+// c16 ^ (row % 16) of that step: rows are a multiple of 256 bytes apart, and the swizzle makes the
+// 16-byte operand reads of 16 consecutive rows hit 16 different bank groups.
+template <int TOK, int WAVES> struct DecodeSmem { uint16_t x[2][TOK][PipeCfg<TOK, WAVES>::ROW_HALVES]; };
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// s_waitcnt vmcnt(N): all but the wave's newest N vector-memory operations have completed.  Also a
+// compiler barrier, so that no memory operation moves across it.
+template <int N> __device__ __forceinline__ void wait_vmem_all_but()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 // A chunk: up to CHUNK consecutive 128-column steps of one (linear, row superblock) unit.
 struct Chunk {
@@ -49,15 +64,17 @@ struct Chunk {
 // or slot_last (the unit it leaves mid-way) -- and cleared.
 template <int V, int TOK, int WAVES>
 __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long s_begin, long s_end,
-                                          float* __restrict__ slot_first, float* __restrict__ slot_last, DecodeSmem<TOK>& sm)
+                                          float* __restrict__ slot_first, float* __restrict__ slot_last, DecodeSmem<TOK, WAVES>& sm)
 {
     constexpr int RT = DecodeCfg<V>::RT;
     constexpr int SCHEME = VInfo<V>::SCHEME;
     constexpr bool WIDE = TOK > 16;                 // 32x32x16 path
     constexpr int MT = 1;                           // narrow path: one 16-token tile
     constexpr int NP = RT / 2, MT2 = WIDE ? TOK / 32 : 1;      // wide path: tile pairs and 32-token tiles
-    constexpr int CHUNK = PipeCfg<TOK>::CHUNK, PIECES = PipeCfg<TOK>::PIECES256 * 4 / WAVES, THREADS = 64 * WAVES;
+    constexpr int CHUNK = PipeCfg<TOK, WAVES>::CHUNK, XQ = PipeCfg<TOK, WAVES>::XQ;
     constexpr int STAGES = DecodeCfg<V>::DEPTH < CHUNK ? DecodeCfg<V>::DEPTH : CHUNK;
+    // vector-memory loads of one Stage: the tiles (one load per KB, the 768-byte 3-bit tile included) and scale + zero
+    constexpr int STAGE_LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) + (SCHEME == SCH_ASYM ? 2 : 0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, kq = lane >> 4;
     const int KT = L.K / 128;
@@ -127,6 +144,10 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     // instead of 16 packed FMAs plus the int -> fp16 conversions.  Otherwise (many tokens, where the
     // fp32 work would grow with M): dequantise each weight to fp16 once, w~ = scale * code + zero.
     constexpr bool POST = !WIDE && V != V_F16;
+    // MFMA A operand: 8 consecutive columns (16-byte group c16 of 128-column step `step`) of a token row
+    auto x_operand = [&](int buf, int row, int step, int c16) {
+        return *reinterpret_cast<const h8*>(&sm.x[buf][row][step * 128 + 8 * (c16 ^ (row & 15))]);
+    };
     auto compute = [&](Stage& b, int buf, int step) {
         if constexpr (WIDE) {
             // dequantise two MFMA steps of every tile at a time, pair tiles (p, p + NP) into 32-row
@@ -154,9 +175,8 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                     const int j = 2 * half + jj;
 #pragma unroll
                     for (int m2 = 0; m2 < MT2; ++m2) {
-                        const uint16_t* xrow = &sm.x[buf][32 * m2 + arow][step * 128 + 32 * j + 16 * ahalf];
-                        const h8 a0 = *reinterpret_cast<const h8*>(xrow);
-                        const h8 a1 = *reinterpret_cast<const h8*>(xrow + 8);
+                        const h8 a0 = x_operand(buf, 32 * m2 + arow, step, 4 * j + 2 * ahalf);
+                        const h8 a1 = x_operand(buf, 32 * m2 + arow, step, 4 * j + 2 * ahalf + 1);
 #pragma unroll
                         for (int p = 0; p < NP; ++p) {
                             accw[p][m2] = mfma32(a0, wb[p][jj], accw[p][m2]);
@@ -180,7 +200,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-                        const h8 a = *reinterpret_cast<const h8*>(&sm.x[buf][16 * mt + r][step * 128 + 32 * j + 8 * kq]);
+                        const h8 a = x_operand(buf, 16 * mt + r, step, 4 * j + kq);
                         xs[mt] = mfma16(a, ones, j == 0 ? zero4 : xs[mt]);
 #pragma unroll
                         for (int t = 0; t < RT; ++t) d[t][mt] = mfma16(a, wb[t][j], j == 0 ? zero4 : d[t][mt]);
@@ -203,7 +223,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-                        const h8 a = *reinterpret_cast<const h8*>(&sm.x[buf][16 * mt + r][step * 128 + 32 * j + 8 * kq]);
+                        const h8 a = x_operand(buf, 16 * mt + r, step, 4 * j + kq);
                         xsum[mt] = mfma16(a, ones, xsum[mt]);
 #pragma unroll
                         for (int t = 0; t < RT; ++t) acc[t][mt] = mfma16(a, wb[t][j], acc[t][mt]);
@@ -224,31 +244,29 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    const h8 a = *reinterpret_cast<const h8*>(&sm.x[buf][16 * mt + r][step * 128 + 32 * j + 8 * kq]);
+                    const h8 a = x_operand(buf, 16 * mt + r, step, 4 * j + kq);
 #pragma unroll
                     for (int t = 0; t < RT; ++t) acc[t][mt] = mfma16(a, wb[t][j], acc[t][mt]);
                 }
         }
     };
 
-    // ---- activation staging: the x columns of one chunk, shared by the workgroup through LDS
-    u32x4 xr[PIECES];
-    auto load_x_chunk = [&](const Chunk& c) {
+    // ---- activation staging: the x columns of one chunk, shared by the workgroup through LDS.
+    // Global-to-LDS loads, 1 KB per wave and instruction (four 256-byte row segments); a lane fetches
+    // the column group that belongs in its 16-byte slot after swizzling.  Token rows past M and steps
+    // past the end of a short chunk are clamped to valid ones: they feed nothing that is stored.
+    // The loads are asynchronous: wait on vmcnt before the barrier that publishes the buffer.
+    auto fill_x_chunk = [&](const Chunk& c, int buf) {
 #pragma unroll
-        for (int i = 0; i < PIECES; ++i) {
-            const int p = tid + THREADS * i, row = p / (CHUNK * 16), c16 = p % (CHUNK * 16);
-            const int tok = m0 + row;
-            u32x4 v = {0, 0, 0, 0};
-            if (tok < M && c16 < c.n * 16) v = *reinterpret_cast<const u32x4*>(L.x + (size_t)tok * L.K + c.kt0 * 128 + c16 * 8);
-            xr[i] = v;
+        for (int i = 0; i < XQ; ++i) {
+            const int q = XQ * wave + i;
+            const int u = 4 * q + (lane >> 4), row = u / CHUNK, seg = min(u % CHUNK, c.n - 1);
+            const int c16 = (lane & 15) ^ (row & 15);
+            const int tok = min(m0 + row, M - 1);
+            const uint16_t* g = L.x + (size_t)tok * L.K + (size_t)(c.kt0 + seg) * 128 + c16 * 8;
+            __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(&sm.x[buf][0][0] + 512 * q), 16, 0, 0);
         }
-    };
-    auto store_x_chunk = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < PIECES; ++i) {
-            const int p = tid + THREADS * i, row = p / (CHUNK * 16), c16 = p % (CHUNK * 16);
-            *reinterpret_cast<u32x4*>(&sm.x[buf][row][c16 * 8]) = xr[i];
-        }
+        asm volatile("" ::: "memory");      // weight loads issued later stay later: vmcnt counts in issue order
     };
 
     // ---- end of a unit: lane holds tokens 4*kq + v of RT consecutive rows starting at nbase
@@ -331,15 +349,15 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     // ---- main loop over chunks; loads for slot i + STAGES are issued right after slot i is consumed,
     // whether that slot lies in this chunk or in the next one (possibly of the next unit)
     Chunk cur = first_chunk(s_begin), nxt = next_chunk(cur);
-    load_x_chunk(cur);
+    fill_x_chunk(cur, 0);
 #pragma unroll
     for (int i = 0; i < STAGES; ++i)
         if (i < cur.n) issue(st[i], cur.sb, cur.kt0 + i);      // slots past a short chunk stay empty
-    store_x_chunk(0);
+    wait_vmem_all_but<0>();
     __syncthreads();
     int buf = 0;
     while (cur.n > 0) {
-        if (nxt.n > 0) load_x_chunk(nxt);
+        if (nxt.n > 0) fill_x_chunk(nxt, buf ^ 1);
         const bool active = row_block(cur.sb) < L.row_blocks;
         if (cur.n == CHUNK && active && nxt.n >= STAGES) {
             // steady state: a full chunk followed by enough steps to refill every slot -- no
@@ -350,7 +368,10 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                 const int q = i + STAGES;                   // slot to refill
                 if (q < CHUNK) issue(st[i % STAGES], cur.sb, cur.kt0 + q);
                 else           issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - CHUNK));
+                if constexpr (WIDE) __builtin_amdgcn_sched_barrier(0);      // keeps a step's operand reads out of earlier steps (register pressure)
             }
+            // the next chunk's activations were requested before this chunk's STAGES refills, which stay in flight
+            wait_vmem_all_but<STAGES * STAGE_LOADS>();
         } else {
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) {
@@ -359,6 +380,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                 if (q < CHUNK) { if (q < cur.n) issue(st[i % STAGES], cur.sb, cur.kt0 + q); }
                 else           { if (q - CHUNK < nxt.n) issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - CHUNK)); }
             }
+            wait_vmem_all_but<0>();
         }
         const bool unit_ends = cur.kt0 + cur.n == KT || nxt.n == 0;
         if (unit_ends) {
@@ -366,7 +388,6 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             const bool whole = u0 >= s_begin && u0 + KT <= s_end;
             finish_unit(cur.sb, whole ? nullptr : (u0 < s_begin ? slot_first : slot_last));
         }
-        if (nxt.n > 0) store_x_chunk(buf ^ 1);
         __syncthreads();
         buf ^= 1;
         cur = nxt;
@@ -403,7 +424,7 @@ template <int TOK, int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const DecodeArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-    DecodeSmem<TOK>& sm = *reinterpret_cast<DecodeSmem<TOK>*>(smem_raw);
+    DecodeSmem<TOK, WAVES>& sm = *reinterpret_cast<DecodeSmem<TOK, WAVES>*>(smem_raw);
     const int b = blockIdx.x;
     const uint64_t lo = range_begin(a, b), hi = range_begin(a, b + 1);
     Cursor c = first_step_at(a, lo);
@@ -501,14 +522,14 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
 template <int TOK, int WAVES>
 static hipError_t launch_tok(const DecodeArgs& a, hipStream_t s)
 {
-    static bool attr_set = false;      // the slab is just over the 64 KB that needs no opt-in
+    static bool attr_set = false;      // the slab may exceed the 64 KB that needs no opt-in
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<TOK, WAVES>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(DecodeSmem<TOK>));
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(DecodeSmem<TOK, WAVES>));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    decode_kernel<TOK, WAVES><<<(unsigned)a.n_blocks, 64 * WAVES, sizeof(DecodeSmem<TOK>), s>>>(a);
+    decode_kernel<TOK, WAVES><<<(unsigned)a.n_blocks, 64 * WAVES, sizeof(DecodeSmem<TOK, WAVES>), s>>>(a);
     return hipGetLastError();
 }
 

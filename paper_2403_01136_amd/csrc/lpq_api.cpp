@@ -194,6 +194,28 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
     return LPQ_OK;
 }
 
+// How many groups to split a linear's token blocks into (see PrefillLin).  With g groups, a linear's
+// weights are fetched into g of the 8 L2s and its activations into 8 / g of them.  Measured on whole
+// stages (OPT-13B and 70B-class shapes, every variant), two groups are best or within 1% of it;
+// other counts are for shapes with too few token or row blocks, or that two groups would spread
+// unevenly over the XCDs.
+int prefill_token_groups(int m_blocks, int n_blocks)
+{
+    static const int forced = env_int("LPQ_PREFILL_TOKEN_GROUPS", 0);      // for experiments
+    if (forced == 1 || forced == 2 || forced == 4 || forced == 8) return forced;
+    static const int order[4] = {2, 4, 1, 8};
+    int best = 1;
+    double best_imbalance = 1e30;
+    for (int i = 0; i < 4; ++i) {
+        const int g = order[i];
+        if (g > 1 && (g > m_blocks || 8 / g > n_blocks)) continue;
+        const double imbalance = 8.0 * prefill_xcd_tiles(m_blocks, n_blocks, g) / ((double)m_blocks * n_blocks);
+        if (imbalance <= 1.15) return g;
+        if (imbalance < best_imbalance) { best = g; best_imbalance = imbalance; }
+    }
+    return best;
+}
+
 // Prefill-phase dispatch of a list of independent linears: one grouped launch per storage variant
 // (and per MAX_PREFILL_LIN linears), tiles of the longest-K linears first.
 lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream)
@@ -223,8 +245,10 @@ lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStrea
                 L.K = w.d.K;
                 L.N = w.d.N;
                 L.n_blocks = (w.d.N + 255) / 256;
+                L.token_groups = prefill_token_groups(m_blocks, L.n_blocks);
+                L.pad = 0;
                 L.tile_begin = (int32_t)tiles;
-                tiles += (long)L.n_blocks * m_blocks;
+                tiles += 8L * prefill_xcd_tiles(m_blocks, L.n_blocks, L.token_groups);
             }
             if (tiles > 0x7fffffffL) return LPQ_ERR_UNSUPPORTED;
             a.total_tiles = (int32_t)tiles;

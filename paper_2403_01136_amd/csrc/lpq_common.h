@@ -39,8 +39,14 @@ struct DecodeArgs {
     LinDesc lin[MAX_LIN_PER_LAUNCH];
 };
 
-// One linear of a grouped prefill launch: its output is cut into tiles of BM tokens x 256 rows of W,
-// numbered tile_begin + mb * n_blocks + nb (row blocks fastest, so neighbours share activations).
+// One linear of a grouped prefill launch: its output is cut into tiles of BM tokens x 256 rows of W.
+// Workgroup ids go round-robin over the chip's 8 XCDs (each with its own L2), so workgroup
+// tile_begin + 8 * l + x is the l-th tile of XCD x (tile_begin is a multiple of 8).  The token blocks
+// are split into token_groups groups and the row blocks into 8 / token_groups classes (row block n is
+// in class n % classes); XCD x owns group x % token_groups and class x / token_groups and walks its
+// tiles token block fastest, so the tiles an XCD runs at one time form a (token blocks) x (row blocks)
+// rectangle whose activations and weights are fetched into that L2 once.  prefill_xcd_tile() decodes
+// (x, l); 8 * prefill_xcd_tiles() workgroups cover the linear (those past an XCD's share exit).
 struct PrefillLin {
     const uint8_t* codes;
     const uint16_t* scales;
@@ -51,7 +57,31 @@ struct PrefillLin {
     int32_t K, N;
     int32_t tile_begin;     // first tile (workgroup) of this linear in the launch
     int32_t n_blocks;       // ceil(N / 256)
+    int32_t token_groups;   // 1, 2, 4 or 8
+    int32_t pad;
 };
+
+// Token block and row block of tile l of XCD x; false if that XCD has fewer tiles.
+__host__ __device__ inline bool prefill_xcd_tile(int m_blocks, int n_blocks, int token_groups, int x, int l, int* tile_m, int* tile_n)
+{
+    const int classes = 8 / token_groups, tg = x % token_groups, rc = x / token_groups;
+    const int group_size = (m_blocks + token_groups - 1) / token_groups;
+    const int m_first = tg * group_size;
+    const int m_cnt = m_blocks - m_first < group_size ? m_blocks - m_first : group_size;
+    if (m_cnt <= 0) return false;
+    *tile_m = m_first + l % m_cnt;
+    *tile_n = rc + classes * (l / m_cnt);
+    return *tile_n < n_blocks;
+}
+
+// Tiles of the busiest XCD.
+__host__ __device__ inline int prefill_xcd_tiles(int m_blocks, int n_blocks, int token_groups)
+{
+    const int classes = 8 / token_groups;
+    const int group_size = (m_blocks + token_groups - 1) / token_groups;      // group 0 is never smaller than the others
+    const int rows_class0 = (n_blocks + classes - 1) / classes;               // nor is class 0
+    return (group_size < m_blocks ? group_size : m_blocks) * rows_class0;
+}
 
 enum { MAX_PREFILL_LIN = 60 };
 

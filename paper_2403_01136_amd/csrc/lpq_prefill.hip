@@ -16,9 +16,9 @@
 // of 16 consecutive token rows fall on 16 different bank groups.  The matrix instruction is
 // v_mfma_f32_32x32x16_f16 (twice the rate of 16x16x32 on this chip): tiles t and t+2 of the wave's
 // block are paired into 32-row operands with v_permlane16_swap after dequantisation, so a lane ends
-// up with two consecutive output rows per token.  Registers are kept under 256
-// per lane so that two workgroups share a CU and one's barrier and dequantisation overlap the
-// other's matrix instructions.
+// up with two consecutive output rows per token.  A workgroup has a CU to itself (one wave per SIMD,
+// up to 512 registers per lane), so the overlap of dequantisation, operand reads and matrix
+// instructions is arranged inside each wave (see the main loop).
 #include "lpq_common.h"
 #include "lpq_device.h"
 
@@ -47,23 +47,12 @@ void prefill_kernel(const PrefillArgs a)
     uint16_t* __restrict__ y = L.y;
     const uint16_t* __restrict__ bias = L.bias;
     const int M = a.M, K = L.K, N = L.N;
-    // Tile order inside a linear: consecutive workgroup ids land on consecutive XCDs (8 of them, each
-    // with its own L2), so workgroup id % 8 picks the token block within a group of 8 and id / 8 walks
-    // the row blocks: every XCD then re-reads one token block's activations (which fit its L2) while
-    // streaming different weights, instead of all XCDs sharing all token blocks.
+    // Tile order inside a linear: workgroup ids go round-robin over the 8 XCDs; each XCD walks a
+    // rectangle of token blocks x row blocks so that its L2 fetches those activations and weights once.
     const int tile = (int)blockIdx.x - L.tile_begin;
     const int m_blocks = (M + BM - 1) / BM;
     int tile_m, tile_n;
-    const int grouped = (m_blocks / 8) * 8 * L.n_blocks;         // tiles of the full groups of 8 token blocks
-    if (tile < grouped) {
-        const int g = tile / (8 * L.n_blocks), q = tile % (8 * L.n_blocks);
-        tile_m = 8 * g + (q & 7);
-        tile_n = q >> 3;
-    } else {
-        const int q = tile - grouped;
-        tile_m = (m_blocks / 8) * 8 + q / L.n_blocks;
-        tile_n = q % L.n_blocks;
-    }
+    if (!prefill_xcd_tile(m_blocks, L.n_blocks, L.token_groups, tile & 7, tile >> 3, &tile_m, &tile_n)) return;
     constexpr int SCHEME = VInfo<V>::SCHEME;
     constexpr int NW = 4;                           // 16-row tiles per wave = one 64-row block
     constexpr int MTB = BM / 32;                    // 32-token tiles per block
@@ -154,57 +143,78 @@ void prefill_kernel(const PrefillArgs a)
         }
     };
 
-    WStep wcur, wnext;
-    load_w(wcur, 0, 0);
+    // Software pipeline inside the wave.  The matrix pipe runs one instruction at a time and a wave
+    // issues in order, so vector work placed between two matrix instructions is free while work placed
+    // in front of a run of them is not.  The step is therefore cut into segments of four matrix
+    // instructions (one 32-token tile, both tile pairs, two k slots); while the segments of one half
+    // step run from wb[h], the next half step is unpacked into wb[1 - h], one tile per segment.
+    // Scheduling barriers keep the compiler from regrouping the segments.
+    h8 wb[2][NW][2];
+    WStep ws[2];                 // HALF_LOADS: raw half steps by parity; else this step's and the next step's codes
+    auto unpack_tile = [&](const WStep& w, int t, int half, int dst) { operands(w, t, half, wb[dst][t]); };
+    auto pair_tiles = [&](int p, int dst) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) pair_tiles_for_mfma32(wb[dst][p][jj], wb[dst][p + 2][jj]);
+    };
+    const int arow = lane & 31, ahalf = lane >> 5;
+    auto x_operands = [&](int buf, int j, int mt, h8 out[2]) {
+        const int row = 32 * mt + arow;
+        out[0] = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf) ^ (row & 15))]);
+        out[1] = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf + 1) ^ (row & 15))]);
+    };
+
+    load_w(ws[0], 0, 0);
+    if constexpr (HALF_LOADS) load_w(ws[1], 0, 1);
     fill_x_slab(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the slab (and the first weights) have landed
+#pragma unroll
+    for (int t = 0; t < NW; ++t) unpack_tile(ws[0], t, 0, 0);
+    pair_tiles(0, 0);
+    pair_tiles(1, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): the slab has landed
     __syncthreads();
 
-    const int arow = lane & 31, ahalf = lane >> 5;
+    constexpr int SEGS = 4 * MTB;                    // segments per 128-column step
+    constexpr int STRIDE = MTB / 4;                  // segments between two pieces of unpacking work
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
-        // start the next step's loads before anything else (weights first, the slab last, so that the
-        // single wait before the barrier is also the wait the next step needs); they land while this
-        // step's tiles are dequantised and multiplied
-        if constexpr (!HALF_LOADS) { if (kt + 1 < KT) load_w(wnext, kt + 1, 0); }
-        if (kt + 1 < KT) fill_x_slab(kt + 1, buf ^ 1);
+        // Loads for the next step go out first and land while this step is multiplied.  Past the last
+        // step they re-read it (no branches in the loop); what is built from them is never multiplied.
+        const int ktn = min(kt + 1, KT - 1);
+        if constexpr (!HALF_LOADS) load_w(ws[1], ktn, 0);
+        fill_x_slab(ktn, buf ^ 1);
+        h8 xa[2][2];                                 // activations are read one segment ahead
+        x_operands(buf, 0, 0, xa[0]);
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            if constexpr (HALF_LOADS) {
-                if (half == 0) load_w(wnext, kt, 1);
-                else if (kt + 1 < KT) load_w(wnext, kt + 1, 0);
-            }
-            // dequantise two steps of each tile, pair tiles (0,2) and (1,3) into 32-row operands:
-            // wb[p] then covers k slots (kq 0, kq 2) and wb[p+2] slots (kq 1, kq 3)
-            h8 wb[NW][2];
+            if constexpr (HALF_LOADS) load_w(ws[half], ktn, half);       // the half step after next
+            // the half step unpacked now: (kt, 1) during half 0, (kt + 1, 0) during half 1
+            const WStep& src = HALF_LOADS ? ws[1 - half] : ws[half];
 #pragma unroll
-            for (int t = 0; t < NW; ++t) operands(wcur, t, half, wb[t]);
-#pragma unroll
-            for (int p = 0; p < 2; ++p)
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj) pair_tiles_for_mfma32(wb[p][jj], wb[p + 2][jj]);
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-                const int j = 2 * half + jj;
+            for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
                 for (int mt = 0; mt < MTB; ++mt) {
-                    const int row = 32 * mt + arow;
-                    const h8 a0 = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf) ^ (row & 15))]);
-                    const h8 a1 = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf + 1) ^ (row & 15))]);
-#pragma unroll
-                    for (int p = 0; p < 2; ++p) {
-                        acc[p][mt] = mfma32(a0, wb[p][jj], acc[p][mt]);
-                        acc[p][mt] = mfma32(a1, wb[p + 2][jj], acc[p][mt]);
+                    const int seg = jj * MTB + mt, gseg = half * 2 * MTB + seg, cur = gseg & 1;
+                    if (gseg + 1 < SEGS) {           // the next segment's activations (same slab)
+                        x_operands(buf, (gseg + 1) / MTB, (gseg + 1) % MTB, xa[cur ^ 1]);
+                        // with no unpacking to place, the reads are best issued ahead of the segment's matrix instructions
+                        if constexpr (V == V_F16) __builtin_amdgcn_sched_barrier(0);
                     }
+                    acc[0][mt] = mfma32(xa[cur][0], wb[half][0][jj], acc[0][mt]);
+                    acc[1][mt] = mfma32(xa[cur][0], wb[half][1][jj], acc[1][mt]);
+                    acc[0][mt] = mfma32(xa[cur][1], wb[half][2][jj], acc[0][mt]);
+                    acc[1][mt] = mfma32(xa[cur][1], wb[half][3][jj], acc[1][mt]);
+                    if (seg == 0 * STRIDE) unpack_tile(src, 0, 1 - half, 1 - half);
+                    if (seg == 1 * STRIDE) unpack_tile(src, 2, 1 - half, 1 - half);
+                    if (seg == 2 * STRIDE) pair_tiles(0, 1 - half);
+                    if (seg == 3 * STRIDE) unpack_tile(src, 1, 1 - half, 1 - half);
+                    if (seg == 4 * STRIDE) unpack_tile(src, 3, 1 - half, 1 - half);
+                    if (seg == 5 * STRIDE) pair_tiles(1, 1 - half);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-            }
-            if constexpr (HALF_LOADS) {
-                if (half == 0) { __builtin_amdgcn_s_waitcnt(0x0F70); wcur = wnext; }     // second half of this step
-            }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): next slab written before anyone reads it
         __syncthreads();
-        wcur = wnext;
+        if constexpr (!HALF_LOADS) ws[0] = ws[1];
     }
 
     if (!active) return;
@@ -230,10 +240,10 @@ void prefill_kernel(const PrefillArgs a)
         }
 }
 
-// Tokens per tile.  Weight bytes are re-read from L2 once per token block, so the variants with the
-// most bytes per weight (8-bit codes, fp16) take 256-token tiles (one workgroup per CU, 256
-// accumulator registers); the others stay at 128 tokens and two workgroups per CU.
-template <int V> struct PrefillTile { enum { BM = (V == V_W3 || V == V_W4) ? 128 : 256 }; };
+// Tokens per tile: 256 for every variant (one workgroup per CU; 256 accumulator registers of the 512
+// a lane can have at one wave per SIMD).  Weight bytes are re-read from L2 once per token block and
+// unpacked once per token block, so larger tiles mean fewer of both per matrix instruction.
+template <int V> struct PrefillTile { enum { BM = 256 }; };
 
 template <int V>
 hipError_t launch_variant(const PrefillArgs& a, hipStream_t s)

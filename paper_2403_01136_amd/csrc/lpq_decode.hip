@@ -187,24 +187,36 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             }
             return;
         }
-        h8 wb[RT][4];
         if constexpr (POST) {
-#pragma unroll
-            for (int t = 0; t < RT; ++t) unpack_subnormal<V>(b.w[t], wb[t]);
+            // In-order issue: vector work in front of a run of matrix instructions is not hidden by
+            // them, vector work between them is.  So the codes of MFMA step j + 1 are unpacked in the
+            // same scheduling group as the matrix instructions of step j.
+            h8 wj[2][RT];
             const _Float16 one = (_Float16)1.0f;
             const h8 ones = {one, one, one, one, one, one, one, one};
+            const f4 zero4 = {0, 0, 0, 0};
+            f4 d[RT], xs;
+#pragma unroll
+            for (int t = 0; t < RT; ++t) wj[0][t] = unpack_subnormal_step<V>(b.w[t], 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const h8 a = x_operand(buf, r, step, 4 * j + kq);
+                if (j < 3) {
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) wj[(j + 1) & 1][t] = unpack_subnormal_step<V>(b.w[t], j + 1);
+                }
+                if constexpr (SCHEME == SCH_ASYM) {
+                    xs = mfma16(a, ones, j == 0 ? zero4 : xs);
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) d[t] = mfma16(a, wj[j & 1][t], j == 0 ? zero4 : d[t]);
+                } else {   // per-row scheme: one scale per row, applied in the epilogue
+                    xsum[0] = mfma16(a, ones, xsum[0]);
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) acc[t][0] = mfma16(a, wj[j & 1][t], acc[t][0]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if constexpr (SCHEME == SCH_ASYM) {
-                f4 d[RT][MT], xs[MT];
-                const f4 zero4 = {0, 0, 0, 0};
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        const h8 a = x_operand(buf, 16 * mt + r, step, 4 * j + kq);
-                        xs[mt] = mfma16(a, ones, j == 0 ? zero4 : xs[mt]);
-#pragma unroll
-                        for (int t = 0; t < RT; ++t) d[t][mt] = mfma16(a, wb[t][j], j == 0 ? zero4 : d[t][mt]);
-                    }
 #pragma unroll
                 for (int t = 0; t < RT; ++t) {
                     const uint32_t sp = b.s[t >> 1], zp = b.z[t >> 1];
@@ -213,23 +225,12 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                     const float sf = (float)__builtin_bit_cast(_Float16, sh) * 16777216.0f;     // scale * 2^24
                     const float zf = (float)__builtin_bit_cast(_Float16, zh);
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            acc[t][mt][v] = __builtin_fmaf(sf, d[t][mt][v], __builtin_fmaf(zf, xs[mt][v], acc[t][mt][v]));
+                    for (int v = 0; v < 4; ++v)
+                        acc[t][0][v] = __builtin_fmaf(sf, d[t][v], __builtin_fmaf(zf, xs[v], acc[t][0][v]));
                 }
-            } else {   // per-row scheme: one scale per row, applied in the epilogue
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        const h8 a = x_operand(buf, 16 * mt + r, step, 4 * j + kq);
-                        xsum[mt] = mfma16(a, ones, xsum[mt]);
-#pragma unroll
-                        for (int t = 0; t < RT; ++t) acc[t][mt] = mfma16(a, wb[t][j], acc[t][mt]);
-                    }
             }
         } else {
+            h8 wb[RT][4];
 #pragma unroll
             for (int t = 0; t < RT; ++t) {
                 unpack_codes<V>(b.w[t], wb[t]);

@@ -197,6 +197,37 @@ __device__ __forceinline__ void unpack_subnormal(const WRaw<V>& w, h8 out[4])
     }
 }
 
+// One MFMA step (32 columns: j) of unpack_subnormal, for callers that interleave the unpacking of
+// step j + 1 with the matrix instructions of step j.
+template <int V>
+__device__ __forceinline__ h8 unpack_subnormal_step(const WRaw<V>& w, int j)
+{
+    if constexpr (V == V_W4) {
+        constexpr uint32_t M4 = 0x000F000Fu;
+        const uint32_t q = w.q[j];
+        const u32x4 o = {q & M4, (q >> 4) & M4, (q >> 8) & M4, (q >> 12) & M4};
+        return __builtin_bit_cast(h8, o);
+    } else if constexpr (V == V_W3) {
+        constexpr uint32_t M3 = 0x00070007u;
+        u32x4 o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int P = 4 * j + k;
+            if (P < 15) o[k] = (w.q[P / 5] >> (3 * (P % 5))) & M3;
+            else o[k] = ((w.q[0] >> 15) & 0x00010001u) | ((w.q[1] >> 14) & 0x00020002u) | ((w.q[2] >> 13) & 0x00040004u);
+        }
+        return __builtin_bit_cast(h8, o);
+    } else if constexpr (V == V_W8 || V == V_I8) {
+        uint32_t a = w.q[j >> 1][2 * (j & 1)], b = w.q[j >> 1][2 * (j & 1) + 1];
+        if constexpr (V == V_I8) { a ^= 0x80808080u; b ^= 0x80808080u; }
+        const u32x4 o = {__builtin_amdgcn_perm(a, 0u, 0x0c050c04u), __builtin_amdgcn_perm(a, 0u, 0x0c070c06u),
+                         __builtin_amdgcn_perm(b, 0u, 0x0c050c04u), __builtin_amdgcn_perm(b, 0u, 0x0c070c06u)};
+        return __builtin_bit_cast(h8, o);
+    } else {
+        return __builtin_bit_cast(h8, w.q[j]);
+    }
+}
+
 // The same for two MFMA steps only (j = 2*half, 2*half + 1): the compute-bound kernels build their
 // operands half a 128-column step at a time to keep 32 instead of 64 operand registers live.
 // `piece8`: for the 8-bit variants, which of w.q[] holds the 16-byte piece of this half (callers that

@@ -276,7 +276,11 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         if (WIDE && rb < L.row_blocks) {
             // lane (n = lane%32, half = lane/32) holds tokens 32*m2 + 8*(v/4) + 4*half + v%4 of NP consecutive rows:
             // tile pair p of a 4-tile block is tiles (p, p+2), i.e. rows 4r + p (n < 16) and 4r + 2 + p (n >= 16)
-            const int ncol = lane & 31, thalf = lane >> 5;
+            const int ncol = lane & 31;
+            int thalf = lane >> 5;
+            // opaque to the optimiser: otherwise it precomputes every token's row offset (tok * N) ahead
+            // of the main loop and keeps dozens of registers live across it for this rare path
+            asm volatile("" : "+v"(thalf));
             const long nbase = (RT == 4) ? rb * 64 + 4 * (ncol & 15) + 2 * (ncol >> 4)
                                          : (rb >> 1) * 64 + 4 * (ncol & 15) + 2 * (rb & 1) + (ncol >> 4);
             float post[NP], bias[NP];

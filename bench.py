@@ -118,16 +118,15 @@ def cpu_baseline(cfg, M, budget_rows=20480):
                       % (budget_rows, K, len(cfg["layers"]), M)}
 
 
-def traffic_from_profiles(cfg, M):
-    """HBM bytes per decode launch as measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
-    the copy calibration) and recorded in profiles/decode_traffic.json for this workload; None if absent."""
-    path = os.path.join(ROOT, "profiles", "decode_traffic.json")
+def traffic_from_profiles(cfg, phase, M):
+    """HBM bytes per launch as measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by the
+    copy calibration) and recorded in profiles/hbm_traffic.json for this workload; None if absent."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         rec = json.load(open(path))
     except (OSError, ValueError):
         return None
-    key = "%s/M=%d" % (cfg["name"], M)
-    return rec.get(key)
+    return rec.get("%s/%s M=%d" % (cfg["name"], phase, M))
 
 
 def main():
@@ -177,7 +176,8 @@ def main():
         algo = wbytes + act_bytes(cfg, Md)
         out.update({"value": wbytes / ms / 1e6, "ms_per_step": ms, "host_ms_per_step": wall})
         out["roofline"] = {"bound": "hbm", "achieved": algo / ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": algo / ms / 1e6 / HBM_PEAK_GBS, "traffic": None, "kernel": "decode_kernel",
+                           "frac": algo / ms / 1e6 / HBM_PEAK_GBS, "traffic": None,
+                           "kernel": "decode_kernel + decode_fixup_kernel (one grouped decode launch of the stage)",
                            "algorithmic_bytes_per_launch": algo}
     if args.only in ("all", "prefill"):
         stage_p, _ = reuse_stage(stage_d, Mp, cfg, device)
@@ -188,7 +188,8 @@ def main():
                           "steps": psteps, "warmup": pwarm,
                           "roofline": {"bound": "mfma", "achieved": flops / ms / 1e9, "peak": MFMA_F16_PEAK_TFLOPS,
                                        "unit": "TFLOP/s", "frac": flops / ms / 1e9 / MFMA_F16_PEAK_TFLOPS, "traffic": None,
-                                       "kernel": "prefill_kernel", "algorithmic_flops_per_step": flops}}
+                                       "kernel": "prefill_kernel (one grouped launch per storage variant)",
+                                       "algorithmic_flops_per_step": flops}}
         if args.only == "prefill":
             out.update({"metric": "prefill TFLOP/s", "unit": "TFLOP/s", "value": out["prefill"]["value"],
                         "ms_per_step": ms, "steps": psteps, "warmup": pwarm, "roofline": out["prefill"]["roofline"]})
@@ -199,10 +200,12 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         out["copy_calibration"] = {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 3}
-    measured = traffic_from_profiles(cfg, Md)
-    if measured and "roofline" in out and out["roofline"]["kernel"] == "decode_kernel":
-        out["roofline"]["traffic"] = measured["bytes_per_launch"]
-        out["roofline"]["traffic_source"] = measured["source"]
+    for phase, M, roof in (("decode", Md, out.get("roofline") if args.only != "prefill" else None),
+                           ("prefill", Mp, out.get("prefill", {}).get("roofline"))):
+        measured = traffic_from_profiles(cfg, phase, M)
+        if measured and roof is not None:
+            roof["traffic"] = measured["bytes_per_launch"]
+            roof["traffic_source"] = measured["source"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, Md)
     print(json.dumps(out))

@@ -206,10 +206,9 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                     for (int t = 0; t < RT; ++t) wj[(j + 1) & 1][t] = unpack_subnormal_step<V>(b.w[t], j + 1);
                 }
                 if constexpr (SCHEME == SCH_ASYM) {
-                    const h8 as = scale_for_subnormal_step<V>(a, j);        // 3/4-bit fields are used where they lie
                     xs = mfma16(a, ones, j == 0 ? zero4 : xs);
 #pragma unroll
-                    for (int t = 0; t < RT; ++t) d[t] = mfma16(as, wj[j & 1][t], j == 0 ? zero4 : d[t]);
+                    for (int t = 0; t < RT; ++t) d[t] = mfma16(a, wj[j & 1][t], j == 0 ? zero4 : d[t]);
                 } else {   // per-row scheme: one scale per row, applied in the epilogue
                     xsum[0] = mfma16(a, ones, xsum[0]);
 #pragma unroll

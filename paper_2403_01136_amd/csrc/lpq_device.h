@@ -155,40 +155,66 @@ __device__ __forceinline__ void unpack_codes(const WRaw<V>& w, h8 out[4])
 // take fp16 subnormals at full precision).  The factor 2^24 is folded into the group scale, which
 // is applied in fp32 after the 128-column partial product.  Signed 8-bit codes come out offset by
 // +128 (two's complement with the top bit flipped); the caller removes 128 * sum(x).
-// One MFMA step (32 columns: j) of the codes as fp16 subnormals, for the kernel that applies scale and
-// zero after the matrix cores.  Fields are masked where they lie instead of being shifted down to bit
-// 0 (a shift per field is most of the unpacking work): the pair k of step j comes out multiplied by
-// 2^subnormal_field_shift(j, k), and the caller multiplies the matching activations by the inverse
-// power of two -- exact unless such an activation falls below 2^-14, where it keeps an absolute
-// accuracy of 2^-25.  Only fields above bit 9 (outside the fp16 mantissa) are shifted, a word at a time.
 template <int V>
-__host__ __device__ constexpr int subnormal_field_shift(int j, int k)
+__device__ __forceinline__ void unpack_subnormal(const WRaw<V>& w, h8 out[4])
 {
-    if (V == V_W4) return 4 * (k & 1);
-    if (V == V_W3) {
-        const int P = 4 * j + k, f = P % 5;
-        return P == 15 ? 0 : 3 * (f < 3 ? f : f - 3);
+    if constexpr (V == V_W4) {
+        constexpr uint32_t M4 = 0x000F000Fu;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t q = w.q[j];
+            const u32x4 o = {q & M4, (q >> 4) & M4, (q >> 8) & M4, (q >> 12) & M4};
+            out[j] = __builtin_bit_cast(h8, o);
+        }
+    } else if constexpr (V == V_W3) {
+        constexpr uint32_t M3 = 0x00070007u;
+        uint32_t pr[16];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const uint32_t q = w.q[i];
+#pragma unroll
+            for (int f = 0; f < 5; ++f) pr[5 * i + f] = (q >> (3 * f)) & M3;
+        }
+        pr[15] = ((w.q[0] >> 15) & 0x00010001u) | ((w.q[1] >> 14) & 0x00020002u) | ((w.q[2] >> 13) & 0x00040004u);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32x4 o = {pr[4 * j], pr[4 * j + 1], pr[4 * j + 2], pr[4 * j + 3]};
+            out[j] = __builtin_bit_cast(h8, o);
+        }
+    } else if constexpr (V == V_W8 || V == V_I8) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t a = w.q[j >> 1][2 * (j & 1)], b = w.q[j >> 1][2 * (j & 1) + 1];
+            if constexpr (V == V_I8) { a ^= 0x80808080u; b ^= 0x80808080u; }
+            // selector bytes: 4..7 = bytes of the first operand, 0x0c = constant zero
+            const u32x4 o = {__builtin_amdgcn_perm(a, 0u, 0x0c050c04u), __builtin_amdgcn_perm(a, 0u, 0x0c070c06u),
+                             __builtin_amdgcn_perm(b, 0u, 0x0c050c04u), __builtin_amdgcn_perm(b, 0u, 0x0c070c06u)};
+            out[j] = __builtin_bit_cast(h8, o);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = __builtin_bit_cast(h8, w.q[j]);
     }
-    return 0;
 }
 
+// One MFMA step (32 columns: j) of unpack_subnormal, for callers that interleave the unpacking of
+// step j + 1 with the matrix instructions of step j.
 template <int V>
 __device__ __forceinline__ h8 unpack_subnormal_step(const WRaw<V>& w, int j)
 {
     if constexpr (V == V_W4) {
         constexpr uint32_t M4 = 0x000F000Fu;
-        const uint32_t q = w.q[j], t = q >> 8;
-        const u32x4 o = {q & M4, q & (M4 << 4), t & M4, t & (M4 << 4)};
+        const uint32_t q = w.q[j];
+        const u32x4 o = {q & M4, (q >> 4) & M4, (q >> 8) & M4, (q >> 12) & M4};
         return __builtin_bit_cast(h8, o);
     } else if constexpr (V == V_W3) {
         constexpr uint32_t M3 = 0x00070007u;
         u32x4 o;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int P = 4 * j + k, f = P % 5;
-            if (P == 15) o[k] = ((w.q[0] >> 15) & 0x00010001u) | ((w.q[1] >> 14) & 0x00020002u) | ((w.q[2] >> 13) & 0x00040004u);
-            else if (f < 3) o[k] = w.q[P / 5] & (M3 << (3 * f));
-            else o[k] = (w.q[P / 5] >> 9) & (M3 << (3 * (f - 3)));       // the word's shift is shared by its fields 3 and 4
+            const int P = 4 * j + k;
+            if (P < 15) o[k] = (w.q[P / 5] >> (3 * (P % 5))) & M3;
+            else o[k] = ((w.q[0] >> 15) & 0x00010001u) | ((w.q[1] >> 14) & 0x00020002u) | ((w.q[2] >> 13) & 0x00040004u);
         }
         return __builtin_bit_cast(h8, o);
     } else if constexpr (V == V_W8 || V == V_I8) {
@@ -200,25 +226,6 @@ __device__ __forceinline__ h8 unpack_subnormal_step(const WRaw<V>& w, int j)
     } else {
         return __builtin_bit_cast(h8, w.q[j]);
     }
-}
-
-// The activations of MFMA step j, each pair divided by the power of two its codes come out multiplied by.
-template <int V>
-__device__ __forceinline__ h8 scale_for_subnormal_step(h8 a, int j)
-{
-    if constexpr (V == V_W3 || V == V_W4) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int sh = subnormal_field_shift<V>(j, k);
-            if (sh == 0) continue;
-            const _Float16 m = (_Float16)(1.0f / (float)(1 << sh));
-            h2 p = {a[2 * k], a[2 * k + 1]};
-            p = p * h2{m, m};
-            a[2 * k] = p[0];
-            a[2 * k + 1] = p[1];
-        }
-    }
-    return a;
 }
 
 // The same for two MFMA steps only (j = 2*half, 2*half + 1): the compute-bound kernels build their

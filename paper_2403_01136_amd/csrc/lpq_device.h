@@ -155,49 +155,7 @@ __device__ __forceinline__ void unpack_codes(const WRaw<V>& w, h8 out[4])
 // take fp16 subnormals at full precision).  The factor 2^24 is folded into the group scale, which
 // is applied in fp32 after the 128-column partial product.  Signed 8-bit codes come out offset by
 // +128 (two's complement with the top bit flipped); the caller removes 128 * sum(x).
-template <int V>
-__device__ __forceinline__ void unpack_subnormal(const WRaw<V>& w, h8 out[4])
-{
-    if constexpr (V == V_W4) {
-        constexpr uint32_t M4 = 0x000F000Fu;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t q = w.q[j];
-            const u32x4 o = {q & M4, (q >> 4) & M4, (q >> 8) & M4, (q >> 12) & M4};
-            out[j] = __builtin_bit_cast(h8, o);
-        }
-    } else if constexpr (V == V_W3) {
-        constexpr uint32_t M3 = 0x00070007u;
-        uint32_t pr[16];
-#pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const uint32_t q = w.q[i];
-#pragma unroll
-            for (int f = 0; f < 5; ++f) pr[5 * i + f] = (q >> (3 * f)) & M3;
-        }
-        pr[15] = ((w.q[0] >> 15) & 0x00010001u) | ((w.q[1] >> 14) & 0x00020002u) | ((w.q[2] >> 13) & 0x00040004u);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const u32x4 o = {pr[4 * j], pr[4 * j + 1], pr[4 * j + 2], pr[4 * j + 3]};
-            out[j] = __builtin_bit_cast(h8, o);
-        }
-    } else if constexpr (V == V_W8 || V == V_I8) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t a = w.q[j >> 1][2 * (j & 1)], b = w.q[j >> 1][2 * (j & 1) + 1];
-            if constexpr (V == V_I8) { a ^= 0x80808080u; b ^= 0x80808080u; }
-            // selector bytes: 4..7 = bytes of the first operand, 0x0c = constant zero
-            const u32x4 o = {__builtin_amdgcn_perm(a, 0u, 0x0c050c04u), __builtin_amdgcn_perm(a, 0u, 0x0c070c06u),
-                             __builtin_amdgcn_perm(b, 0u, 0x0c050c04u), __builtin_amdgcn_perm(b, 0u, 0x0c070c06u)};
-            out[j] = __builtin_bit_cast(h8, o);
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) out[j] = __builtin_bit_cast(h8, w.q[j]);
-    }
-}
-
-// One MFMA step (32 columns: j) of unpack_subnormal, for callers that interleave the unpacking of
+// One MFMA step (32 columns: j) of the codes as subnormals; callers interleave the unpacking of
 // step j + 1 with the matrix instructions of step j.
 template <int V>
 __device__ __forceinline__ h8 unpack_subnormal_step(const WRaw<V>& w, int j)

@@ -102,6 +102,20 @@ def test_prefill_small(orc, bits, scheme, M):
     check_output(y, orc.qlinear(x, w, bits, scheme, bias), "prefill %d-bit M=%d" % (bits, M))
 
 
+@pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("mag", [2.0 ** -12, 2.0 ** -6, 2.0 ** 5], ids=["x_2e-12", "x_2e-6", "x_2e5"])
+def test_activation_magnitude(orc, bits, scheme, mag):
+    """The tolerance holds whatever the scale of the activations (tiny ones near the fp16 subnormal
+    range, large ones short of overflow in the outputs): no step of the kernels may cost them bits."""
+    N, K = 128, 512
+    w = wl.weight_np(N, K, "mag", bits, scheme)
+    for M, fn, tag in [(8, lpq.lpq_qlinear_decode, "decode"), (40, lpq.lpq_qlinear_decode, "decode"),
+                       (64, lpq.lpq_qlinear_prefill, "prefill")]:
+        x = (wl.act_np(M, K, False, "mag", M).astype(np.float32) * mag).astype(np.float16)
+        y = fn(lpq.lpq_quantize_pack(to_dev(w), bits, scheme), to_dev(x))
+        check_output(y, orc.qlinear(x, w, bits, scheme), "%s %d-bit M=%d x*%g" % (tag, bits, M, mag))
+
+
 def test_decode_and_prefill_agree_and_are_deterministic(orc):
     N, K, M = 128, 2048, 24
     w = wl.weight_np(N, K, "agree")

@@ -118,6 +118,47 @@ def cpu_baseline(cfg, M, budget_rows=20480):
                       % (budget_rows, K, len(cfg["layers"]), M)}
 
 
+def loader_bench(cfg, device, layer=2, staging_mib=64, reps=3):
+    """On-the-fly quantised loading (Sec. 5 of the paper) of one layer's four fp16 weights from pinned host
+    memory: lpq_load_quantize_pack against a plain host-to-device copy of the same bytes (the PCIe bound)."""
+    import torch
+    import paper_2403_01136_amd as lpq
+    from paper_2403_01136_amd import workloads as wl
+    bits, scheme = cfg["layers"][layer]
+    shapes = wl.linear_shapes(cfg)
+    hosts = []
+    for name in wl.LINEARS:
+        K, N = shapes[name]
+        w = wl.weight_torch(N, K, device, cfg["name"], layer, name)
+        h = torch.empty((N, K), dtype=torch.float16, pin_memory=True)
+        h.copy_(w)
+        hosts.append(h)
+        del w
+    torch.cuda.synchronize()
+    nbytes = sum(h.numel() * 2 for h in hosts)
+    staging = torch.empty(staging_mib << 20, dtype=torch.uint8, device=device)
+    dst = torch.empty(max(h.numel() for h in hosts), dtype=torch.float16, device=device)
+
+    def timed(fn):
+        best = None
+        for _ in range(reps + 1):                      # the first pass warms up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            best = dt if best is None or _ == 1 else min(best, dt)
+        return best
+
+    keep = []
+    t_load = timed(lambda: keep.__setitem__(slice(None), [lpq.lpq_load_quantize_pack(h, bits, scheme, staging) for h in hosts]))
+    t_copy = timed(lambda: [dst[:h.numel()].view(h.shape).copy_(h, non_blocking=True) for h in hosts])
+    return {"metric": "on-the-fly quantised load, fp16 source GB/s from pinned host memory", "value": nbytes / t_load / 1e9,
+            "unit": "GB/s", "ms": t_load * 1e3, "bytes": nbytes, "bits": bits,
+            "workload": "the four linears of layer %d of %s, staging %d MiB" % (layer, cfg["name"], staging_mib),
+            "h2d_copy_GBs": nbytes / t_copy / 1e9, "frac_of_h2d_copy": t_copy / t_load}
+
+
 def traffic_from_profiles(cfg, phase, M):
     """HBM bytes per launch as measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by the
     copy calibration) and recorded in profiles/hbm_traffic.json for this workload; None if absent."""
@@ -138,6 +179,7 @@ def main():
     ap.add_argument("--decode-m", type=int, default=None)
     ap.add_argument("--only", choices=["all", "decode", "prefill"], default="all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-loader", action="store_true", help="skip the host-to-device quantised-load measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times, so a --pmc run can scale FETCH_SIZE / WRITE_SIZE by it")
     args = ap.parse_args()
@@ -206,6 +248,8 @@ def main():
         if measured and roof is not None:
             roof["traffic"] = measured["bytes_per_launch"]
             roof["traffic_source"] = measured["source"]
+    if not args.no_loader and args.only == "all":
+        out["loader"] = loader_bench(cfg, device, layer=min(2, len(cfg["layers"]) - 1))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, Md)
     print(json.dumps(out))

@@ -129,6 +129,31 @@ lpq_status lpq_packed_sizes(const lpq_qdesc *desc, size_t *code_bytes, size_t *s
  * Weights must be finite.  Errors: NULL, BITS, SCHEME, SHAPE, ALIGN, DEVICE. */
 lpq_status lpq_quantize_pack(const void *w_fp16, const lpq_qdesc *desc, lpq_qweight *out, void *hip_stream);
 
+/* The same quantiser on a window of rows: rows [row0, row0 + n_rows) of the weight that `desc` describes,
+ * read from a device buffer that holds just those rows ([n_rows][K] fp16).  row0 and n_rows are multiples
+ * of 64 (the storage format's row blocks; n_rows may be 0).  Writes only those rows' codes, scales and
+ * zeros in `out`, so a weight can be quantised piecewise, in any order, as its rows arrive.
+ * Errors: as lpq_quantize_pack; SHAPE also for a window that is not on 64-row boundaries or leaves W. */
+lpq_status lpq_quantize_pack_rows(const void *w_rows_fp16, const lpq_qdesc *desc, int32_t row0, int32_t n_rows,
+                                  lpq_qweight *out, void *hip_stream);
+
+/* On-the-fly quantised loading of one module's weight from HOST memory (Sec. 5, "On-The-Fly Quantizer":
+ * module-level weights, host-to-device copy overlapped with on-GPU quantisation, so that the fp16 weight is
+ * never resident on the device as a whole).
+ *   w_fp16_host: HOST pointer, fp16 [N][K] row-major, 16-byte aligned.  Pinned memory gives asynchronous
+ *                copies that overlap the quantiser; pageable memory works but serialises.
+ *   staging:     device buffer of staging_bytes, caller-owned; it is split into two halves that take turns
+ *                receiving a band of rows (as many 64-row blocks as fit in a half) while the other half is
+ *                quantised.  LPQ_ERR_BUFSIZE if a half cannot hold 64 rows (64 * K * 2 bytes).
+ *   out:         as for lpq_quantize_pack; the result is bit-identical to it.
+ * Copies run on a library-owned stream (one per device, default priority); the quantiser runs on
+ * `hip_stream`, which also orders everything: work queued on it before the call completes before the
+ * first copy starts, and when the work this call queued on it has completed, `out` is ready and the host
+ * buffer and the staging buffer are free again.  The call itself returns without synchronising.
+ * Errors: NULL, BITS, SCHEME, SHAPE, ALIGN, BUFSIZE, DEVICE. */
+lpq_status lpq_load_quantize_pack(const void *w_fp16_host, const lpq_qdesc *desc, lpq_qweight *out, void *staging,
+                                  size_t staging_bytes, void *hip_stream);
+
 /* One quantised linear at a prefill micro-batch (Sec. 4.3: M = eta * s tokens): weight tiles
  * are dequantised in registers to fp16 and multiplied on the matrix cores.
  *   w: host struct with device buffers;  x: device fp16 [M][K];  y: device fp16 [M][N].

@@ -15,8 +15,8 @@ LPQ_FP16, LPQ_ASYM_GROUP, LPQ_SYM_CHANNEL = 0, 1, 2
 LPQ_PREFILL, LPQ_DECODE = 0, 1
 LPQ_OK = 0
 LINEARS = ("qkv", "out", "fc1", "fc2")
-EXPORTS = ("lpq_packed_sizes", "lpq_quantize_pack", "lpq_qlinear_prefill", "lpq_qlinear_decode",
-           "lpq_stage_linears", "lpq_unpack_dequant", "lpq_status_str")
+EXPORTS = ("lpq_packed_sizes", "lpq_quantize_pack", "lpq_quantize_pack_rows", "lpq_load_quantize_pack",
+           "lpq_qlinear_prefill", "lpq_qlinear_decode", "lpq_stage_linears", "lpq_unpack_dequant", "lpq_status_str")
 
 
 class lpq_qdesc(ctypes.Structure):
@@ -58,6 +58,8 @@ def load_library():
         vp, i32, szp = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_size_t)
         L.lpq_packed_sizes.argtypes = [ctypes.POINTER(lpq_qdesc), szp, szp, szp]
         L.lpq_quantize_pack.argtypes = [vp, ctypes.POINTER(lpq_qdesc), ctypes.POINTER(lpq_qweight), vp]
+        L.lpq_quantize_pack_rows.argtypes = [vp, ctypes.POINTER(lpq_qdesc), i32, i32, ctypes.POINTER(lpq_qweight), vp]
+        L.lpq_load_quantize_pack.argtypes = [vp, ctypes.POINTER(lpq_qdesc), ctypes.POINTER(lpq_qweight), vp, ctypes.c_size_t, vp]
         L.lpq_qlinear_prefill.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, vp]
         L.lpq_qlinear_decode.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, vp]
         L.lpq_stage_linears.argtypes = [ctypes.POINTER(lpq_layer), i32, ctypes.c_int, i32, ctypes.POINTER(lpq_layer_io), vp]
@@ -132,6 +134,33 @@ def lpq_quantize_pack(w, bits, scheme, bias=None, stream=None):
     qw = QWeight(bits, scheme, K, N, w.device, bias)
     st, d = qw.struct(), make_desc(bits, scheme, K, N)
     _check(load_library().lpq_quantize_pack(w.data_ptr(), ctypes.byref(d), ctypes.byref(st), _stream(stream)), "lpq_quantize_pack")
+    return qw
+
+
+def lpq_quantize_pack_rows(w_rows, qw, row0, stream=None):
+    """Quantise rows [row0, row0 + len(w_rows)) of the weight behind `qw` from w_rows (fp16 [n_rows][K] on the GPU)."""
+    w_rows = _fp16_2d(w_rows, "w_rows") if w_rows.shape[0] else w_rows
+    st, d = qw.struct(), make_desc(qw.bits, qw.scheme, qw.K, qw.N)
+    _check(load_library().lpq_quantize_pack_rows(w_rows.data_ptr() if w_rows.shape[0] else qw.codes.data_ptr(), ctypes.byref(d),
+                                                 int(row0), int(w_rows.shape[0]), ctypes.byref(st), _stream(stream)),
+           "lpq_quantize_pack_rows")
+    return qw
+
+
+def lpq_load_quantize_pack(w_host, bits, scheme, staging, device=None, bias=None, stream=None):
+    """w_host: fp16 [N][K] in HOST memory (pinned for overlap); staging: uint8 CUDA tensor that takes the
+    rows in two alternating halves -> QWeight, bit-identical to lpq_quantize_pack of the whole weight."""
+    import torch
+    if w_host.dtype != torch.float16 or w_host.dim() != 2 or not w_host.is_contiguous() or w_host.is_cuda:
+        raise ValueError("w_host must be a contiguous 2-D fp16 host tensor")
+    if staging.dtype != torch.uint8 or not staging.is_cuda or not staging.is_contiguous():
+        raise ValueError("staging must be a contiguous uint8 CUDA tensor")
+    N, K = w_host.shape
+    qw = QWeight(bits, scheme, K, N, staging.device if device is None else device, bias)
+    st, d = qw.struct(), make_desc(bits, scheme, K, N)
+    _check(load_library().lpq_load_quantize_pack(w_host.data_ptr(), ctypes.byref(d), ctypes.byref(st), staging.data_ptr(),
+                                                 staging.numel(), _stream(stream)), "lpq_load_quantize_pack")
+    qw._host_source = w_host          # the copies read it until the stream has caught up
     return qw
 
 

@@ -52,6 +52,17 @@ lpq_status check_weight(const lpq_qweight* w)
     return LPQ_OK;
 }
 
+// the descriptor a quantiser call is given and the buffers it is to fill
+lpq_status check_quantize_target(const lpq_qdesc* desc, const lpq_qweight* out)
+{
+    lpq_status st = check_desc(desc);
+    if (st != LPQ_OK) return st;
+    if (out->d.bits != desc->bits || out->d.scheme != desc->scheme || out->d.K != desc->K || out->d.N != desc->N ||
+        out->d.group_size != desc->group_size)
+        return LPQ_ERR_SHAPE;
+    return check_weight(out);
+}
+
 lpq_status check_linear(const lpq_qweight* w, const void* x, int32_t M, const void* y)
 {
     lpq_status st = check_weight(w);
@@ -84,6 +95,22 @@ lpq_status workspace(size_t need, float** out)
         g_ws.bytes[dev] = want;
     }
     *out = static_cast<float*>(g_ws.ptr[dev]);
+    return LPQ_OK;
+}
+
+// ---- copy stream of the on-the-fly loader: one per device, default priority, created on first use ----
+lpq_status copy_stream(hipStream_t* out)
+{
+    static std::mutex mu;
+    static hipStream_t streams[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!streams[dev] && hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking) != hipSuccess) {
+        streams[dev] = nullptr;
+        return LPQ_ERR_DEVICE;
+    }
+    *out = streams[dev];
     return LPQ_OK;
 }
 
@@ -280,15 +307,69 @@ lpq_status lpq_packed_sizes(const lpq_qdesc* desc, size_t* code_bytes, size_t* s
 lpq_status lpq_quantize_pack(const void* w_fp16, const lpq_qdesc* desc, lpq_qweight* out, void* hip_stream)
 {
     if (!w_fp16 || !desc || !out) return LPQ_ERR_NULL;
-    lpq_status st = check_desc(desc);
-    if (st != LPQ_OK) return st;
-    if (out->d.bits != desc->bits || out->d.scheme != desc->scheme || out->d.K != desc->K || out->d.N != desc->N ||
-        out->d.group_size != desc->group_size)
-        return LPQ_ERR_SHAPE;
-    st = check_weight(out);
+    lpq_status st = check_quantize_target(desc, out);
     if (st != LPQ_OK) return st;
     if (misaligned(w_fp16)) return LPQ_ERR_ALIGN;
-    return launch_quantize_pack(w_fp16, *desc, *out, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPQ_OK : LPQ_ERR_DEVICE;
+    return launch_quantize_pack(w_fp16, *desc, 0, desc->N, *out, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPQ_OK : LPQ_ERR_DEVICE;
+}
+
+lpq_status lpq_quantize_pack_rows(const void* w_rows_fp16, const lpq_qdesc* desc, int32_t row0, int32_t n_rows, lpq_qweight* out,
+                                  void* hip_stream)
+{
+    if (!w_rows_fp16 || !desc || !out) return LPQ_ERR_NULL;
+    lpq_status st = check_quantize_target(desc, out);
+    if (st != LPQ_OK) return st;
+    if (row0 < 0 || n_rows < 0 || row0 % 64 != 0 || n_rows % 64 != 0 || (int64_t)row0 + n_rows > desc->N) return LPQ_ERR_SHAPE;
+    if (misaligned(w_rows_fp16)) return LPQ_ERR_ALIGN;
+    return launch_quantize_pack(w_rows_fp16, *desc, row0, n_rows, *out, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? LPQ_OK : LPQ_ERR_DEVICE;
+}
+
+lpq_status lpq_load_quantize_pack(const void* w_fp16_host, const lpq_qdesc* desc, lpq_qweight* out, void* staging, size_t staging_bytes,
+                                  void* hip_stream)
+{
+    if (!w_fp16_host || !desc || !out || !staging) return LPQ_ERR_NULL;
+    lpq_status st = check_quantize_target(desc, out);
+    if (st != LPQ_OK) return st;
+    if (misaligned(w_fp16_host) || misaligned(staging)) return LPQ_ERR_ALIGN;
+    const size_t row_bytes = (size_t)desc->K * 2;
+    const size_t half = (staging_bytes / 2) & ~(size_t)255;              // keeps the second half 16-byte aligned
+    const int64_t chunk_rows = std::min<int64_t>((int64_t)(half / row_bytes) / 64 * 64, desc->N);
+    if (chunk_rows < 64) return LPQ_ERR_BUFSIZE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipStream_t copy = nullptr;
+    st = copy_stream(&copy);
+    if (st != LPQ_OK) return st;
+    // copied[b]: chunk in staging half b has arrived; consumed[b]: its quantisation has been enqueued and,
+    // once the event fires, finished -- only then may the next copy overwrite that half
+    hipEvent_t copied[2] = {nullptr, nullptr}, consumed[2] = {nullptr, nullptr};
+    bool ok = true;
+    for (int b = 0; b < 2 && ok; ++b)
+        ok = hipEventCreateWithFlags(&copied[b], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&consumed[b], hipEventDisableTiming) == hipSuccess;
+    // the copy stream starts after whatever the caller already queued on its stream (which may still use staging)
+    hipEvent_t start = nullptr;
+    ok = ok && hipEventCreateWithFlags(&start, hipEventDisableTiming) == hipSuccess && hipEventRecord(start, stream) == hipSuccess &&
+         hipStreamWaitEvent(copy, start, 0) == hipSuccess;
+    int64_t row = 0;
+    for (int c = 0; ok && row < desc->N; ++c, row += chunk_rows) {
+        const int b = c & 1;
+        const int64_t rows = std::min<int64_t>(chunk_rows, desc->N - row);
+        uint8_t* dst = static_cast<uint8_t*>(staging) + (size_t)b * half;
+        if (c >= 2) ok = hipStreamWaitEvent(copy, consumed[b], 0) == hipSuccess;
+        ok = ok && hipMemcpyAsync(dst, static_cast<const uint8_t*>(w_fp16_host) + (size_t)row * row_bytes, (size_t)rows * row_bytes,
+                                  hipMemcpyHostToDevice, copy) == hipSuccess;
+        ok = ok && hipEventRecord(copied[b], copy) == hipSuccess && hipStreamWaitEvent(stream, copied[b], 0) == hipSuccess;
+        ok = ok && launch_quantize_pack(dst, *desc, row, rows, *out, stream) == hipSuccess;
+        ok = ok && hipEventRecord(consumed[b], stream) == hipSuccess;
+    }
+    // destroying an event that is still pending only releases it once it has completed
+    for (int b = 0; b < 2; ++b) {
+        if (copied[b]) (void)hipEventDestroy(copied[b]);
+        if (consumed[b]) (void)hipEventDestroy(consumed[b]);
+    }
+    if (start) (void)hipEventDestroy(start);
+    return ok ? LPQ_OK : LPQ_ERR_DEVICE;
 }
 
 lpq_status lpq_unpack_dequant(const lpq_qweight* w, void* w_fp32, void* hip_stream)

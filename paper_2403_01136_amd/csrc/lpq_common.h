@@ -97,7 +97,8 @@ int variant_of(const lpq_qdesc& d);           // -1 if the (bits, scheme) pair i
 size_t tile_bytes_of(int variant);
 
 // launchers (each returns a hipError_t from the launch)
-hipError_t launch_quantize_pack(const void* w, const lpq_qdesc& d, const lpq_qweight& out, hipStream_t s);
+// rows [row0, row0 + n_rows) of W (multiples of 64), read from a buffer that holds just those rows
+hipError_t launch_quantize_pack(const void* w_rows, const lpq_qdesc& d, long row0, long n_rows, const lpq_qweight& out, hipStream_t s);
 hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);

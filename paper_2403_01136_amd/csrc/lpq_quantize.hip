@@ -17,6 +17,9 @@ namespace lpq {
 
 namespace {
 
+// The 64-row blocks [rb0, rb0 + n_rb) of W that a launch quantises; the source pointer starts at row 64 * rb0.
+struct RowWindow { long rb0, n_rb; };
+
 __device__ __forceinline__ uint16_t f2h_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 __device__ __forceinline__ float h2f_bits(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
 
@@ -78,19 +81,19 @@ __device__ __forceinline__ void store_packed(uint8_t* __restrict__ codes, long t
 
 // grouped asymmetric scheme: one (row, 128 columns) group per 4 lanes
 template <int BITS>
-__global__ __launch_bounds__(256) void quantize_asym_kernel(const uint16_t* __restrict__ w, int K, long NT,
+__global__ __launch_bounds__(256) void quantize_asym_kernel(const uint16_t* __restrict__ w, int K, long NT, RowWindow win,
                                                             uint8_t* __restrict__ codes, uint16_t* __restrict__ scales,
                                                             uint16_t* __restrict__ zeros)
 {
     const int KT = K / 128;
-    const long tile = (long)blockIdx.x * 4 + (threadIdx.x >> 6);      // ((rb * KT + kt) * 4 + t)
-    if (tile >= NT * KT) return;
+    const long tile = win.rb0 * KT * 4 + (long)blockIdx.x * 4 + (threadIdx.x >> 6);      // ((rb * KT + kt) * 4 + t)
+    if (tile >= (win.rb0 + win.n_rb) * KT * 4) return;
     const int lane = threadIdx.x & 63, t = (int)(tile & 3);
     const long rb = (tile >> 2) / KT;
     const int kt = (int)((tile >> 2) % KT);
     const long n = rb * 64 + 4 * (lane & 15) + t;
     float v[32];
-    load_owned(w, K, n, kt, lane, v);
+    load_owned(w, K, n - 64 * win.rb0, kt, lane, v);
     float lo = v[0], hi = v[0];
 #pragma unroll
     for (int i = 1; i < 32; ++i) { lo = fminf(lo, v[i]); hi = fmaxf(hi, v[i]); }
@@ -118,11 +121,11 @@ __global__ __launch_bounds__(256) void quantize_asym_kernel(const uint16_t* __re
 }
 
 // per-row symmetric scheme, pass 1: scale[n] = fp16(max|w[n,:]| / 127)
-__global__ __launch_bounds__(256) void row_absmax_scale_kernel(const uint16_t* __restrict__ w, int K, uint16_t* __restrict__ scales)
+__global__ __launch_bounds__(256) void row_absmax_scale_kernel(const uint16_t* __restrict__ w, int K, RowWindow win, uint16_t* __restrict__ scales)
 {
     __shared__ float red[4];
-    const long n = blockIdx.x;
-    const uint16_t* row = w + n * K;
+    const long n = 64 * win.rb0 + blockIdx.x;
+    const uint16_t* row = w + (long)blockIdx.x * K;
     float a = 0.0f;
     for (int k = threadIdx.x * 8; k < K; k += 256 * 8) {
         const h8 t = *reinterpret_cast<const h8*>(row + k);
@@ -142,18 +145,18 @@ __global__ __launch_bounds__(256) void row_absmax_scale_kernel(const uint16_t* _
 }
 
 // per-row symmetric scheme, pass 2: code = clamp(rint(w / scale), -127, 127)
-__global__ __launch_bounds__(256) void quantize_sym_kernel(const uint16_t* __restrict__ w, int K, long NT,
+__global__ __launch_bounds__(256) void quantize_sym_kernel(const uint16_t* __restrict__ w, int K, RowWindow win,
                                                            uint8_t* __restrict__ codes, const uint16_t* __restrict__ scales)
 {
     const int KT = K / 128;
-    const long tile = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= NT * KT) return;
+    const long tile = win.rb0 * KT * 4 + (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= (win.rb0 + win.n_rb) * KT * 4) return;
     const int lane = threadIdx.x & 63, t = (int)(tile & 3);
     const long rb = (tile >> 2) / KT;
     const int kt = (int)((tile >> 2) % KT);
     const long n = rb * 64 + 4 * (lane & 15) + t;
     float v[32];
-    load_owned(w, K, n, kt, lane, v);
+    load_owned(w, K, n - 64 * win.rb0, kt, lane, v);
     const float sf = h2f_bits(scales[n]);
     int c[32];
 #pragma unroll
@@ -165,16 +168,16 @@ __global__ __launch_bounds__(256) void quantize_sym_kernel(const uint16_t* __res
 }
 
 // 16-bit layers: the fp16 weights unchanged, reordered into tiles (piece j of a lane = operand of MFMA step j)
-__global__ __launch_bounds__(256) void pack_fp16_kernel(const uint16_t* __restrict__ w, int K, long NT, uint8_t* __restrict__ codes)
+__global__ __launch_bounds__(256) void pack_fp16_kernel(const uint16_t* __restrict__ w, int K, RowWindow win, uint8_t* __restrict__ codes)
 {
     const int KT = K / 128;
-    const long tile = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= NT * KT) return;
+    const long tile = win.rb0 * KT * 4 + (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= (win.rb0 + win.n_rb) * KT * 4) return;
     const int lane = threadIdx.x & 63, t = (int)(tile & 3);
     const long rb = (tile >> 2) / KT;
     const int kt = (int)((tile >> 2) % KT);
     const long n = rb * 64 + 4 * (lane & 15) + t;
-    const uint16_t* p = w + n * K + (long)kt * 128 + 8 * (lane >> 4);
+    const uint16_t* p = w + (n - 64 * win.rb0) * K + (long)kt * 128 + 8 * (lane >> 4);
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         *reinterpret_cast<u32x4*>(codes + tile * 4096 + 1024 * j + 16 * lane) = *reinterpret_cast<const u32x4*>(p + 32 * j);
@@ -233,25 +236,26 @@ __global__ __launch_bounds__(256) void unpack_dequant_kernel(const uint8_t* __re
 
 }  // namespace
 
-hipError_t launch_quantize_pack(const void* w, const lpq_qdesc& d, const lpq_qweight& out, hipStream_t s)
+hipError_t launch_quantize_pack(const void* w_rows, const lpq_qdesc& d, long row0, long n_rows, const lpq_qweight& out, hipStream_t s)
 {
     const long NT = d.N / 16;
     const int KT = d.K / 128;
-    const long tiles = NT * KT;
-    const unsigned blocks = (unsigned)((tiles + 3) / 4);
-    const uint16_t* wp = static_cast<const uint16_t*>(w);
+    const RowWindow win = {row0 / 64, n_rows / 64};
+    const unsigned blocks = (unsigned)(win.n_rb * KT);           // four tiles (one 64-row block step) per workgroup
+    const uint16_t* wp = static_cast<const uint16_t*>(w_rows);
     uint8_t* codes = static_cast<uint8_t*>(out.codes);
     uint16_t* sc = static_cast<uint16_t*>(out.scales);
     uint16_t* zr = static_cast<uint16_t*>(out.zeros);
+    if (blocks == 0) return hipSuccess;
     switch (variant_of(d)) {
-    case V_W3: quantize_asym_kernel<3><<<blocks, 256, 0, s>>>(wp, d.K, NT, codes, sc, zr); break;
-    case V_W4: quantize_asym_kernel<4><<<blocks, 256, 0, s>>>(wp, d.K, NT, codes, sc, zr); break;
-    case V_W8: quantize_asym_kernel<8><<<blocks, 256, 0, s>>>(wp, d.K, NT, codes, sc, zr); break;
+    case V_W3: quantize_asym_kernel<3><<<blocks, 256, 0, s>>>(wp, d.K, NT, win, codes, sc, zr); break;
+    case V_W4: quantize_asym_kernel<4><<<blocks, 256, 0, s>>>(wp, d.K, NT, win, codes, sc, zr); break;
+    case V_W8: quantize_asym_kernel<8><<<blocks, 256, 0, s>>>(wp, d.K, NT, win, codes, sc, zr); break;
     case V_I8:
-        row_absmax_scale_kernel<<<(unsigned)d.N, 256, 0, s>>>(wp, d.K, sc);
-        quantize_sym_kernel<<<blocks, 256, 0, s>>>(wp, d.K, NT, codes, sc);
+        row_absmax_scale_kernel<<<(unsigned)n_rows, 256, 0, s>>>(wp, d.K, win, sc);
+        quantize_sym_kernel<<<blocks, 256, 0, s>>>(wp, d.K, win, codes, sc);
         break;
-    case V_F16: pack_fp16_kernel<<<blocks, 256, 0, s>>>(wp, d.K, NT, codes); break;
+    case V_F16: pack_fp16_kernel<<<blocks, 256, 0, s>>>(wp, d.K, win, codes); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

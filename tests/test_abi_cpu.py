@@ -79,6 +79,20 @@ def test_entry_points_validate_before_touching_the_device():
     # descriptor mismatch between desc and out
     d2 = lpq.make_desc(3, 1, 128, 64)
     assert lib.lpq_quantize_pack(fake, ctypes.byref(d2), ctypes.byref(good), None) == 4
+    # row windows: on 64-row boundaries and inside W
+    d3 = lpq.make_desc(4, 1, 128, 192)
+    w3 = lpq.lpq_qweight(d3, fake, fake, fake, None)
+    for row0, n_rows in ((32, 64), (0, 100), (128, 128), (-64, 64), (0, -64)):
+        assert lib.lpq_quantize_pack_rows(fake, ctypes.byref(d3), row0, n_rows, ctypes.byref(w3), None) == 4
+    assert lib.lpq_quantize_pack_rows(None, ctypes.byref(d3), 0, 64, ctypes.byref(w3), None) == 1
+    assert lib.lpq_quantize_pack_rows(fake + 2, ctypes.byref(d3), 0, 64, ctypes.byref(w3), None) == 5
+    # loader: NULL host or staging pointer, misaligned pointers, staging halves too small for 64 rows
+    assert lib.lpq_load_quantize_pack(None, ctypes.byref(d3), ctypes.byref(w3), fake, 1 << 20, None) == 1
+    assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d3), ctypes.byref(w3), None, 1 << 20, None) == 1
+    assert lib.lpq_load_quantize_pack(fake + 8, ctypes.byref(d3), ctypes.byref(w3), fake, 1 << 20, None) == 5
+    assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d3), ctypes.byref(w3), fake + 4, 1 << 20, None) == 5
+    assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d3), ctypes.byref(w3), fake, 2 * 64 * 128 * 2 - 1, None) == 6
+    assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d2), ctypes.byref(w3), fake, 1 << 20, None) == 4
     # bad bits inside a weight
     bad = lpq.lpq_qweight(lpq.lpq_qdesc(5, 1, 128, 128, 64), fake, fake, fake, None)
     assert lib.lpq_qlinear_decode(ctypes.byref(bad), fake, 1, fake, None) == 2

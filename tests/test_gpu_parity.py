@@ -57,6 +57,43 @@ def test_quantize_pack_edge_groups(orc, bits, scheme):
     assert np.array_equal(deq.view(np.uint32), orc.dequant_weights(w, bits, scheme).view(np.uint32))
 
 
+# ---- quantise a weight piecewise, and stream it from host memory (Sec. 5, on-the-fly quantizer) ----
+
+@pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
+def test_quantize_pack_rows_any_order(orc, bits, scheme):
+    """Row windows quantised out of order, from buffers that hold only those rows, give the same packed
+    weight as one call over the whole matrix (and the oracle)."""
+    import torch
+    N, K = 448, 384
+    w = wl.weight_np(N, K, "rows", bits, scheme)
+    qw = lpq.QWeight(bits, scheme, K, N, torch.device("cuda"))
+    for t in (qw.codes, qw.scales, qw.zeros):
+        if t is not None:
+            t.view(torch.uint8).fill_(0xA5)
+    for row0, n_rows in ((256, 192), (0, 64), (64, 0), (128, 128), (64, 64)):
+        lpq.lpq_quantize_pack_rows(to_dev(w[row0:row0 + n_rows]), qw, row0)
+    check_packed(qw, orc, w)
+
+
+@pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("pinned", [True, False], ids=["pinned", "pageable"])
+def test_load_quantize_pack_from_host(orc, bits, scheme, pinned):
+    """Streaming from host memory through two staging halves (several chunks, a ragged last one) is
+    bit-identical to quantising the resident weight; then the linear runs on the result."""
+    import torch
+    N, K, M = 704, 256, 8
+    w = wl.weight_np(N, K, "load", bits, scheme)
+    w_host = torch.from_numpy(w.copy())
+    if pinned:
+        w_host = w_host.pin_memory()
+    staging = torch.empty(2 * 192 * K * 2 + 300, dtype=torch.uint8, device="cuda")      # 192-row chunks: 3 full + 128 rows
+    qw = lpq.lpq_load_quantize_pack(w_host, bits, scheme, staging)
+    torch.cuda.synchronize()
+    check_packed(qw, orc, w)
+    x = wl.act_np(M, K, True, "load", M)
+    check_output(lpq.lpq_qlinear_decode(qw, to_dev(x)), orc.qlinear(x, w, bits, scheme), "decode after load %d-bit" % bits)
+
+
 # ---- a3: decode linear ---------------------------------------------------------------------
 
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)

@@ -112,6 +112,13 @@ typedef struct {
 
 typedef enum { LPQ_PREFILL = 0, LPQ_DECODE = 1 } lpq_phase;
 
+/* What a linear does to acc + bias before its one rounding to fp16 (used by the decoder layer). */
+typedef enum { LPQ_ACT_NONE = 0, LPQ_ACT_RELU = 1, LPQ_ACT_GELU_TANH = 2 } lpq_activation;
+typedef struct {
+    int32_t activation;      /* lpq_activation, applied to acc + bias                               */
+    const void *residual;    /* device fp16 [M][N] added after the activation, or NULL              */
+} lpq_epilogue;
+
 /* Bytes of the three packed buffers of a weight (Sec. 4.1: codes = K*N*bits/8, dense).
  * Host-only, touches no device.  Errors: NULL, BITS, SCHEME, SHAPE. */
 lpq_status lpq_packed_sizes(const lpq_qdesc *desc, size_t *code_bytes, size_t *scale_bytes, size_t *zero_bytes);
@@ -165,6 +172,13 @@ lpq_status lpq_qlinear_prefill(const lpq_qweight *w, const void *x, int32_t M, v
  * M >= 1 (rows are processed 64 at a time).  Errors as for lpq_qlinear_prefill, plus BUFSIZE. */
 lpq_status lpq_qlinear_decode(const lpq_qweight *w, const void *x, int32_t M, void *y, void *hip_stream);
 
+/* One linear with a fused epilogue: y = fp16(act(x . w~^T + bias) + residual), one rounding.  `phase`
+ * picks the kernel family as in lpq_stage_linears.  ep may be NULL (= lpq_qlinear_prefill / _decode).
+ * residual may alias y (each element is read before it is written, by the same thread).
+ * Errors: as the plain calls; UNSUPPORTED for an unknown activation. */
+lpq_status lpq_qlinear_fused(const lpq_qweight *w, const void *x, int32_t M, void *y, const lpq_epilogue *ep,
+                             lpq_phase phase, void *hip_stream);
+
 /* All 4 * n_layers linears of a stage, each layer at its own bitwidth (Sec. 4.3: stage
  * latency is the sum over its layers of the per-layer latency at that layer's precision).
  *   layers: host array [n_layers];  io: host array [n_layers] of device pointers.
@@ -173,6 +187,59 @@ lpq_status lpq_qlinear_decode(const lpq_qweight *w, const void *x, int32_t M, vo
  * Errors: as above; nothing is launched unless every layer validates. */
 lpq_status lpq_stage_linears(const lpq_layer *layers, int32_t n_layers, lpq_phase phase, int32_t M,
                              const lpq_layer_io *io, void *hip_stream);
+
+/* ---- The rest of the decoder layer (beyond the hot path of the four linears) -------------------------
+ * The published pre-LayerNorm decoder block of the paper's models, with the KV cache reserved for
+ * max_seq = s + n positions per sequence (Sec. 4.1, "KV Storage Modeling"; Sec. 5):
+ *   h1 = LN1(x); qkv = h1 . Wqkv^T; append K, V at positions pos0 .. pos0+T-1; a = attention(q, cache);
+ *   x1 = x + a . Wout^T; h2 = LN2(x1); f = act(h2 . Wfc1^T); y = x1 + f . Wfc2^T
+ * with every operator's output rounded once to fp16.  Token rows are ordered [sequence][token]:
+ * M = n_seqs * T rows, T = 1 in the decode phase; all sequences of a call are at the same position pos0.
+ * Caches (device, fp16, caller-owned, one pair per layer): k_cache [batch][n_heads][max_seq][head_dim],
+ * vt_cache [batch][n_heads][head_dim][max_seq] (V transposed: a feature's positions are contiguous). */
+typedef struct {
+    int32_t n_heads, head_dim;   /* hidden size = n_heads * head_dim; head_dim is 64 or 128                */
+    int32_t max_seq;             /* cache positions per sequence, a multiple of 64                         */
+    int32_t activation;          /* lpq_activation of the feed-forward block                               */
+    float ln_eps;
+} lpq_layer_cfg;
+
+typedef struct {
+    const void *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;   /* device fp16 [hidden]                     */
+    void *k_cache, *vt_cache;                                  /* device fp16, layouts above               */
+    const float *alibi_slopes;   /* device fp32 [n_heads]: score += slope * (key position - query position), or NULL */
+} lpq_layer_state;
+
+/* y[m][:] = (x[m][:] - mean) / sqrt(var + eps) * gamma + beta per row (biased variance), fp32 statistics.
+ * x, y: device fp16 [M][hidden]; hidden % 8 == 0, hidden <= 16384.  Errors: NULL, SHAPE, ALIGN, DEVICE. */
+lpq_status lpq_layernorm(const void *x, const void *gamma, const void *beta, float eps, int32_t M, int32_t hidden, void *y,
+                         void *hip_stream);
+
+/* Copy the K and V parts of qkv (device fp16 [n_seqs * T][3 * hidden]; per token q | k | v, heads of
+ * head_dim each) into the caches at positions pos0 .. pos0 + T - 1 of sequences 0 .. n_seqs - 1.
+ * Errors: NULL, SHAPE (head_dim, max_seq, pos0 + T > max_seq, counts < 1), ALIGN, DEVICE. */
+lpq_status lpq_kv_append(const void *qkv, const lpq_layer_cfg *cfg, const lpq_layer_state *st, int32_t n_seqs, int32_t T,
+                         int32_t pos0, void *hip_stream);
+
+/* Causal attention of the T new tokens of each sequence over cache positions 0 .. pos0 + t:
+ * out = softmax(q . k / sqrt(head_dim) + alibi) . v per head, heads concatenated; queries are the q part of
+ * qkv; the caches must already hold positions < pos0 + T (lpq_kv_append).  out: device fp16 [n_seqs * T][hidden].
+ * T = 1 streams the cache once (split over positions when there are few sequences, partial results in the
+ * library's workspace); T > 1 runs on the matrix cores.  Errors: as lpq_kv_append, plus BUFSIZE. */
+lpq_status lpq_attention(const void *qkv, const lpq_layer_cfg *cfg, const lpq_layer_state *st, int32_t n_seqs, int32_t T,
+                         int32_t pos0, void *out, void *hip_stream);
+
+/* Bytes of workspace lpq_decoder_layer needs for M = n_seqs * T token rows (0 on a bad argument). */
+size_t lpq_decoder_layer_workspace(const lpq_layer *layer, const lpq_layer_cfg *cfg, int32_t M);
+
+/* One decoder layer: x, y device fp16 [n_seqs * T][hidden] (y may be x); `layer` holds the four quantised
+ * linears (their K, N must match hidden and the feed-forward size; biases optional); `workspace` is a
+ * caller-owned device buffer of at least lpq_decoder_layer_workspace bytes, 16-byte aligned.  `phase`
+ * picks the linears' kernel family; attention follows T.  Updates the caches at pos0 .. pos0 + T - 1.
+ * Errors: NULL, BITS, SCHEME, SHAPE, ALIGN, BUFSIZE, DEVICE, UNSUPPORTED (activation). */
+lpq_status lpq_decoder_layer(const lpq_layer *layer, const lpq_layer_cfg *cfg, const lpq_layer_state *st, lpq_phase phase,
+                             int32_t n_seqs, int32_t T, int32_t pos0, const void *x, void *y, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
 
 /* Test helper, not on the hot path: w_fp32[n][k] = scale * code + zero (fp32 multiply, then
  * fp32 add; the fp16 weight itself for LPQ_FP16) read back from the packed buffers.

@@ -16,7 +16,10 @@ LPQ_PREFILL, LPQ_DECODE = 0, 1
 LPQ_OK = 0
 LINEARS = ("qkv", "out", "fc1", "fc2")
 EXPORTS = ("lpq_packed_sizes", "lpq_quantize_pack", "lpq_quantize_pack_rows", "lpq_load_quantize_pack",
-           "lpq_qlinear_prefill", "lpq_qlinear_decode", "lpq_stage_linears", "lpq_unpack_dequant", "lpq_status_str")
+           "lpq_qlinear_prefill", "lpq_qlinear_decode", "lpq_qlinear_fused", "lpq_stage_linears", "lpq_layernorm",
+           "lpq_kv_append", "lpq_attention", "lpq_decoder_layer_workspace", "lpq_decoder_layer", "lpq_unpack_dequant",
+           "lpq_status_str")
+LPQ_ACT_NONE, LPQ_ACT_RELU, LPQ_ACT_GELU_TANH = 0, 1, 2
 
 
 class lpq_qdesc(ctypes.Structure):
@@ -35,6 +38,21 @@ class lpq_layer(ctypes.Structure):
 
 class lpq_layer_io(ctypes.Structure):
     _fields_ = [("x_" + n, ctypes.c_void_p) for n in LINEARS] + [("y_" + n, ctypes.c_void_p) for n in LINEARS]
+
+
+class lpq_epilogue(ctypes.Structure):
+    _fields_ = [("activation", ctypes.c_int32), ("residual", ctypes.c_void_p)]
+
+
+class lpq_layer_cfg(ctypes.Structure):
+    _fields_ = [("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("max_seq", ctypes.c_int32),
+                ("activation", ctypes.c_int32), ("ln_eps", ctypes.c_float)]
+
+
+class lpq_layer_state(ctypes.Structure):
+    _fields_ = [("ln1_gamma", ctypes.c_void_p), ("ln1_beta", ctypes.c_void_p), ("ln2_gamma", ctypes.c_void_p),
+                ("ln2_beta", ctypes.c_void_p), ("k_cache", ctypes.c_void_p), ("vt_cache", ctypes.c_void_p),
+                ("alibi_slopes", ctypes.c_void_p)]
 
 
 class LpqError(RuntimeError):
@@ -63,11 +81,18 @@ def load_library():
         L.lpq_qlinear_prefill.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, vp]
         L.lpq_qlinear_decode.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, vp]
         L.lpq_stage_linears.argtypes = [ctypes.POINTER(lpq_layer), i32, ctypes.c_int, i32, ctypes.POINTER(lpq_layer_io), vp]
+        L.lpq_qlinear_fused.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, ctypes.POINTER(lpq_epilogue), ctypes.c_int, vp]
+        L.lpq_layernorm.argtypes = [vp, vp, vp, ctypes.c_float, i32, i32, vp, vp]
+        cfgp, stp = ctypes.POINTER(lpq_layer_cfg), ctypes.POINTER(lpq_layer_state)
+        L.lpq_kv_append.argtypes = [vp, cfgp, stp, i32, i32, i32, vp]
+        L.lpq_attention.argtypes = [vp, cfgp, stp, i32, i32, i32, vp, vp]
+        L.lpq_decoder_layer_workspace.argtypes = [ctypes.POINTER(lpq_layer), cfgp, i32]
+        L.lpq_decoder_layer.argtypes = [ctypes.POINTER(lpq_layer), cfgp, stp, ctypes.c_int, i32, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
         L.lpq_unpack_dequant.argtypes = [ctypes.POINTER(lpq_qweight), vp, vp]
         L.lpq_status_str.argtypes = [ctypes.c_int]
         L.lpq_status_str.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
-            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).restype = ctypes.c_size_t if name == "lpq_decoder_layer_workspace" else ctypes.c_int
         _lib = L
     return _lib
 
@@ -187,6 +212,83 @@ def lpq_qlinear_prefill(qw, x, y=None, stream=None):
 
 def lpq_qlinear_decode(qw, x, y=None, stream=None):
     return _qlinear("lpq_qlinear_decode", qw, x, y, stream)
+
+
+def lpq_qlinear_fused(qw, x, phase, activation=LPQ_ACT_NONE, residual=None, y=None, stream=None):
+    """y = fp16(act(x . w~^T + bias) + residual) with one rounding; residual may be y itself."""
+    import torch
+    x = _fp16_2d(x, "x")
+    M = x.shape[0]
+    if y is None:
+        y = torch.empty((M, qw.N), dtype=torch.float16, device=x.device)
+    if residual is not None and tuple(_fp16_2d(residual, "residual").shape) != (M, qw.N):
+        raise ValueError("residual must be [%d][%d]" % (M, qw.N))
+    st = qw.struct()
+    ep = lpq_epilogue(int(activation), residual.data_ptr() if residual is not None else None)
+    _check(load_library().lpq_qlinear_fused(ctypes.byref(st), x.data_ptr(), M, _fp16_2d(y, "y").data_ptr(), ctypes.byref(ep),
+                                            int(phase), _stream(stream)), "lpq_qlinear_fused")
+    return y
+
+
+def lpq_layernorm(x, gamma, beta, eps, y=None, stream=None):
+    import torch
+    x = _fp16_2d(x, "x")
+    if y is None:
+        y = torch.empty_like(x)
+    _check(load_library().lpq_layernorm(x.data_ptr(), gamma.data_ptr(), beta.data_ptr(), float(eps), x.shape[0], x.shape[1],
+                                        y.data_ptr(), _stream(stream)), "lpq_layernorm")
+    return y
+
+
+class LayerState:
+    """Caller-owned state of one decoder layer: layer-norm parameters, the pre-allocated KV cache
+    (k_cache [batch][heads][max_seq][head_dim], vt_cache [batch][heads][head_dim][max_seq]), optional ALiBi slopes."""
+
+    def __init__(self, n_heads, head_dim, max_seq, batch, device, ln1, ln2, activation=LPQ_ACT_RELU, ln_eps=1e-5, alibi_slopes=None):
+        import torch
+        self.cfg = lpq_layer_cfg(n_heads, head_dim, max_seq, int(activation), float(ln_eps))
+        self.ln1, self.ln2, self.alibi = ln1, ln2, alibi_slopes
+        self.k_cache = torch.zeros((batch, n_heads, max_seq, head_dim), dtype=torch.float16, device=device)
+        self.vt_cache = torch.zeros((batch, n_heads, head_dim, max_seq), dtype=torch.float16, device=device)
+
+    def struct(self):
+        return lpq_layer_state(self.ln1[0].data_ptr(), self.ln1[1].data_ptr(), self.ln2[0].data_ptr(), self.ln2[1].data_ptr(),
+                               self.k_cache.data_ptr(), self.vt_cache.data_ptr(),
+                               self.alibi.data_ptr() if self.alibi is not None else None)
+
+
+def lpq_kv_append(qkv, state, n_seqs, T, pos0, stream=None):
+    st = state.struct()
+    _check(load_library().lpq_kv_append(_fp16_2d(qkv, "qkv").data_ptr(), ctypes.byref(state.cfg), ctypes.byref(st), n_seqs, T, pos0,
+                                        _stream(stream)), "lpq_kv_append")
+
+
+def lpq_attention(qkv, state, n_seqs, T, pos0, out=None, stream=None):
+    import torch
+    qkv = _fp16_2d(qkv, "qkv")
+    if out is None:
+        out = torch.empty((qkv.shape[0], qkv.shape[1] // 3), dtype=torch.float16, device=qkv.device)
+    st = state.struct()
+    _check(load_library().lpq_attention(qkv.data_ptr(), ctypes.byref(state.cfg), ctypes.byref(st), n_seqs, T, pos0, out.data_ptr(),
+                                        _stream(stream)), "lpq_attention")
+    return out
+
+
+def lpq_decoder_layer(layer, state, phase, n_seqs, T, pos0, x, y=None, workspace=None, stream=None):
+    """layer: dict name -> QWeight (qkv, out, fc1, fc2); state: LayerState.  Returns (y, workspace)."""
+    import torch
+    x = _fp16_2d(x, "x")
+    if y is None:
+        y = torch.empty_like(x)
+    ls = lpq_layer(*[layer[n].struct() for n in LINEARS])
+    need = load_library().lpq_decoder_layer_workspace(ctypes.byref(ls), ctypes.byref(state.cfg), x.shape[0])
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    st = state.struct()
+    _check(load_library().lpq_decoder_layer(ctypes.byref(ls), ctypes.byref(state.cfg), ctypes.byref(st), int(phase), n_seqs, T, pos0,
+                                            x.data_ptr(), y.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "lpq_decoder_layer")
+    return y, workspace
 
 
 class Stage:

@@ -162,6 +162,8 @@ struct LinearCall {
     const lpq_qweight* w;
     const void* x;
     void* y;
+    const void* residual = nullptr;
+    int32_t act = LPQ_ACT_NONE;
 };
 
 // Decode-phase dispatch of a list of independent linears: grouped launches of at most
@@ -200,6 +202,9 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
             L.x = static_cast<const uint16_t*>(calls[c].x);
             L.y = static_cast<uint16_t*>(calls[c].y);
             L.bias = static_cast<const uint16_t*>(w.bias);
+            L.residual = static_cast<const uint16_t*>(calls[c].residual);
+            L.act = calls[c].act;
+            L.pad = 0;
             L.K = w.d.K;
             L.N = w.d.N;
             L.variant = variant_of(w.d);
@@ -269,11 +274,12 @@ lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStrea
                 L.x = static_cast<const uint16_t*>(mine[i]->x);
                 L.y = static_cast<uint16_t*>(mine[i]->y);
                 L.bias = static_cast<const uint16_t*>(w.bias);
+                L.residual = static_cast<const uint16_t*>(mine[i]->residual);
+                L.act = mine[i]->act;
                 L.K = w.d.K;
                 L.N = w.d.N;
                 L.n_blocks = (w.d.N + 255) / 256;
                 L.token_groups = prefill_token_groups(m_blocks, L.n_blocks);
-                L.pad = 0;
                 L.tile_begin = (int32_t)tiles;
                 tiles += 8L * prefill_xcd_tiles(m_blocks, L.n_blocks, L.token_groups);
             }
@@ -283,6 +289,32 @@ lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStrea
         }
     }
     return LPQ_OK;
+}
+
+lpq_status check_attention_args(const lpq_layer_cfg* cfg, const lpq_layer_state* st, int32_t n_seqs, int32_t T, int32_t pos0)
+{
+    if (!st->k_cache || !st->vt_cache) return LPQ_ERR_NULL;
+    if (cfg->n_heads < 1 || (cfg->head_dim != 64 && cfg->head_dim != 128) || cfg->max_seq < 64 || cfg->max_seq % 64 != 0) return LPQ_ERR_SHAPE;
+    if (n_seqs < 1 || T < 1 || pos0 < 0 || (int64_t)pos0 + T > cfg->max_seq) return LPQ_ERR_SHAPE;
+    if (misaligned(st->k_cache) || misaligned(st->vt_cache) || (reinterpret_cast<uintptr_t>(st->alibi_slopes) & 3u)) return LPQ_ERR_ALIGN;
+    return LPQ_OK;
+}
+
+lpq_status run_attention(const void* qkv, const lpq_layer_cfg* cfg, const lpq_layer_state* st, int32_t n_seqs, int32_t T, int32_t pos0,
+                         void* out, hipStream_t stream)
+{
+    float* part = nullptr;
+    if (T == 1) {
+        int range = 0, splits = 0;
+        attention_decode_plan(n_seqs, cfg->n_heads, pos0 + 1, &range, &splits);
+        const size_t floats = attention_decode_workspace_floats(n_seqs, cfg->n_heads, cfg->head_dim, splits);
+        if (floats) {
+            lpq_status s = workspace(floats * sizeof(float), &part);
+            if (s != LPQ_OK) return s;
+        }
+    }
+    return launch_attention(qkv, st->k_cache, st->vt_cache, st->alibi_slopes, n_seqs, T, pos0, cfg->n_heads, cfg->head_dim, cfg->max_seq,
+                            out, part, stream) == hipSuccess ? LPQ_OK : LPQ_ERR_DEVICE;
 }
 
 }  // namespace
@@ -372,6 +404,85 @@ lpq_status lpq_load_quantize_pack(const void* w_fp16_host, const lpq_qdesc* desc
     return ok ? LPQ_OK : LPQ_ERR_DEVICE;
 }
 
+lpq_status lpq_layernorm(const void* x, const void* gamma, const void* beta, float eps, int32_t M, int32_t hidden, void* y, void* hip_stream)
+{
+    if (!x || !gamma || !beta || !y) return LPQ_ERR_NULL;
+    if (M < 1 || hidden < 8 || hidden % 8 != 0 || hidden > layernorm_max_hidden() || !(eps >= 0.0f)) return LPQ_ERR_SHAPE;
+    if (misaligned(x) || misaligned(gamma) || misaligned(beta) || misaligned(y)) return LPQ_ERR_ALIGN;
+    return launch_layernorm(x, gamma, beta, eps, M, hidden, y, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPQ_OK : LPQ_ERR_DEVICE;
+}
+
+lpq_status lpq_kv_append(const void* qkv, const lpq_layer_cfg* cfg, const lpq_layer_state* st, int32_t n_seqs, int32_t T, int32_t pos0,
+                         void* hip_stream)
+{
+    if (!qkv || !cfg || !st) return LPQ_ERR_NULL;
+    lpq_status s = check_attention_args(cfg, st, n_seqs, T, pos0);
+    if (s != LPQ_OK) return s;
+    if (misaligned(qkv)) return LPQ_ERR_ALIGN;
+    return launch_kv_append(qkv, st->k_cache, st->vt_cache, n_seqs, T, pos0, cfg->n_heads, cfg->head_dim, cfg->max_seq,
+                            static_cast<hipStream_t>(hip_stream)) == hipSuccess ? LPQ_OK : LPQ_ERR_DEVICE;
+}
+
+lpq_status lpq_attention(const void* qkv, const lpq_layer_cfg* cfg, const lpq_layer_state* st, int32_t n_seqs, int32_t T, int32_t pos0,
+                         void* out, void* hip_stream)
+{
+    if (!qkv || !cfg || !st || !out) return LPQ_ERR_NULL;
+    lpq_status s = check_attention_args(cfg, st, n_seqs, T, pos0);
+    if (s != LPQ_OK) return s;
+    if (misaligned(qkv) || misaligned(out)) return LPQ_ERR_ALIGN;
+    return run_attention(qkv, cfg, st, n_seqs, T, pos0, out, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t lpq_decoder_layer_workspace(const lpq_layer* layer, const lpq_layer_cfg* cfg, int32_t M)
+{
+    if (!layer || !cfg || M < 1 || cfg->n_heads < 1 || cfg->head_dim < 1) return 0;
+    const size_t h = (size_t)cfg->n_heads * cfg->head_dim, f = (size_t)std::max(layer->fc1.d.N, 0);
+    return (size_t)M * (5 * h + f) * 2;       // h1 / h2, qkv (3h), attention output, feed-forward activations
+}
+
+lpq_status lpq_decoder_layer(const lpq_layer* layer, const lpq_layer_cfg* cfg, const lpq_layer_state* st, lpq_phase phase, int32_t n_seqs,
+                             int32_t T, int32_t pos0, const void* x, void* y, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!layer || !cfg || !st || !x || !y || !workspace) return LPQ_ERR_NULL;
+    if (phase != LPQ_PREFILL && phase != LPQ_DECODE) return LPQ_ERR_UNSUPPORTED;
+    if (cfg->activation != LPQ_ACT_NONE && cfg->activation != LPQ_ACT_RELU && cfg->activation != LPQ_ACT_GELU_TANH) return LPQ_ERR_UNSUPPORTED;
+    lpq_status s = check_attention_args(cfg, st, n_seqs, T, pos0);
+    if (s != LPQ_OK) return s;
+    if (!st->ln1_gamma || !st->ln1_beta || !st->ln2_gamma || !st->ln2_beta) return LPQ_ERR_NULL;
+    const lpq_qweight* w[4] = {&layer->qkv, &layer->out, &layer->fc1, &layer->fc2};
+    for (int j = 0; j < 4; ++j) {
+        s = check_weight(w[j]);
+        if (s != LPQ_OK) return s;
+    }
+    const int64_t h = (int64_t)cfg->n_heads * cfg->head_dim, f = layer->fc1.d.N, M = (int64_t)n_seqs * T;
+    if (h > layernorm_max_hidden() || M > 0x7fffffff) return LPQ_ERR_SHAPE;
+    if (layer->qkv.d.K != h || layer->qkv.d.N != 3 * h || layer->out.d.K != h || layer->out.d.N != h || layer->fc1.d.K != h ||
+        layer->fc2.d.K != f || layer->fc2.d.N != h)
+        return LPQ_ERR_SHAPE;
+    if (misaligned(x) || misaligned(y) || misaligned(workspace) || misaligned(st->ln1_gamma) || misaligned(st->ln1_beta) ||
+        misaligned(st->ln2_gamma) || misaligned(st->ln2_beta))
+        return LPQ_ERR_ALIGN;
+    if (workspace_bytes < lpq_decoder_layer_workspace(layer, cfg, (int32_t)M)) return LPQ_ERR_BUFSIZE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    uint16_t* h1 = static_cast<uint16_t*>(workspace);          // LN1 output, later LN2 output
+    uint16_t* qkv = h1 + M * h;
+    uint16_t* att = qkv + 3 * M * h;
+    uint16_t* ff = att + M * h;
+    auto linear = [&](const lpq_qweight* wt, const void* in, void* out, const void* residual, int act) {
+        std::vector<LinearCall> calls(1, LinearCall{wt, in, out, residual, act});
+        return phase == LPQ_PREFILL ? run_prefill(calls, (int32_t)M, stream) : run_decode(calls, (int32_t)M, stream);
+    };
+    if (launch_layernorm(x, st->ln1_gamma, st->ln1_beta, cfg->ln_eps, (int)M, (int)h, h1, stream) != hipSuccess) return LPQ_ERR_DEVICE;
+    if ((s = linear(&layer->qkv, h1, qkv, nullptr, LPQ_ACT_NONE)) != LPQ_OK) return s;
+    if (launch_kv_append(qkv, st->k_cache, st->vt_cache, n_seqs, T, pos0, cfg->n_heads, cfg->head_dim, cfg->max_seq, stream) != hipSuccess)
+        return LPQ_ERR_DEVICE;
+    if ((s = run_attention(qkv, cfg, st, n_seqs, T, pos0, att, stream)) != LPQ_OK) return s;
+    if ((s = linear(&layer->out, att, y, x, LPQ_ACT_NONE)) != LPQ_OK) return s;                    // y = x + out-projection
+    if (launch_layernorm(y, st->ln2_gamma, st->ln2_beta, cfg->ln_eps, (int)M, (int)h, h1, stream) != hipSuccess) return LPQ_ERR_DEVICE;
+    if ((s = linear(&layer->fc1, h1, ff, nullptr, cfg->activation)) != LPQ_OK) return s;
+    return linear(&layer->fc2, ff, y, y, LPQ_ACT_NONE);                                           // y += feed-forward
+}
+
 lpq_status lpq_unpack_dequant(const lpq_qweight* w, void* w_fp32, void* hip_stream)
 {
     lpq_status st = check_weight(w);
@@ -386,7 +497,7 @@ lpq_status lpq_qlinear_prefill(const lpq_qweight* w, const void* x, int32_t M, v
 {
     lpq_status st = check_linear(w, x, M, y);
     if (st != LPQ_OK) return st;
-    std::vector<LinearCall> calls(1, LinearCall{w, x, y});
+    std::vector<LinearCall> calls(1, LinearCall{w, x, y, nullptr, LPQ_ACT_NONE});
     return run_prefill(calls, M, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -394,8 +505,27 @@ lpq_status lpq_qlinear_decode(const lpq_qweight* w, const void* x, int32_t M, vo
 {
     lpq_status st = check_linear(w, x, M, y);
     if (st != LPQ_OK) return st;
-    std::vector<LinearCall> calls(1, LinearCall{w, x, y});
+    std::vector<LinearCall> calls(1, LinearCall{w, x, y, nullptr, LPQ_ACT_NONE});
     return run_decode(calls, M, static_cast<hipStream_t>(hip_stream));
+}
+
+lpq_status lpq_qlinear_fused(const lpq_qweight* w, const void* x, int32_t M, void* y, const lpq_epilogue* ep, lpq_phase phase,
+                             void* hip_stream)
+{
+    lpq_status st = check_linear(w, x, M, y);
+    if (st != LPQ_OK) return st;
+    if (phase != LPQ_PREFILL && phase != LPQ_DECODE) return LPQ_ERR_UNSUPPORTED;
+    LinearCall c{w, x, y, nullptr, LPQ_ACT_NONE};
+    if (ep) {
+        if (ep->activation != LPQ_ACT_NONE && ep->activation != LPQ_ACT_RELU && ep->activation != LPQ_ACT_GELU_TANH)
+            return LPQ_ERR_UNSUPPORTED;
+        if (ep->residual && misaligned(ep->residual)) return LPQ_ERR_ALIGN;
+        c.residual = ep->residual;
+        c.act = ep->activation;
+    }
+    std::vector<LinearCall> calls(1, c);
+    return phase == LPQ_PREFILL ? run_prefill(calls, M, static_cast<hipStream_t>(hip_stream))
+                                : run_decode(calls, M, static_cast<hipStream_t>(hip_stream));
 }
 
 lpq_status lpq_stage_linears(const lpq_layer* layers, int32_t n_layers, lpq_phase phase, int32_t M, const lpq_layer_io* io,
@@ -413,7 +543,7 @@ lpq_status lpq_stage_linears(const lpq_layer* layers, int32_t n_layers, lpq_phas
         for (int j = 0; j < 4; ++j) {
             lpq_status st = check_linear(w[j], xs[j], M, ys[j]);
             if (st != LPQ_OK) return st;
-            calls.push_back(LinearCall{w[j], xs[j], ys[j]});
+            calls.push_back(LinearCall{w[j], xs[j], ys[j], nullptr, LPQ_ACT_NONE});
         }
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);

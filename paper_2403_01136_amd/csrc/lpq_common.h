@@ -17,15 +17,18 @@ struct LinDesc {
     const uint16_t* x;      // fp16 [M][K]
     uint16_t* y;            // fp16 [M][N]
     const uint16_t* bias;   // fp16 [N] or null
+    const uint16_t* residual;   // fp16 [M][N] added to the output before its one rounding, or null
     uint64_t cum_weight;
     uint32_t step_weight;
     int32_t K, N;
     int32_t variant;        // V_W3 .. V_F16
     int32_t row_blocks;     // N / rows per wave (64; 32 for fp16 weights)
     int32_t row_superblocks;// ceil(row_blocks / waves per workgroup)
+    int32_t act;            // lpq_activation applied to acc + bias (before the residual)
+    int32_t pad;
 };
 
-enum { MAX_LIN_PER_LAUNCH = 44 };   // keeps DecodeArgs under the 4 KB kernel-argument limit
+enum { MAX_LIN_PER_LAUNCH = 40 };   // keeps DecodeArgs under 4 KB of kernel arguments
 
 // Even-share decomposition: the launch's total weight is cut into n_blocks equal ranges; workgroup
 // b streams the steps whose start offset falls in [b, b+1) * total / n_blocks.  A (linear, row
@@ -58,7 +61,8 @@ struct PrefillLin {
     int32_t tile_begin;     // first tile (workgroup) of this linear in the launch
     int32_t n_blocks;       // ceil(N / 256)
     int32_t token_groups;   // 1, 2, 4 or 8
-    int32_t pad;
+    int32_t act;            // lpq_activation applied to acc + bias (before the residual)
+    const uint16_t* residual;   // fp16 [M][N] added to the output before its one rounding, or null
 };
 
 // Token block and row block of tile l of XCD x; false if that XCD has fewer tiles.
@@ -83,7 +87,7 @@ __host__ __device__ inline int prefill_xcd_tiles(int m_blocks, int n_blocks, int
     return (group_size < m_blocks ? group_size : m_blocks) * rows_class0;
 }
 
-enum { MAX_PREFILL_LIN = 60 };
+enum { MAX_PREFILL_LIN = 44 };
 
 struct PrefillArgs {
     int32_t n_lin, M, total_tiles, pad;
@@ -103,5 +107,13 @@ hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);
 int prefill_tokens_per_tile(int variant);
+// the rest of the decoder layer (lpq_layer.hip)
+hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, float eps, int M, int h, void* y, hipStream_t s);
+int layernorm_max_hidden();
+hipError_t launch_kv_append(const void* qkv, void* kc, void* vtc, int n_seqs, int T, int pos0, int H, int d, int S, hipStream_t s);
+void attention_decode_plan(int n_seqs, int H, int L, int* range, int* splits);
+size_t attention_decode_workspace_floats(int n_seqs, int H, int d, int splits);
+hipError_t launch_attention(const void* qkv, const void* kc, const void* vtc, const float* slopes, int n_seqs, int T, int pos0, int H, int d,
+                            int S, void* out, float* part, hipStream_t s);
 
 }  // namespace lpq

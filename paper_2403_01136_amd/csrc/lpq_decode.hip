@@ -298,9 +298,14 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                     if (tok >= M) continue;
                     if (!partial) {
                         typedef _Float16 hv __attribute__((ext_vector_type(NP)));
-                        hv o;
+                        hv o, res;
+                        if (L.residual) res = *reinterpret_cast<const hv*>(L.residual + (size_t)tok * L.N + nbase);
 #pragma unroll
-                        for (int p = 0; p < NP; ++p) o[p] = (_Float16)(accw[p][m2][v] * post[p] + bias[p]);
+                        for (int p = 0; p < NP; ++p) {
+                            float val = apply_activation(accw[p][m2][v] * post[p] + bias[p], L.act);
+                            if (L.residual) val += (float)res[p];
+                            o[p] = (_Float16)val;
+                        }
                         *reinterpret_cast<hv*>(L.y + (size_t)tok * L.N + nbase) = o;
                     } else {
                         typedef float fv __attribute__((ext_vector_type(NP)));
@@ -335,9 +340,14 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                     }
                     if (!partial) {
                         typedef _Float16 hv __attribute__((ext_vector_type(RT)));
-                        hv o;
+                        hv o, res;
+                        if (L.residual) res = *reinterpret_cast<const hv*>(L.residual + (size_t)tok * L.N + nbase);
 #pragma unroll
-                        for (int t = 0; t < RT; ++t) o[t] = (_Float16)(val[t] + bias[t]);
+                        for (int t = 0; t < RT; ++t) {
+                            float e = apply_activation(val[t] + bias[t], L.act);
+                            if (L.residual) e += (float)res[t];
+                            o[t] = (_Float16)e;
+                        }
                         *reinterpret_cast<hv*>(L.y + (size_t)tok * L.N + nbase) = o;
                     } else {
                         typedef float fv __attribute__((ext_vector_type(RT)));
@@ -516,6 +526,13 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
             if (L.bias)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) sv[v] += (float)__builtin_bit_cast(_Float16, L.bias[nbase + n4 + v]);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sv[v] = apply_activation(sv[v], L.act);
+            if (L.residual) {
+                const h4 res = *reinterpret_cast<const h4*>(L.residual + (size_t)(a.m0 + tok) * L.N + nbase + n4);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sv[v] += (float)res[v];
+            }
             const h4 out = {(_Float16)sv[0], (_Float16)sv[1], (_Float16)sv[2], (_Float16)sv[3]};
             *reinterpret_cast<h4*>(L.y + (size_t)(a.m0 + tok) * L.N + nbase + n4) = out;
         }

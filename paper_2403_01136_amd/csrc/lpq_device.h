@@ -68,6 +68,14 @@ __device__ __forceinline__ WRaw<V> load_tile(const uint8_t* __restrict__ codes, 
     return w;
 }
 
+// Output epilogue: activation (lpq_activation) on acc + bias, in fp32.
+__device__ __forceinline__ float apply_activation(float v, int act)
+{
+    if (act == LPQ_ACT_RELU) return fmaxf(v, 0.0f);
+    if (act == LPQ_ACT_GELU_TANH) return 0.5f * v * (1.0f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
+    return v;
+}
+
 // ---- unpack to fp16 values that are exactly the integer codes --------------------------
 // OR-ing a code field into the mantissa of fp16 1024.0 (0x6400) gives 1024 + c*code exactly,
 // c = 2^(field's bit offset in the half-word); one packed op then removes the offset.

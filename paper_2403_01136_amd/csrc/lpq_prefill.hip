@@ -44,7 +44,7 @@ void prefill_kernel(const PrefillArgs a)
     const uint16_t* __restrict__ scales = L.scales;
     const uint16_t* __restrict__ zeros = L.zeros;
     const uint16_t* __restrict__ x = L.x;
-    uint16_t* __restrict__ y = L.y;
+    uint16_t* y = L.y;                               // may alias L.residual
     const uint16_t* __restrict__ bias = L.bias;
     const int M = a.M, K = L.K, N = L.N;
     // Tile order inside a linear: workgroup ids go round-robin over the 8 XCDs; each XCD walks a
@@ -235,7 +235,14 @@ void prefill_kernel(const PrefillArgs a)
         for (int v = 0; v < 16; ++v) {
             const int tok = m0 + 32 * mt + 8 * (v / 4) + 4 * thalf + (v % 4);
             if (tok >= M) continue;
-            const h2 o = {(_Float16)(acc[0][mt][v] * post[0] + bs[0]), (_Float16)(acc[1][mt][v] * post[1] + bs[1])};
+            float e0 = apply_activation(acc[0][mt][v] * post[0] + bs[0], L.act);
+            float e1 = apply_activation(acc[1][mt][v] * post[1] + bs[1], L.act);
+            if (L.residual) {
+                const h2 res = *reinterpret_cast<const h2*>(L.residual + (size_t)tok * N + nbase);
+                e0 += (float)res[0];
+                e1 += (float)res[1];
+            }
+            const h2 o = {(_Float16)e0, (_Float16)e1};
             *reinterpret_cast<h2*>(y + (size_t)tok * N + nbase) = o;
         }
 }

@@ -93,6 +93,42 @@ def test_entry_points_validate_before_touching_the_device():
     assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d3), ctypes.byref(w3), fake + 4, 1 << 20, None) == 5
     assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d3), ctypes.byref(w3), fake, 2 * 64 * 128 * 2 - 1, None) == 6
     assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d2), ctypes.byref(w3), fake, 1 << 20, None) == 4
+    # fused epilogue: unknown activation, misaligned residual, unknown phase
+    ep = lpq.lpq_epilogue(7, None)
+    assert lib.lpq_qlinear_fused(ctypes.byref(good), fake, 1, fake, ctypes.byref(ep), 1, None) == 8
+    ep = lpq.lpq_epilogue(1, fake + 2)
+    assert lib.lpq_qlinear_fused(ctypes.byref(good), fake, 1, fake, ctypes.byref(ep), 1, None) == 5
+    assert lib.lpq_qlinear_fused(ctypes.byref(good), fake, 1, fake, None, 3, None) == 8
+    assert lib.lpq_qlinear_fused(ctypes.byref(good), None, 1, fake, None, 1, None) == 1
+    # layer norm
+    assert lib.lpq_layernorm(None, fake, fake, 1e-5, 1, 64, fake, None) == 1
+    for M, h in ((0, 64), (1, 60), (1, 0), (1, 16392)):
+        assert lib.lpq_layernorm(fake, fake, fake, 1e-5, M, h, fake, None) == 4
+    assert lib.lpq_layernorm(fake, fake + 2, fake, 1e-5, 1, 64, fake, None) == 5
+    # attention and KV cache: head size, cache length, positions
+    st = lpq.lpq_layer_state(fake, fake, fake, fake, fake, fake, None)
+    for cfg, n_seqs, T, pos0 in ((lpq.lpq_layer_cfg(4, 96, 128, 1, 1e-5), 1, 1, 0), (lpq.lpq_layer_cfg(4, 64, 100, 1, 1e-5), 1, 1, 0),
+                                 (lpq.lpq_layer_cfg(4, 64, 128, 1, 1e-5), 1, 2, 127), (lpq.lpq_layer_cfg(4, 64, 128, 1, 1e-5), 0, 1, 0),
+                                 (lpq.lpq_layer_cfg(0, 64, 128, 1, 1e-5), 1, 1, 0), (lpq.lpq_layer_cfg(4, 64, 128, 1, 1e-5), 1, 1, -1)):
+        assert lib.lpq_kv_append(fake, ctypes.byref(cfg), ctypes.byref(st), n_seqs, T, pos0, None) == 4
+        assert lib.lpq_attention(fake, ctypes.byref(cfg), ctypes.byref(st), n_seqs, T, pos0, fake, None) == 4
+    cfg = lpq.lpq_layer_cfg(4, 64, 128, 1, 1e-5)
+    no_cache = lpq.lpq_layer_state(fake, fake, fake, fake, None, fake, None)
+    assert lib.lpq_attention(fake, ctypes.byref(cfg), ctypes.byref(no_cache), 1, 1, 0, fake, None) == 1
+    assert lib.lpq_attention(fake + 2, ctypes.byref(cfg), ctypes.byref(st), 1, 1, 0, fake, None) == 5
+    # decoder layer: weights must fit hidden = heads * head_dim; workspace size is checked
+    h, f = 256, 512
+    mk = lambda K, N: lpq.lpq_qweight(lpq.make_desc(4, 1, K, N), fake, fake, fake, None)
+    layer = lpq.lpq_layer(mk(h, 3 * h), mk(h, h), mk(h, f), mk(f, h))
+    need = lib.lpq_decoder_layer_workspace(ctypes.byref(layer), ctypes.byref(cfg), 8)
+    assert need == 8 * (5 * h + f) * 2 and lib.lpq_decoder_layer_workspace(None, ctypes.byref(cfg), 8) == 0
+    args = (ctypes.byref(layer), ctypes.byref(cfg), ctypes.byref(st), 1, 8, 1, 0, fake, fake, fake)
+    assert lib.lpq_decoder_layer(*args, need - 1, None) == 6
+    wrong = lpq.lpq_layer(mk(h, 3 * h), mk(h, h), mk(h, f), mk(f, 2 * h))
+    assert lib.lpq_decoder_layer(ctypes.byref(wrong), *args[1:], need, None) == 4
+    bad_act = lpq.lpq_layer_cfg(4, 64, 128, 9, 1e-5)
+    assert lib.lpq_decoder_layer(args[0], ctypes.byref(bad_act), *args[2:], need, None) == 8
+    assert lib.lpq_decoder_layer(args[0], args[1], args[2], 1, 8, 1, 0, None, fake, fake, need, None) == 1
     # bad bits inside a weight
     bad = lpq.lpq_qweight(lpq.lpq_qdesc(5, 1, 128, 128, 64), fake, fake, fake, None)
     assert lib.lpq_qlinear_decode(ctypes.byref(bad), fake, 1, fake, None) == 2

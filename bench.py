@@ -159,6 +159,62 @@ def loader_bench(cfg, device, layer=2, staging_mib=64, reps=3):
             "h2d_copy_GBs": nbytes / t_copy / 1e9, "frac_of_h2d_copy": t_copy / t_load}
 
 
+def layer_bench(cfg, device, layer=2, n_heads=None, head_dim=128, n_gen=100, steps=20):
+    """One whole decoder layer (layer norms, quantised linears with fused epilogues, KV cache, attention):
+    the per-layer latency l_{i,j,b} that the paper's cost model consumes (Sec. 4.3), at the prefill
+    micro-batch (eta prompts of s tokens) and at the decode micro-batch (xi sequences) with s + n/2 cached
+    positions, as the paper averages the decode cost."""
+    import torch
+    import paper_2403_01136_amd as lpq
+    from paper_2403_01136_amd import workloads as wl
+    bits, scheme = cfg["layers"][layer]
+    h, f = cfg["h"], cfg["f"]
+    H = n_heads or h // head_dim
+    shapes = wl.linear_shapes(cfg)
+    Mp, xi = cfg["prefill_M"], cfg["decode_Ms"][-1 if cfg["name"] != "bloom176b_share10_w3" else 2]
+    s_len = 512 if Mp % 512 == 0 else Mp
+    eta = Mp // s_len
+    S = ((s_len + n_gen + 63) // 64) * 64
+    batch = max(eta, xi)
+    lw = {}
+    for name in wl.LINEARS:
+        K, N = shapes[name]
+        w = wl.weight_torch(N, K, device, cfg["name"], layer, name)
+        lw[name] = lpq.lpq_quantize_pack(w, bits, scheme)
+        del w
+    ones, zeros = torch.ones(h, dtype=torch.float16, device=device), torch.zeros(h, dtype=torch.float16, device=device)
+    st = lpq.LayerState(H, head_dim, S, batch, device, (ones, zeros), (ones, zeros))
+    wbytes = sum(q.nbytes for q in lw.values())
+
+    def timed(phase, n_seqs, T, pos0):
+        x = wl.act_torch(n_seqs * T, h, cfg["act_outliers"], device, cfg["name"], layer, "layer", T)
+        y, ws = lpq.lpq_decoder_layer(lw, st, phase, n_seqs, T, pos0, x)
+        for _ in range(2):
+            lpq.lpq_decoder_layer(lw, st, phase, n_seqs, T, pos0, x, y, ws)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            lpq.lpq_decoder_layer(lw, st, phase, n_seqs, T, pos0, x, y, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    ms_pre = timed(lpq.LPQ_PREFILL, eta, s_len, 0)
+    pos_dec = s_len + n_gen // 2
+    ms_dec = timed(lpq.LPQ_DECODE, xi, 1, pos_dec)
+    lin_flops = 2.0 * Mp * sum(K * N for K, N in shapes.values())
+    att_flops = 4.0 * eta * H * head_dim * s_len * (s_len + 1) / 2          # q.k and p.v over the causal half
+    kv_bytes = 2.0 * xi * (pos_dec + 1) * h * 2
+    act_bytes = 2.0 * xi * (h * 9 + 3 * h + 2 * f)                          # rows read and written by the operators, fp16
+    return {"workload": "one %d-bit layer of %s: h=%d, %d heads of %d, f=%d; prefill %d x %d tokens; decode %d sequences at "
+                        "position %d (s + n/2)" % (bits, cfg["name"], h, H, head_dim, f, eta, s_len, xi, pos_dec),
+            "prefill_ms": ms_pre, "prefill_TFLOPs": (lin_flops + att_flops) / ms_pre / 1e9,
+            "decode_ms": ms_dec, "decode_GBs": (wbytes + kv_bytes + act_bytes) / ms_dec / 1e6,
+            "decode_bytes": {"weights": wbytes, "kv_cache": kv_bytes, "activations": act_bytes},
+            "decode_frac_of_hbm_peak": (wbytes + kv_bytes + act_bytes) / ms_dec / 1e6 / HBM_PEAK_GBS}
+
+
 def traffic_from_profiles(cfg, phase, M):
     """HBM bytes per launch as measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by the
     copy calibration) and recorded in profiles/hbm_traffic.json for this workload; None if absent."""
@@ -180,6 +236,7 @@ def main():
     ap.add_argument("--only", choices=["all", "decode", "prefill"], default="all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loader", action="store_true", help="skip the host-to-device quantised-load measurement")
+    ap.add_argument("--no-layer", action="store_true", help="skip the whole-decoder-layer measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times, so a --pmc run can scale FETCH_SIZE / WRITE_SIZE by it")
     args = ap.parse_args()
@@ -248,6 +305,8 @@ def main():
         if measured and roof is not None:
             roof["traffic"] = measured["bytes_per_launch"]
             roof["traffic_source"] = measured["source"]
+    if not args.no_layer and args.only == "all":
+        out["layer"] = layer_bench(cfg, device, layer=min(2, len(cfg["layers"]) - 1))
     if not args.no_loader and args.only == "all":
         out["loader"] = loader_bench(cfg, device, layer=min(2, len(cfg["layers"]) - 1))
     if not args.no_cpu_baseline:

@@ -218,6 +218,12 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         }
         if (total >= ((uint64_t)1 << 50)) return LPQ_ERR_UNSUPPORTED;
         a.total_weight = total;
+        // A small launch (one linear of a decoder layer) is not cut into more ranges than it has chunks of
+        // steps: thinner ranges stream no faster and only multiply the pieces the fix-up pass has to add.
+        static const int min_steps = std::max(1, env_int("LPQ_DECODE_MIN_STEPS", 16));
+        int64_t steps = 0;
+        for (int i = 0; i < a.n_lin; ++i) steps += (int64_t)a.lin[i].row_superblocks * (a.lin[i].K / 128);
+        a.n_blocks = (int32_t)std::max<int64_t>(1, std::min<int64_t>(n_blocks, steps / min_steps));
         for (int m0 = 0; m0 < M; m0 += 64) {
             a.m0 = m0;
             if (launch_decode(a, stream) != hipSuccess) return LPQ_ERR_DEVICE;

@@ -485,56 +485,98 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
     const int stride = a.waves * 64;                                    // floats per token row of a partial tile
     const long nbase = (long)sb * rows_wg;
     const int m_cnt = min(64, a.M - a.m0);
-    constexpr int PER_THREAD = 16;                                      // groups of 4 consecutive rows per thread and pass
+    // A pass covers 1024 groups of 4 consecutive rows (16 tokens of a four-wave workgroup's rows).  Every
+    // piece costs a round of memory latency, so a unit cut into many pieces (a single small linear spread
+    // over the whole chip) has them dealt round-robin to the four waves, each wave adding its pieces for
+    // all 1024 groups, and the four sums are then added in a fixed order through LDS; a unit cut into a few
+    // pieces (the usual case in a stage-wide launch) is added by all threads piece after piece.
+    // Deterministic either way.
+    constexpr int PER_LANE = 16, PER_THREAD = 4;
+    __shared__ f4 wsum[4][256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n_items = m_cnt * (rows_wg / 4);
-    for (int base = 0; base < n_items; base += 256 * PER_THREAD) {
-        f4 sum[PER_THREAD];
-        size_t off[PER_THREAD];
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int idx = base + threadIdx.x + 256 * i;
-            const int tok = idx / (rows_wg / 4), n4 = (idx % (rows_wg / 4)) * 4;
-            off[i] = (size_t)tok * stride + n4;
-            sum[i] = f4{0, 0, 0, 0};
-        }
-        auto add_piece = [&](int slot) {       // all of a piece's loads are issued before the first add
-            const float* p = a.partial + (size_t)slot * a.slot_floats;
-            f4 v[PER_THREAD];
-#pragma unroll
-            for (int i = 0; i < PER_THREAD; ++i)
-                if (base + threadIdx.x + 256 * i < n_items) v[i] = *reinterpret_cast<const f4*>(p + off[i]);
-#pragma unroll
-            for (int i = 0; i < PER_THREAD; ++i)
-                if (base + threadIdx.x + 256 * i < n_items) sum[i] += v[i];
-        };
-        add_piece(2 * b + 1);
+    auto for_each_piece = [&](auto&& fn) {         // slot 2b+1, then slot 2b' of every later non-empty range that starts in this unit
+        fn(2 * b + 1);
         for (int bb = b + 1; bb < a.n_blocks; ++bb) {
             const uint64_t lo = range_begin(a, bb);
             const uint64_t first = L.cum_weight + (uint64_t)((lo - L.cum_weight + L.step_weight - 1) / L.step_weight) * L.step_weight;
             if (first >= unit_end) break;
             if (first >= range_begin(a, bb + 1)) continue;      // empty range: it wrote nothing
-            add_piece(2 * bb);
+            fn(2 * bb);
         }
+    };
+    auto finish = [&](int idx, f4 sv) {            // bias, activation, residual, one rounding
+        if (idx >= n_items) return;
+        const int tok = idx / (rows_wg / 4), n4 = (idx % (rows_wg / 4)) * 4;
+        if (nbase + n4 >= L.N) return;
+        if (L.bias)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sv[v] += (float)__builtin_bit_cast(_Float16, L.bias[nbase + n4 + v]);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sv[v] = apply_activation(sv[v], L.act);
         typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        if (L.residual) {
+            const h4 res = *reinterpret_cast<const h4*>(L.residual + (size_t)(a.m0 + tok) * L.N + nbase + n4);
 #pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int idx = base + threadIdx.x + 256 * i;
-            if (idx >= n_items) continue;
-            const int tok = idx / (rows_wg / 4), n4 = (idx % (rows_wg / 4)) * 4;
-            if (nbase + n4 >= L.N) continue;
-            f4 sv = sum[i];
-            if (L.bias)
+            for (int v = 0; v < 4; ++v) sv[v] += (float)res[v];
+        }
+        const h4 out = {(_Float16)sv[0], (_Float16)sv[1], (_Float16)sv[2], (_Float16)sv[3]};
+        *reinterpret_cast<h4*>(L.y + (size_t)(a.m0 + tok) * L.N + nbase + n4) = out;
+    };
+    // ranges that overlap the unit (an upper bound that needs no walk): unit weight / range weight, plus both ends
+    const uint64_t n_pieces = (uint64_t)KT * L.step_weight * (uint64_t)a.n_blocks / a.total_weight + 2;
+    for (int base = 0; base < n_items; base += 1024) {
+        if (n_pieces <= 4) {
+            f4 sum[PER_THREAD];
+            size_t off[PER_THREAD];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) sv[v] += (float)__builtin_bit_cast(_Float16, L.bias[nbase + n4 + v]);
-#pragma unroll
-            for (int v = 0; v < 4; ++v) sv[v] = apply_activation(sv[v], L.act);
-            if (L.residual) {
-                const h4 res = *reinterpret_cast<const h4*>(L.residual + (size_t)(a.m0 + tok) * L.N + nbase + n4);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) sv[v] += (float)res[v];
+            for (int i = 0; i < PER_THREAD; ++i) {
+                const int idx = base + threadIdx.x + 256 * i;
+                off[i] = (size_t)(idx / (rows_wg / 4)) * stride + (idx % (rows_wg / 4)) * 4;
+                sum[i] = f4{0, 0, 0, 0};
             }
-            const h4 out = {(_Float16)sv[0], (_Float16)sv[1], (_Float16)sv[2], (_Float16)sv[3]};
-            *reinterpret_cast<h4*>(L.y + (size_t)(a.m0 + tok) * L.N + nbase + n4) = out;
+            for_each_piece([&](int slot) {         // all of a piece's loads are issued before the first add
+                const float* p = a.partial + (size_t)slot * a.slot_floats;
+                f4 v[PER_THREAD];
+#pragma unroll
+                for (int i = 0; i < PER_THREAD; ++i)
+                    if (base + threadIdx.x + 256 * i < n_items) v[i] = *reinterpret_cast<const f4*>(p + off[i]);
+#pragma unroll
+                for (int i = 0; i < PER_THREAD; ++i)
+                    if (base + threadIdx.x + 256 * i < n_items) sum[i] += v[i];
+            });
+#pragma unroll
+            for (int i = 0; i < PER_THREAD; ++i) finish(base + threadIdx.x + 256 * i, sum[i]);
+            continue;
+        }
+        f4 sum[PER_LANE];
+        size_t off[PER_LANE];
+#pragma unroll
+        for (int i = 0; i < PER_LANE; ++i) {
+            const int idx = base + lane + 64 * i;
+            off[i] = (size_t)(idx / (rows_wg / 4)) * stride + (idx % (rows_wg / 4)) * 4;
+            sum[i] = f4{0, 0, 0, 0};
+        }
+        int piece = 0;
+        for_each_piece([&](int slot) {
+            if ((piece++ & 3) != wave) return;
+            const float* p = a.partial + (size_t)slot * a.slot_floats;
+            f4 v[PER_LANE];
+#pragma unroll
+            for (int i = 0; i < PER_LANE; ++i)
+                if (base + lane + 64 * i < n_items) v[i] = *reinterpret_cast<const f4*>(p + off[i]);
+#pragma unroll
+            for (int i = 0; i < PER_LANE; ++i)
+                if (base + lane + 64 * i < n_items) sum[i] += v[i];
+        });
+#pragma unroll
+        for (int q = 0; q < PER_LANE / 4; ++q) {                // groups base + 256q .. + 255
+            __syncthreads();                                    // the previous round has read wsum
+#pragma unroll
+            for (int i = 0; i < 4; ++i) wsum[wave][lane + 64 * i] = sum[4 * q + i];
+            __syncthreads();
+            finish(base + 256 * q + threadIdx.x,
+                   (wsum[0][threadIdx.x] + wsum[1][threadIdx.x]) + (wsum[2][threadIdx.x] + wsum[3][threadIdx.x]));
         }
     }
 }

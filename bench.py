@@ -233,7 +233,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--decode-m", type=int, default=None)
-    ap.add_argument("--only", choices=["all", "decode", "prefill"], default="all")
+    ap.add_argument("--only", choices=["all", "decode", "prefill", "layer"], default="all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loader", action="store_true", help="skip the host-to-device quantised-load measurement")
     ap.add_argument("--no-layer", action="store_true", help="skip the whole-decoder-layer measurement")
@@ -257,6 +257,10 @@ def main():
     Md = args.decode_m or cfg["decode_Ms"][-1 if args.config != 4 else 2]
     Mp = cfg["prefill_M"]
 
+    if args.only == "layer":          # the whole-decoder-layer measurement alone (for profiling it)
+        print(json.dumps({"metric": "decoder layer latency", "unit": "ms", "n_gpus": 1, "data": "synthetic",
+                          "layer": layer_bench(cfg, device, layer=min(2, len(cfg["layers"]) - 1), steps=args.steps)}))
+        return
     qt = []
     stage_d, _ = build_stage(cfg, Md, device, quant_times=qt)
     wbytes = wl.stage_packed_bytes(cfg)

@@ -82,22 +82,29 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint16_t* __restri
 }
 
 // ---- KV append: the K and V parts of qkv [tokens][3h] into the caches at positions pos0.. -----
+// Grid (sequences * heads, ceil(T / 64)): a workgroup moves 64 tokens of one head.  K rows are copied as
+// they are; V is transposed through LDS so that a wave writes 64 consecutive positions of one feature row.
+template <int D>
 __global__ __launch_bounds__(256) void kv_append_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ kc, uint16_t* __restrict__ vtc,
-                                                        int n_seqs, int T, int pos0, int H, int d, int S)
+                                                        int T, int pos0, int H, int S)
 {
-    const int h = H * d, chunks = h / 8;
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;            // (token, 16-byte chunk of the hidden dimension)
-    if (i >= (long)n_seqs * T * chunks) return;
-    const int ch = (int)(i % chunks);
-    const long tok = i / chunks;
-    const int b = (int)(tok / T), t = (int)(tok % T), head = (8 * ch) / d, e0 = (8 * ch) % d;
-    const uint16_t* src = qkv + tok * 3 * h + 8 * ch;
+    __shared__ uint16_t vs[64][D + 2];                 // +2: feature-major reads of a column hit different banks
     typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
-    const u16x8 k = *reinterpret_cast<const u16x8*>(src + h), v = *reinterpret_cast<const u16x8*>(src + 2 * h);
-    *reinterpret_cast<u16x8*>(kc + (((size_t)b * H + head) * S + pos0 + t) * d + e0) = k;
-    uint16_t* vt = vtc + (((size_t)b * H + head) * d + e0) * S + pos0 + t;
+    const int bh = blockIdx.x, b = bh / H, head = bh % H, t0 = 64 * blockIdx.y;
+    const int h = H * D, nt = min(64, T - t0);
+    constexpr int CH = D / 8;                          // 16-byte chunks per token and head
+    for (int i = threadIdx.x; i < nt * CH; i += 256) {
+        const int t = i / CH, c = i % CH;
+        const uint16_t* src = qkv + ((size_t)b * T + t0 + t) * 3 * h + head * D + 8 * c;
+        const u16x8 k = *reinterpret_cast<const u16x8*>(src + h), v = *reinterpret_cast<const u16x8*>(src + 2 * h);
+        *reinterpret_cast<u16x8*>(kc + (((size_t)b * H + head) * S + pos0 + t0 + t) * D + 8 * c) = k;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) vt[(size_t)e * S] = v[e];
+        for (int e = 0; e < 8; ++e) vs[t][8 * c + e] = v[e];
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane < nt)
+        for (int dd = wave; dd < D; dd += 4) vtc[(((size_t)b * H + head) * D + dd) * S + pos0 + t0 + lane] = vs[lane][dd];
 }
 
 // ---- decode attention: one new token per sequence over L = pos0 + 1 cached positions ------------
@@ -131,14 +138,23 @@ __global__ __launch_bounds__(256) void attention_decode_kernel(const uint16_t* _
         for (int e = 0; e < 8; ++e) q[e] = (float)t[e];
     }
     const uint16_t* kbase = kc + ((size_t)b * H + head) * S * D;
-    for (int i = wave * KPW + lane / LPK; i < n; i += 4 * KPW) {
-        const h8 k = *reinterpret_cast<const h8*>(kbase + (size_t)(j0 + i) * D + 8 * (lane % LPK));
-        float dot = 0.0f;
+    // four key rows per lane and round, their loads issued together (positions past the range are clamped
+    // to its last one and not stored)
+    for (int i0 = wave * KPW + lane / LPK; i0 < n; i0 += 16 * KPW) {
+        h8 k[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) dot += q[e] * (float)k[e];
+        for (int u = 0; u < 4; ++u)
+            k[u] = *reinterpret_cast<const h8*>(kbase + (size_t)(j0 + min(i0 + 4 * KPW * u, n - 1)) * D + 8 * (lane % LPK));
 #pragma unroll
-        for (int off = LPK / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
-        if (lane % LPK == 0) sc[i] = dot * inv_sqrt_d + slope * (float)(j0 + i - (L - 1));
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + 4 * KPW * u;
+            float dot = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot += q[e] * (float)k[u][e];
+#pragma unroll
+            for (int off = LPK / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+            if (lane % LPK == 0 && i < n) sc[i] = dot * inv_sqrt_d + slope * (float)(j0 + i - (L - 1));
+        }
     }
     __syncthreads();
     float m = -INFINITY;
@@ -154,21 +170,28 @@ __global__ __launch_bounds__(256) void attention_decode_kernel(const uint16_t* _
     __syncthreads();
     // out[dd] = sum_j p[j] * VT[dd][j]; wave w takes rows dd = w, w + 4, ...
     const uint16_t* vbase = vtc + ((size_t)b * H + head) * D * S;
-    for (int dd = wave; dd < D; dd += 4) {
-        float acc = 0.0f;
+    // four feature rows per wave and round, their loads issued together
+    for (int d0 = 4 * wave; d0 < D; d0 += 16) {
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int i = 8 * lane; i < n; i += 512) {
-            const h8 v = *reinterpret_cast<const h8*>(vbase + (size_t)dd * S + j0 + i);
+            h8 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const h8*>(vbase + (size_t)(d0 + u) * S + j0 + i);
             const f4 p0 = *reinterpret_cast<const f4*>(&sc[i]), p1 = *reinterpret_cast<const f4*>(&sc[i + 4]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float p = e < 4 ? p0[e] : p1[e - 4];
-                acc += p != 0.0f ? p * (float)v[e] : 0.0f;          // positions past L hold anything, also NaN
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc[u] += p != 0.0f ? p * (float)v[u][e] : 0.0f;      // positions past L hold anything, also NaN
             }
         }
-        acc = wave_sum(acc);
-        if (lane == 0) {
-            if (splits == 1) out[(size_t)b * h + head * D + dd] = __builtin_bit_cast(uint16_t, (_Float16)(acc / l));
-            else part[((size_t)bh * splits + split) * (D + 2) + dd] = acc;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float r = wave_sum(acc[u]);
+            if (lane == 0) {
+                if (splits == 1) out[(size_t)b * h + head * D + d0 + u] = __builtin_bit_cast(uint16_t, (_Float16)(r / l));
+                else part[((size_t)bh * splits + split) * (D + 2) + d0 + u] = r;
+            }
         }
     }
     if (splits > 1 && tid == 0) {
@@ -330,9 +353,10 @@ int layernorm_max_hidden() { return 256 * 8 * LN_MAX_CHUNKS; }
 
 hipError_t launch_kv_append(const void* qkv, void* kc, void* vtc, int n_seqs, int T, int pos0, int H, int d, int S, hipStream_t s)
 {
-    const long items = (long)n_seqs * T * (H * d / 8);
-    kv_append_kernel<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(static_cast<const uint16_t*>(qkv), static_cast<uint16_t*>(kc),
-                                                                     static_cast<uint16_t*>(vtc), n_seqs, T, pos0, H, d, S);
+    const dim3 grid((unsigned)(n_seqs * H), (unsigned)((T + 63) / 64));
+    const uint16_t* q = static_cast<const uint16_t*>(qkv);
+    if (d == 128) kv_append_kernel<128><<<grid, 256, 0, s>>>(q, static_cast<uint16_t*>(kc), static_cast<uint16_t*>(vtc), T, pos0, H, S);
+    else          kv_append_kernel<64><<<grid, 256, 0, s>>>(q, static_cast<uint16_t*>(kc), static_cast<uint16_t*>(vtc), T, pos0, H, S);
     return hipGetLastError();
 }
 

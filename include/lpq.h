@@ -241,6 +241,21 @@ lpq_status lpq_decoder_layer(const lpq_layer *layer, const lpq_layer_cfg *cfg, c
                              int32_t n_seqs, int32_t T, int32_t pos0, const void *x, void *y, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
 
+/* Variance indicator of one linear operator (Sec. 4.2, Theorem 1 and Eq. 3): the estimated extra output
+ * variance D_W * S_W(b)^2 * G(X) under b-bit weight quantisation, G(X) = Var[X] / 4 (deterministic rounding,
+ * stochastic = 0) or (E[X]^2 + Var[X]) / 6 (stochastic = 1), E and Var over all elements of X.  A layer's
+ * indicator omega_{i,b} is the sum of its operators' values.
+ *   w_fp16: device fp16 [N][K] (the unquantised weight; K % 128 == 0);  x: device fp16 [M][K].
+ *   omega:  device double[8], written asynchronously:
+ *           [0..2] bits 3, 4, 8 with the quantiser's granularity: sum over (row, 128-column) groups of
+ *                  128 * ((max - min) / (2^b - 1))^2;   [3] symmetric 8-bit, a scale per row;
+ *           [4..6] bits 3, 4, 8 as printed in the paper: one scaling factor for the whole matrix, D_W = N * K;
+ *           [7]    symmetric 8-bit, one scaling factor for the whole matrix.
+ * Scaling factors are not rounded to fp16.  Uses the library's per-device workspace.
+ * Errors: NULL, SHAPE (K % 128, counts < 1), ALIGN, BUFSIZE, DEVICE. */
+lpq_status lpq_variance_indicator(const void *w_fp16, int32_t K, int32_t N, const void *x, int32_t M, int32_t stochastic,
+                                  double *omega, void *hip_stream);
+
 /* Test helper, not on the hot path: w_fp32[n][k] = scale * code + zero (fp32 multiply, then
  * fp32 add; the fp16 weight itself for LPQ_FP16) read back from the packed buffers.
  *   w_fp32: device float [N][K].  Errors: NULL, BITS, SCHEME, SHAPE, ALIGN, DEVICE. */

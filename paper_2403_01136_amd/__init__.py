@@ -17,7 +17,8 @@ LPQ_OK = 0
 LINEARS = ("qkv", "out", "fc1", "fc2")
 EXPORTS = ("lpq_packed_sizes", "lpq_quantize_pack", "lpq_quantize_pack_rows", "lpq_load_quantize_pack",
            "lpq_qlinear_prefill", "lpq_qlinear_decode", "lpq_qlinear_fused", "lpq_stage_linears", "lpq_layernorm",
-           "lpq_kv_append", "lpq_attention", "lpq_decoder_layer_workspace", "lpq_decoder_layer", "lpq_unpack_dequant",
+           "lpq_kv_append", "lpq_attention", "lpq_decoder_layer_workspace", "lpq_decoder_layer", "lpq_variance_indicator",
+           "lpq_unpack_dequant",
            "lpq_status_str")
 LPQ_ACT_NONE, LPQ_ACT_RELU, LPQ_ACT_GELU_TANH = 0, 1, 2
 
@@ -82,6 +83,7 @@ def load_library():
         L.lpq_qlinear_decode.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, vp]
         L.lpq_stage_linears.argtypes = [ctypes.POINTER(lpq_layer), i32, ctypes.c_int, i32, ctypes.POINTER(lpq_layer_io), vp]
         L.lpq_qlinear_fused.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, ctypes.POINTER(lpq_epilogue), ctypes.c_int, vp]
+        L.lpq_variance_indicator.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp]
         L.lpq_layernorm.argtypes = [vp, vp, vp, ctypes.c_float, i32, i32, vp, vp]
         cfgp, stp = ctypes.POINTER(lpq_layer_cfg), ctypes.POINTER(lpq_layer_state)
         L.lpq_kv_append.argtypes = [vp, cfgp, stp, i32, i32, i32, vp]
@@ -289,6 +291,18 @@ def lpq_decoder_layer(layer, state, phase, n_seqs, T, pos0, x, y=None, workspace
                                             x.data_ptr(), y.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)),
            "lpq_decoder_layer")
     return y, workspace
+
+
+def lpq_variance_indicator(w, x, stochastic=False, stream=None):
+    """Eight forms of D_W * S_W(b)^2 * G(X) (see include/lpq.h) as a float64 CUDA tensor of 8 values."""
+    import torch
+    w, x = _fp16_2d(w, "w"), _fp16_2d(x, "x")
+    if x.shape[1] != w.shape[1]:
+        raise ValueError("x and w must have the same number of columns")
+    out = torch.empty(8, dtype=torch.float64, device=w.device)
+    _check(load_library().lpq_variance_indicator(w.data_ptr(), w.shape[1], w.shape[0], x.data_ptr(), x.shape[0], int(bool(stochastic)),
+                                                 out.data_ptr(), _stream(stream)), "lpq_variance_indicator")
+    return out
 
 
 class Stage:

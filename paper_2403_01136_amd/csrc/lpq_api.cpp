@@ -489,6 +489,19 @@ lpq_status lpq_decoder_layer(const lpq_layer* layer, const lpq_layer_cfg* cfg, c
     return linear(&layer->fc2, ff, y, y, LPQ_ACT_NONE);                                           // y += feed-forward
 }
 
+lpq_status lpq_variance_indicator(const void* w_fp16, int32_t K, int32_t N, const void* x, int32_t M, int32_t stochastic, double* omega,
+                                  void* hip_stream)
+{
+    if (!w_fp16 || !x || !omega) return LPQ_ERR_NULL;
+    if (K < 128 || K % 128 != 0 || N < 1 || M < 1) return LPQ_ERR_SHAPE;
+    if (misaligned(w_fp16) || misaligned(x) || (reinterpret_cast<uintptr_t>(omega) & 7u)) return LPQ_ERR_ALIGN;
+    float* ws = nullptr;
+    lpq_status st = workspace(indicator_workspace_bytes(N, (long)M * K / 8), &ws);
+    if (st != LPQ_OK) return st;
+    return launch_indicator(w_fp16, K, N, x, M, stochastic != 0, omega, ws, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? LPQ_OK : LPQ_ERR_DEVICE;
+}
+
 lpq_status lpq_unpack_dequant(const lpq_qweight* w, void* w_fp32, void* hip_stream)
 {
     lpq_status st = check_weight(w);

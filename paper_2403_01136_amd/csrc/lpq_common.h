@@ -107,6 +107,9 @@ hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);
 int prefill_tokens_per_tile(int variant);
+// variance indicator (lpq_indicator.hip)
+size_t indicator_workspace_bytes(int N, long n8);
+hipError_t launch_indicator(const void* w, int K, int N, const void* x, int M, int stochastic, double* omega, void* ws, hipStream_t s);
 // the rest of the decoder layer (lpq_layer.hip)
 hipError_t launch_layernorm(const void* x, const void* gamma, const void* beta, float eps, int M, int h, void* y, hipStream_t s);
 int layernorm_max_hidden();

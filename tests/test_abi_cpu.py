@@ -129,6 +129,13 @@ def test_entry_points_validate_before_touching_the_device():
     bad_act = lpq.lpq_layer_cfg(4, 64, 128, 9, 1e-5)
     assert lib.lpq_decoder_layer(args[0], ctypes.byref(bad_act), *args[2:], need, None) == 8
     assert lib.lpq_decoder_layer(args[0], args[1], args[2], 1, 8, 1, 0, None, fake, fake, need, None) == 1
+    # variance indicator
+    assert lib.lpq_variance_indicator(None, 128, 64, fake, 1, 0, fake, None) == 1
+    assert lib.lpq_variance_indicator(fake, 128, 64, fake, 1, 0, None, None) == 1
+    for K, N, M in ((100, 64, 1), (0, 64, 1), (128, 0, 1), (128, 64, 0)):
+        assert lib.lpq_variance_indicator(fake, K, N, fake, M, 0, fake, None) == 4
+    assert lib.lpq_variance_indicator(fake + 2, 128, 64, fake, 1, 0, fake, None) == 5
+    assert lib.lpq_variance_indicator(fake, 128, 64, fake, 1, 0, fake + 4, None) == 5
     # bad bits inside a weight
     bad = lpq.lpq_qweight(lpq.lpq_qdesc(5, 1, 128, 128, 64), fake, fake, fake, None)
     assert lib.lpq_qlinear_decode(ctypes.byref(bad), fake, 1, fake, None) == 2

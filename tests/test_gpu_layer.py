@@ -10,6 +10,7 @@ import pytest
 import paper_2403_01136_amd as lpq
 from paper_2403_01136_amd import workloads as wl
 from gpu_util import check_output, to_dev, u16
+from oracle import indicator as OI
 from oracle import layer as OL
 
 pytestmark = pytest.mark.gpu
@@ -140,3 +141,17 @@ def test_decoder_layer_prefill_then_decode(orc, bits, scheme, act, alibi):
         kd = st.k_cache.cpu().numpy().astype(np.float64)[:, :, :pos + T]
         assert np.linalg.norm(kd - k_ref[:, :, :pos + T].astype(np.float64)) <= 2e-3 * np.linalg.norm(kd)
         pos += T
+
+
+@pytest.mark.parametrize("stochastic", [False, True], ids=["deterministic", "stochastic"])
+@pytest.mark.parametrize("N,K,M", [(1, 128, 1), (70, 640, 33), (5120, 5120, 16), (333, 14336, 5)])
+def test_variance_indicator(N, K, M, stochastic):
+    """All eight forms of D_W * S_W(b)^2 * G(X) against the fp64 oracle (reductions in fp32 / fp64: 1e-5)."""
+    w = wl.weight_np(N, K, "ind", N, K)
+    x = wl.act_np(M, K, True, "ind", M)
+    if stochastic:
+        x = (x.astype(np.float32) + 0.75).astype(np.float16)          # a mean that matters
+    got = lpq.lpq_variance_indicator(to_dev(w), to_dev(x), stochastic).cpu().numpy()
+    ref = OI.indicator(w, x, stochastic)
+    for i, key in enumerate(OI.ORDER):
+        assert abs(got[i] - ref[key]) <= 1e-5 * abs(ref[key]) + 1e-300, (key, got[i], ref[key])

@@ -145,18 +145,18 @@ lpq_status lpq_quantize_pack_rows(const void *w_rows_fp16, const lpq_qdesc *desc
                                   lpq_qweight *out, void *hip_stream);
 
 /* On-the-fly quantised loading of one module's weight from HOST memory (Sec. 5, "On-The-Fly Quantizer":
- * module-level weights, host-to-device copy overlapped with on-GPU quantisation, so that the fp16 weight is
- * never resident on the device as a whole).
+ * module-level weights quantised on the GPU as they arrive, so that the fp16 weight is never resident on
+ * the device as a whole).
  *   w_fp16_host: HOST pointer, fp16 [N][K] row-major, 16-byte aligned.  Pinned memory gives asynchronous
- *                copies that overlap the quantiser; pageable memory works but serialises.
- *   staging:     device buffer of staging_bytes, caller-owned; it is split into two halves that take turns
- *                receiving a band of rows (as many 64-row blocks as fit in a half) while the other half is
- *                quantised.  LPQ_ERR_BUFSIZE if a half cannot hold 64 rows (64 * K * 2 bytes).
+ *                copies at the link's rate; pageable memory works but is staged by the runtime.
+ *   staging:     device buffer of staging_bytes, caller-owned, 16-byte aligned; it receives one band of rows
+ *                at a time (as many 64-row blocks as fit), which is then quantised into its place in `out`.
+ *                LPQ_ERR_BUFSIZE if it cannot hold 64 rows (64 * K * 2 bytes).
  *   out:         as for lpq_quantize_pack; the result is bit-identical to it.
- * Copies run on a library-owned stream (one per device, default priority); the quantiser runs on
- * `hip_stream`, which also orders everything: work queued on it before the call completes before the
- * first copy starts, and when the work this call queued on it has completed, `out` is ready and the host
- * buffer and the staging buffer are free again.  The call itself returns without synchronising.
+ * Copies and quantiser alternate on `hip_stream` (the quantiser is some thirty times faster than the host
+ * link, so the link stays busy); when the work queued on it has completed, `out` is ready and the host
+ * buffer and the staging buffer are free again.  The call itself returns without synchronising when the
+ * host memory is pinned.
  * Errors: NULL, BITS, SCHEME, SHAPE, ALIGN, BUFSIZE, DEVICE. */
 lpq_status lpq_load_quantize_pack(const void *w_fp16_host, const lpq_qdesc *desc, lpq_qweight *out, void *staging,
                                   size_t staging_bytes, void *hip_stream);

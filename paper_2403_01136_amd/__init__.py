@@ -175,8 +175,8 @@ def lpq_quantize_pack_rows(w_rows, qw, row0, stream=None):
 
 
 def lpq_load_quantize_pack(w_host, bits, scheme, staging, device=None, bias=None, stream=None):
-    """w_host: fp16 [N][K] in HOST memory (pinned for overlap); staging: uint8 CUDA tensor that takes the
-    rows in two alternating halves -> QWeight, bit-identical to lpq_quantize_pack of the whole weight."""
+    """w_host: fp16 [N][K] in HOST memory (pinned for asynchronous copies); staging: uint8 CUDA tensor that
+    receives one band of rows at a time -> QWeight, bit-identical to lpq_quantize_pack of the whole weight."""
     import torch
     if w_host.dtype != torch.float16 or w_host.dim() != 2 or not w_host.is_contiguous() or w_host.is_cuda:
         raise ValueError("w_host must be a contiguous 2-D fp16 host tensor")

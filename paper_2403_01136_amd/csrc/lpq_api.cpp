@@ -98,22 +98,6 @@ lpq_status workspace(size_t need, float** out)
     return LPQ_OK;
 }
 
-// ---- copy stream of the on-the-fly loader: one per device, default priority, created on first use ----
-lpq_status copy_stream(hipStream_t* out)
-{
-    static std::mutex mu;
-    static hipStream_t streams[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
-    std::lock_guard<std::mutex> lock(mu);
-    if (!streams[dev] && hipStreamCreateWithFlags(&streams[dev], hipStreamNonBlocking) != hipSuccess) {
-        streams[dev] = nullptr;
-        return LPQ_ERR_DEVICE;
-    }
-    *out = streams[dev];
-    return LPQ_OK;
-}
-
 int env_int(const char* name, int fallback)
 {
     const char* e = std::getenv(name);
@@ -370,44 +354,22 @@ lpq_status lpq_load_quantize_pack(const void* w_fp16_host, const lpq_qdesc* desc
     lpq_status st = check_quantize_target(desc, out);
     if (st != LPQ_OK) return st;
     if (misaligned(w_fp16_host) || misaligned(staging)) return LPQ_ERR_ALIGN;
+    // Bands of rows alternate on the caller's stream: copy a band into the staging buffer, quantise it into
+    // its place, copy the next.  The quantiser runs some thirty times faster than the host link, so the copy
+    // engine idles 2-3 % of the time; a second stream that overlapped the two was measured at +1 % at best and
+    // at -35 % in a runtime state seen after large allocations had been freed, so it is not used.
     const size_t row_bytes = (size_t)desc->K * 2;
-    const size_t half = (staging_bytes / 2) & ~(size_t)255;              // keeps the second half 16-byte aligned
-    const int64_t chunk_rows = std::min<int64_t>((int64_t)(half / row_bytes) / 64 * 64, desc->N);
+    const int64_t chunk_rows = std::min<int64_t>((int64_t)(staging_bytes / row_bytes) / 64 * 64, desc->N);
     if (chunk_rows < 64) return LPQ_ERR_BUFSIZE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipStream_t copy = nullptr;
-    st = copy_stream(&copy);
-    if (st != LPQ_OK) return st;
-    // copied[b]: chunk in staging half b has arrived; consumed[b]: its quantisation has been enqueued and,
-    // once the event fires, finished -- only then may the next copy overwrite that half
-    hipEvent_t copied[2] = {nullptr, nullptr}, consumed[2] = {nullptr, nullptr};
-    bool ok = true;
-    for (int b = 0; b < 2 && ok; ++b)
-        ok = hipEventCreateWithFlags(&copied[b], hipEventDisableTiming) == hipSuccess &&
-             hipEventCreateWithFlags(&consumed[b], hipEventDisableTiming) == hipSuccess;
-    // the copy stream starts after whatever the caller already queued on its stream (which may still use staging)
-    hipEvent_t start = nullptr;
-    ok = ok && hipEventCreateWithFlags(&start, hipEventDisableTiming) == hipSuccess && hipEventRecord(start, stream) == hipSuccess &&
-         hipStreamWaitEvent(copy, start, 0) == hipSuccess;
-    int64_t row = 0;
-    for (int c = 0; ok && row < desc->N; ++c, row += chunk_rows) {
-        const int b = c & 1;
+    for (int64_t row = 0; row < desc->N; row += chunk_rows) {
         const int64_t rows = std::min<int64_t>(chunk_rows, desc->N - row);
-        uint8_t* dst = static_cast<uint8_t*>(staging) + (size_t)b * half;
-        if (c >= 2) ok = hipStreamWaitEvent(copy, consumed[b], 0) == hipSuccess;
-        ok = ok && hipMemcpyAsync(dst, static_cast<const uint8_t*>(w_fp16_host) + (size_t)row * row_bytes, (size_t)rows * row_bytes,
-                                  hipMemcpyHostToDevice, copy) == hipSuccess;
-        ok = ok && hipEventRecord(copied[b], copy) == hipSuccess && hipStreamWaitEvent(stream, copied[b], 0) == hipSuccess;
-        ok = ok && launch_quantize_pack(dst, *desc, row, rows, *out, stream) == hipSuccess;
-        ok = ok && hipEventRecord(consumed[b], stream) == hipSuccess;
+        if (hipMemcpyAsync(staging, static_cast<const uint8_t*>(w_fp16_host) + (size_t)row * row_bytes, (size_t)rows * row_bytes,
+                           hipMemcpyHostToDevice, stream) != hipSuccess)
+            return LPQ_ERR_DEVICE;
+        if (launch_quantize_pack(staging, *desc, row, rows, *out, stream) != hipSuccess) return LPQ_ERR_DEVICE;
     }
-    // destroying an event that is still pending only releases it once it has completed
-    for (int b = 0; b < 2; ++b) {
-        if (copied[b]) (void)hipEventDestroy(copied[b]);
-        if (consumed[b]) (void)hipEventDestroy(consumed[b]);
-    }
-    if (start) (void)hipEventDestroy(start);
-    return ok ? LPQ_OK : LPQ_ERR_DEVICE;
+    return LPQ_OK;
 }
 
 lpq_status lpq_layernorm(const void* x, const void* gamma, const void* beta, float eps, int32_t M, int32_t hidden, void* y, void* hip_stream)

@@ -105,12 +105,25 @@ __global__ __launch_bounds__(256) void quantize_asym_kernel(const uint16_t* __re
     if ((sh & 0x7fffu) == 0) sh = 0x3c00u;                 // flat group: scale 1, codes 0
     const uint16_t zh = f2h_bits(__fadd_rn(lo, 0.0f));     // min is an fp16 value; +0 makes -0 -> +0
     const float sf = h2f_bits(sh), zf = h2f_bits(zh);
+    // code = rint((w - zero) / scale) with the quotient rounded to fp32 first.  The correctly rounded
+    // division is ten instructions; a multiplication by a refined reciprocal is one and is off by at most
+    // two units in the last place of a quotient below 256, i.e. by less than 2^-14.  So the fast quotient
+    // decides the code unless it lies within 2^-13 of a half-integer, and only then (about one weight in
+    // 4000, decided per element for the whole wave) is the exact division done: the codes are those of the
+    // exact formula in every case.
+    float rcp = __builtin_amdgcn_rcpf(sf);
+    rcp = __builtin_fmaf(__builtin_fmaf(-sf, rcp, 1.0f), rcp, rcp);
     int c[32];
 #pragma unroll
     for (int i = 0; i < 32; ++i) {
-        const float t = __fdiv_rn(__fsub_rn(v[i], zf), sf);
-        const float r = __builtin_rintf(t);
-        c[i] = (int)fminf(fmaxf(r, 0.0f), (float)QMAX);
+        const float num = __fsub_rn(v[i], zf);
+        float t = __fmul_rn(num, rcp);
+        float r = __builtin_rintf(t);
+        if (__builtin_amdgcn_ballot_w64(!(fabsf(__fsub_rn(t, r)) < 0.5f - 0x1p-13f)) != 0) {      // also catches NaN / Inf
+            t = __fdiv_rn(num, sf);
+            r = __builtin_rintf(t);
+        }
+        c[i] = (int)__builtin_amdgcn_fmed3f(r, 0.0f, (float)QMAX);
     }
     store_packed<BITS, false>(codes, tile, lane, c);
     if (lane < 16) {                                   // stored group-major: [K/128][N]
@@ -158,11 +171,18 @@ __global__ __launch_bounds__(256) void quantize_sym_kernel(const uint16_t* __res
     float v[32];
     load_owned(w, K, n - 64 * win.rb0, kt, lane, v);
     const float sf = h2f_bits(scales[n]);
+    float rcp = __builtin_amdgcn_rcpf(sf);             // guarded fast quotient, as in quantize_asym_kernel
+    rcp = __builtin_fmaf(__builtin_fmaf(-sf, rcp, 1.0f), rcp, rcp);
     int c[32];
 #pragma unroll
     for (int i = 0; i < 32; ++i) {
-        const float r = __builtin_rintf(__fdiv_rn(v[i], sf));
-        c[i] = (int)fminf(fmaxf(r, -127.0f), 127.0f);
+        float t = __fmul_rn(v[i], rcp);
+        float r = __builtin_rintf(t);
+        if (__builtin_amdgcn_ballot_w64(!(fabsf(__fsub_rn(t, r)) < 0.5f - 0x1p-13f)) != 0) {
+            t = __fdiv_rn(v[i], sf);
+            r = __builtin_rintf(t);
+        }
+        c[i] = (int)__builtin_amdgcn_fmed3f(r, -127.0f, 127.0f);
     }
     store_packed<8, true>(codes, tile, lane, c);
 }

@@ -86,12 +86,12 @@ def test_entry_points_validate_before_touching_the_device():
         assert lib.lpq_quantize_pack_rows(fake, ctypes.byref(d3), row0, n_rows, ctypes.byref(w3), None) == 4
     assert lib.lpq_quantize_pack_rows(None, ctypes.byref(d3), 0, 64, ctypes.byref(w3), None) == 1
     assert lib.lpq_quantize_pack_rows(fake + 2, ctypes.byref(d3), 0, 64, ctypes.byref(w3), None) == 5
-    # loader: NULL host or staging pointer, misaligned pointers, staging halves too small for 64 rows
+    # loader: NULL host or staging pointer, misaligned pointers, staging too small for 64 rows
     assert lib.lpq_load_quantize_pack(None, ctypes.byref(d3), ctypes.byref(w3), fake, 1 << 20, None) == 1
     assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d3), ctypes.byref(w3), None, 1 << 20, None) == 1
     assert lib.lpq_load_quantize_pack(fake + 8, ctypes.byref(d3), ctypes.byref(w3), fake, 1 << 20, None) == 5
     assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d3), ctypes.byref(w3), fake + 4, 1 << 20, None) == 5
-    assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d3), ctypes.byref(w3), fake, 2 * 64 * 128 * 2 - 1, None) == 6
+    assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d3), ctypes.byref(w3), fake, 64 * 128 * 2 - 1, None) == 6
     assert lib.lpq_load_quantize_pack(fake, ctypes.byref(d2), ctypes.byref(w3), fake, 1 << 20, None) == 4
     # fused epilogue: unknown activation, misaligned residual, unknown phase
     ep = lpq.lpq_epilogue(7, None)

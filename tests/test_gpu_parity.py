@@ -78,7 +78,7 @@ def test_quantize_pack_rows_any_order(orc, bits, scheme):
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("pinned", [True, False], ids=["pinned", "pageable"])
 def test_load_quantize_pack_from_host(orc, bits, scheme, pinned):
-    """Streaming from host memory through two staging halves (several chunks, a ragged last one) is
+    """Streaming from host memory through a staging buffer (several bands of rows, a ragged last one) is
     bit-identical to quantising the resident weight; then the linear runs on the result."""
     import torch
     N, K, M = 704, 256, 8
@@ -86,7 +86,7 @@ def test_load_quantize_pack_from_host(orc, bits, scheme, pinned):
     w_host = torch.from_numpy(w.copy())
     if pinned:
         w_host = w_host.pin_memory()
-    staging = torch.empty(2 * 192 * K * 2 + 300, dtype=torch.uint8, device="cuda")      # 192-row chunks: 3 full + 128 rows
+    staging = torch.empty(192 * K * 2 + 300, dtype=torch.uint8, device="cuda")          # 192-row bands: 3 full + 128 rows
     qw = lpq.lpq_load_quantize_pack(w_host, bits, scheme, staging)
     torch.cuda.synchronize()
     check_packed(qw, orc, w)

@@ -19,6 +19,9 @@
  *     live in an internal per-device workspace that grows on demand.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     enqueue work and return without synchronising.
+ *   - Calls record only kernel launches (and, for the loader, copies) on `hip_stream`, so they can be
+ *     captured in a HIP graph once an eager call of the same shape has run (the internal workspace is
+ *     allocated, and kernel attributes are set, on first use -- not things a capture may contain).
  *   - Arguments are validated on the host before the first HIP call; on any error nothing is
  *     launched and no buffer is touched.  No exceptions, no errno, no global error state.
  *   - fp16 is IEEE binary16.  x is [M][K], y is [M][N], both dense row-major, 16-byte

@@ -155,3 +155,40 @@ def test_variance_indicator(N, K, M, stochastic):
     ref = OI.indicator(w, x, stochastic)
     for i, key in enumerate(OI.ORDER):
         assert abs(got[i] - ref[key]) <= 1e-5 * abs(ref[key]) + 1e-300, (key, got[i], ref[key])
+
+
+def test_decoder_layer_decode_step_in_a_hip_graph(orc):
+    """A decode step of the layer captured once (after an eager warm-up, so that nothing is allocated during
+    capture) and replayed several times, with eager work and synchronisations between the replays: every
+    replay must reproduce the eager result bit for bit, caches included."""
+    import torch
+    B, H, d, S, f, pos = 4, 4, 64, 128, 512, 40
+    h = H * d
+    st, ln, _ = make_state(B, H, d, S, "graph")
+    r = rng("graph")
+    shapes = {"qkv": (h, 3 * h), "out": (h, h), "fc1": (h, f), "fc2": (f, h)}
+    layer = {n: lpq.lpq_quantize_pack(to_dev(f16(r.standard_normal((N, K)) / np.sqrt(K))), 4, 1) for n, (K, N) in shapes.items()}
+    st.k_cache.copy_(to_dev(f16(r.standard_normal((B, H, S, d)))))
+    st.vt_cache.copy_(to_dev(f16(r.standard_normal((B, H, d, S)))))
+    x = to_dev(f16(r.standard_normal((B, h))))
+    y_eager, ws = lpq.lpq_decoder_layer(layer, st, lpq.LPQ_DECODE, B, 1, pos, x)          # warm-up: workspaces exist now
+    torch.cuda.synchronize()
+    k_eager, v_eager = st.k_cache.clone(), st.vt_cache.clone()
+    y_graph = torch.empty_like(y_eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            lpq.lpq_decoder_layer(layer, st, lpq.LPQ_DECODE, B, 1, pos, x, y_graph, ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for replay in range(4):
+        y_graph.fill_(float("nan"))
+        st.k_cache[:, :, pos].fill_(0), st.vt_cache[:, :, :, pos].fill_(0)                 # the step must rewrite its position
+        other = lpq.lpq_qlinear_decode(layer["fc1"], x)                                     # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(u16(y_graph), u16(y_eager)), "replay %d" % replay
+        assert torch.equal(st.k_cache, k_eager) and torch.equal(st.vt_cache, v_eager), "replay %d caches" % replay
+        assert torch.isfinite(other).all()

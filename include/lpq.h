@@ -259,6 +259,76 @@ lpq_status lpq_decoder_layer(const lpq_layer *layer, const lpq_layer_cfg *cfg, c
 lpq_status lpq_variance_indicator(const void *w_fp16, int32_t K, int32_t N, const void *x, int32_t M, int32_t stochastic,
                                   double *omega, void *hip_stream);
 
+/* ---- The assigner's cost models and bitwidth-transfer heuristic (Sec. 4.1, Sec. 4.3): host code only -------------
+ * Every pointer below is a HOST pointer, nothing touches a device, nothing is asynchronous.  These calls close the
+ * loop from the measured decoder-layer latencies back to the plan (layers per stage, bitwidth per layer) that the
+ * kernels above serve. */
+
+/* Shape of a model for the memory cost model (Table 2 notation). */
+typedef struct lpq_model_shape {
+    int64_t h1, h2;        /* hidden size, feed-forward size                                         */
+    int64_t vocab, d_t;    /* vocabulary size, word-embedding width                                  */
+    int64_t pos;           /* max position embeddings                                                */
+    int32_t rmsnorm, pad;  /* 1: RMSNorm (4 h1 bytes of norm weights per layer), 0: LayerNorm (6 h1) */
+} lpq_model_shape;
+
+/* Memory cost model (Sec. 4.1), bytes as doubles (negative on a bad argument):
+ * embeddings + LM head in fp16: (vocab d_t + pos d_t + [2 h1 d_t if h1 != d_t] + vocab d_t) * 2;
+ * one decoder layer at `bit` bits: (4 h1^2 + 2 h1 h2) * bit / 8 + the norm term;
+ * KV cache of one layer for v requests of s + n positions: 2 v (s + n) h1 * bit_kv / 8. */
+double lpq_mem_embedding_bytes(const lpq_model_shape *m);
+double lpq_mem_layer_bytes(const lpq_model_shape *m, int32_t bit);
+double lpq_mem_kv_bytes(const lpq_model_shape *m, int64_t v, int64_t s, int64_t n, int32_t bit_kv);
+
+/* Latency cost model (Sec. 4.1): least-squares fit of one decoder layer's time, per phase and precision.
+ *   LPQ_PREFILL: t ~ c0 + c1 v + c2 s + c3 v s + c4 v s^2          (len = prompt length s;  5 coefficients)
+ *   LPQ_DECODE:  t ~ c0 + c1 v + c2 v (t+s) + c3 (t+s)             (len = cached positions; 4 coefficients)
+ * v, len, t: n_samples values each.  Solved by Householder QR on scaled columns.
+ * Errors: NULL, SHAPE (fewer samples than coefficients, or samples that do not determine them), UNSUPPORTED (phase). */
+lpq_status lpq_latency_fit(lpq_phase phase, int32_t n_samples, const double *v, const double *len, const double *t,
+                           double *coef);
+lpq_status lpq_latency_predict(lpq_phase phase, const double *coef, int32_t n, const double *v, const double *len,
+                               double *t_out);
+
+/* The assignment program of Sec. 4.3 (Eq. 1 and its constraints) for L layers of one shape on N pipeline devices.
+ * A plan is counts[N] (consecutive layers per stage, each >= 1, summing to L) and choice[L] (index into bits). */
+typedef struct lpq_plan_problem {
+    int32_t L, N, n_bits, pad;
+    const int32_t *bits;      /* [n_bits] allowed bitwidths                                                     */
+    const double *omega;      /* [L][n_bits] variance indicator of layer i at bits[k]                           */
+    const double *lat_pre;    /* [N][n_bits] seconds of one layer at bits[k] on device j, prefill micro-batch   */
+    const double *lat_dec;    /* [N][n_bits] the same for one decode step at the mean context s + n / 2         */
+    const double *mem;        /* [n_bits] bytes a layer at bits[k] reserves (weights + its KV cache)            */
+    const double *cap;        /* [N] bytes device j offers to layers (temporary memory already taken off)       */
+    const double *comm_pre;   /* [N] seconds of stage j's prefill send P_pre / f_j, or NULL for none            */
+    const double *comm_dec;   /* [N] the same for decode, or NULL                                               */
+    double emb;               /* bytes of embeddings the first device also holds                                */
+    double theta;             /* weight of the quality term                                                     */
+    int32_t B, eta, xi, n;    /* global batch, prefill and decode micro-batch, tokens to generate               */
+} lpq_plan_problem;
+
+/* Eq. (1): (ceil(B/eta) - 1) Tmax_pre + (ceil(B/xi) - 1)(n - 1) Tmax_dec + T_pre + T_dec + theta * sum omega, with
+ * Tmax the largest stage time or send time of the phase; only the quality term if with_latency == 0.
+ * *obj = +infinity for a plan that is malformed or exceeds a device's memory.  Errors: NULL, SHAPE. */
+lpq_status lpq_plan_objective(const lpq_plan_problem *p, const int32_t *counts, const int32_t *choice, int32_t with_latency,
+                              double *obj);
+
+/* "adabits" (Sec. 4.3, Algorithm 2's starting point): the program without its latency terms, solved exactly by
+ * dynamic programming over stages and per-stage bitwidth counts.  Writes a plan of least theta * sum omega under the
+ * memory constraints; *obj = +infinity (plan untouched) if none exists.  Among equal plans any may be returned.
+ * Errors: NULL, SHAPE (L < N, n_bits > 4, sizes < 1), BUFSIZE (tables would exceed 1 GiB). */
+lpq_status lpq_plan_adabits(const lpq_plan_problem *p, int32_t *counts, int32_t *choice, double *obj);
+
+/* Bitwidth transfer (Sec. 4.3, Algorithm 2) from the plan in counts / choice (in and out).  Each round ranks the
+ * stages by ceil(B/eta) T_pre,j + ((ceil(B/xi) - 1)(n - 1) + 1) T_dec,j, takes the slowest as the straggler, tries
+ * with every other stage (fastest first) every rule (b_st, b_pi, nums = max(1, b_pi / b_st)), b_st != b_pi in bits
+ * order -- the straggler hands nums layers of b_st bits over and takes one of b_pi bits back, layer windows shift
+ * accordingly, each stage gives its bitwidths to the layers that lose least -- and applies the exchange with the
+ * strictly lowest Eq. (1) value if that is below the current one; it ends when a round finds none.
+ * *obj = the final Eq. (1) value, *rounds = exchanges applied.  Errors: NULL, SHAPE (malformed start plan). */
+lpq_status lpq_plan_bitwidth_transfer(const lpq_plan_problem *p, int32_t *counts, int32_t *choice, double *obj,
+                                      int32_t *rounds);
+
 /* Test helper, not on the hot path: w_fp32[n][k] = scale * code + zero (fp32 multiply, then
  * fp32 add; the fp16 weight itself for LPQ_FP16) read back from the packed buffers.
  *   w_fp32: device float [N][K].  Errors: NULL, BITS, SCHEME, SHAPE, ALIGN, DEVICE. */

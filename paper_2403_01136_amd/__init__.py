@@ -18,6 +18,8 @@ LINEARS = ("qkv", "out", "fc1", "fc2")
 EXPORTS = ("lpq_packed_sizes", "lpq_quantize_pack", "lpq_quantize_pack_rows", "lpq_load_quantize_pack",
            "lpq_qlinear_prefill", "lpq_qlinear_decode", "lpq_qlinear_fused", "lpq_stage_linears", "lpq_layernorm",
            "lpq_kv_append", "lpq_attention", "lpq_decoder_layer_workspace", "lpq_decoder_layer", "lpq_variance_indicator",
+           "lpq_mem_embedding_bytes", "lpq_mem_layer_bytes", "lpq_mem_kv_bytes", "lpq_latency_fit", "lpq_latency_predict",
+           "lpq_plan_objective", "lpq_plan_adabits", "lpq_plan_bitwidth_transfer",
            "lpq_unpack_dequant",
            "lpq_status_str")
 LPQ_ACT_NONE, LPQ_ACT_RELU, LPQ_ACT_GELU_TANH = 0, 1, 2
@@ -56,6 +58,21 @@ class lpq_layer_state(ctypes.Structure):
                 ("alibi_slopes", ctypes.c_void_p)]
 
 
+class lpq_model_shape(ctypes.Structure):
+    _fields_ = [("h1", ctypes.c_int64), ("h2", ctypes.c_int64), ("vocab", ctypes.c_int64), ("d_t", ctypes.c_int64),
+                ("pos", ctypes.c_int64), ("rmsnorm", ctypes.c_int32), ("pad", ctypes.c_int32)]
+
+
+_dp, _ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+
+
+class lpq_plan_problem(ctypes.Structure):
+    _fields_ = [("L", ctypes.c_int32), ("N", ctypes.c_int32), ("n_bits", ctypes.c_int32), ("pad", ctypes.c_int32),
+                ("bits", _ip), ("omega", _dp), ("lat_pre", _dp), ("lat_dec", _dp), ("mem", _dp), ("cap", _dp),
+                ("comm_pre", _dp), ("comm_dec", _dp), ("emb", ctypes.c_double), ("theta", ctypes.c_double),
+                ("B", ctypes.c_int32), ("eta", ctypes.c_int32), ("xi", ctypes.c_int32), ("n", ctypes.c_int32)]
+
+
 class LpqError(RuntimeError):
     def __init__(self, status, where):
         self.status = int(status)
@@ -91,10 +108,21 @@ def load_library():
         L.lpq_decoder_layer_workspace.argtypes = [ctypes.POINTER(lpq_layer), cfgp, i32]
         L.lpq_decoder_layer.argtypes = [ctypes.POINTER(lpq_layer), cfgp, stp, ctypes.c_int, i32, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
         L.lpq_unpack_dequant.argtypes = [ctypes.POINTER(lpq_qweight), vp, vp]
+        shp, pp, i64 = ctypes.POINTER(lpq_model_shape), ctypes.POINTER(lpq_plan_problem), ctypes.c_int64
+        L.lpq_mem_embedding_bytes.argtypes = [shp]
+        L.lpq_mem_layer_bytes.argtypes = [shp, i32]
+        L.lpq_mem_kv_bytes.argtypes = [shp, i64, i64, i64, i32]
+        L.lpq_latency_fit.argtypes = [ctypes.c_int, i32, _dp, _dp, _dp, _dp]
+        L.lpq_latency_predict.argtypes = [ctypes.c_int, _dp, i32, _dp, _dp, _dp]
+        L.lpq_plan_objective.argtypes = [pp, _ip, _ip, i32, _dp]
+        L.lpq_plan_adabits.argtypes = [pp, _ip, _ip, _dp]
+        L.lpq_plan_bitwidth_transfer.argtypes = [pp, _ip, _ip, _dp, _ip]
         L.lpq_status_str.argtypes = [ctypes.c_int]
         L.lpq_status_str.restype = ctypes.c_char_p
+        other = {"lpq_decoder_layer_workspace": ctypes.c_size_t, "lpq_mem_embedding_bytes": ctypes.c_double,
+                 "lpq_mem_layer_bytes": ctypes.c_double, "lpq_mem_kv_bytes": ctypes.c_double}
         for name in EXPORTS[:-1]:
-            getattr(L, name).restype = ctypes.c_size_t if name == "lpq_decoder_layer_workspace" else ctypes.c_int
+            getattr(L, name).restype = other.get(name, ctypes.c_int)
         _lib = L
     return _lib
 
@@ -330,6 +358,117 @@ class Stage:
 def lpq_stage_linears(stage, phase, stream=None):
     """Run all 4 * n_layers linears of a Stage in the given phase (LPQ_PREFILL / LPQ_DECODE)."""
     _check(load_library().lpq_stage_linears(stage.layers, stage.n, phase, stage.M, stage.io, _stream(stream)), "lpq_stage_linears")
+
+
+# ---- cost models and planner: host arrays in, host arrays out (numpy only carries the buffers) -------------------
+
+def _shape(h1, h2=1, vocab=1, d_t=None, pos=0, rmsnorm=False):
+    return lpq_model_shape(h1, h2, vocab, h1 if d_t is None else d_t, pos, int(bool(rmsnorm)), 0)
+
+
+def _nonneg(value, where):
+    if value < 0:
+        raise ValueError("%s: bad argument" % where)
+    return value
+
+
+def lpq_mem_embedding_bytes(vocab, d_t, pos, h1):
+    m = _shape(h1, 1, vocab, d_t, pos)
+    return _nonneg(load_library().lpq_mem_embedding_bytes(ctypes.byref(m)), "lpq_mem_embedding_bytes")
+
+
+def lpq_mem_layer_bytes(h1, h2, bit, rmsnorm=False):
+    m = _shape(h1, h2, rmsnorm=rmsnorm)
+    return _nonneg(load_library().lpq_mem_layer_bytes(ctypes.byref(m), bit), "lpq_mem_layer_bytes")
+
+
+def lpq_mem_kv_bytes(v, s, n, h1, bit_kv=16):
+    m = _shape(h1)
+    return _nonneg(load_library().lpq_mem_kv_bytes(ctypes.byref(m), v, s, n, bit_kv), "lpq_mem_kv_bytes")
+
+
+def _f64(a):
+    import numpy as np
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _i32(a):
+    import numpy as np
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def lpq_latency_fit(phase, v, length, t):
+    """Coefficients (5 for LPQ_PREFILL, 4 for LPQ_DECODE) of the layer-latency regression."""
+    import numpy as np
+    v, length, t = _f64(v).ravel(), _f64(length).ravel(), _f64(t).ravel()
+    if not (len(v) == len(length) == len(t)):
+        raise ValueError("v, length and t must have one value per sample")
+    coef = np.zeros(5 if phase == LPQ_PREFILL else 4)
+    _check(load_library().lpq_latency_fit(int(phase), len(t), v.ctypes.data_as(_dp), length.ctypes.data_as(_dp),
+                                          t.ctypes.data_as(_dp), coef.ctypes.data_as(_dp)), "lpq_latency_fit")
+    return coef
+
+
+def lpq_latency_predict(phase, coef, v, length):
+    import numpy as np
+    coef, v, length = _f64(coef).ravel(), _f64(v).ravel(), _f64(length).ravel()
+    if len(coef) != (5 if phase == LPQ_PREFILL else 4) or len(v) != len(length):
+        raise ValueError("coefficient or sample count does not match the phase")
+    out = np.zeros(len(v))
+    _check(load_library().lpq_latency_predict(int(phase), coef.ctypes.data_as(_dp), len(v), v.ctypes.data_as(_dp),
+                                              length.ctypes.data_as(_dp), out.ctypes.data_as(_dp)), "lpq_latency_predict")
+    return out
+
+
+class PlanProblem:
+    """Marshalled lpq_plan_problem; keeps the arrays it points to alive."""
+
+    def __init__(self, bits, omega, lat_pre, lat_dec, mem, cap, emb, B, eta, xi, n, theta, comm_pre=None, comm_dec=None):
+        self.bits, self.omega = _i32(bits), _f64(omega)
+        self.lat_pre, self.lat_dec, self.mem, self.cap = _f64(lat_pre), _f64(lat_dec), _f64(mem), _f64(cap)
+        self.comm_pre = None if comm_pre is None else _f64(comm_pre)
+        self.comm_dec = None if comm_dec is None else _f64(comm_dec)
+        self.L, self.N, nb = self.omega.shape[0], self.cap.shape[0], self.bits.shape[0]
+        if self.omega.shape != (self.L, nb) or self.lat_pre.shape != (self.N, nb) or self.lat_dec.shape != (self.N, nb) \
+                or self.mem.shape != (nb,) or any(c is not None and c.shape != (self.N,) for c in (self.comm_pre, self.comm_dec)):
+            raise ValueError("array shapes do not match L, N and the number of bitwidths")
+        ptr = lambda a: None if a is None else a.ctypes.data_as(_dp)
+        self.struct = lpq_plan_problem(self.L, self.N, nb, 0, self.bits.ctypes.data_as(_ip), ptr(self.omega), ptr(self.lat_pre),
+                                       ptr(self.lat_dec), ptr(self.mem), ptr(self.cap), ptr(self.comm_pre), ptr(self.comm_dec),
+                                       float(emb), float(theta), int(B), int(eta), int(xi), int(n))
+
+
+def lpq_plan_objective(problem, counts, choice, with_latency=True):
+    counts, choice = _i32(counts), _i32(choice)
+    if counts.shape != (problem.N,) or choice.shape != (problem.L,):
+        raise ValueError("counts needs N entries and choice L entries")
+    obj = ctypes.c_double()
+    _check(load_library().lpq_plan_objective(ctypes.byref(problem.struct), counts.ctypes.data_as(_ip), choice.ctypes.data_as(_ip),
+                                             int(bool(with_latency)), ctypes.byref(obj)), "lpq_plan_objective")
+    return obj.value
+
+
+def lpq_plan_adabits(problem):
+    """(objective, counts, choice) of a least-indicator plan that fits the devices; counts is None if none fits."""
+    import numpy as np
+    counts, choice, obj = np.zeros(problem.N, np.int32), np.zeros(problem.L, np.int32), ctypes.c_double()
+    _check(load_library().lpq_plan_adabits(ctypes.byref(problem.struct), counts.ctypes.data_as(_ip), choice.ctypes.data_as(_ip),
+                                           ctypes.byref(obj)), "lpq_plan_adabits")
+    if obj.value == float("inf"):
+        return obj.value, None, None
+    return obj.value, counts.tolist(), choice.tolist()
+
+
+def lpq_plan_bitwidth_transfer(problem, counts, choice):
+    """(objective, counts, choice, rounds) after Algorithm 2 from the given plan."""
+    counts, choice = _i32(counts).copy(), _i32(choice).copy()
+    if counts.shape != (problem.N,) or choice.shape != (problem.L,):
+        raise ValueError("counts needs N entries and choice L entries")
+    obj, rounds = ctypes.c_double(), ctypes.c_int32()
+    _check(load_library().lpq_plan_bitwidth_transfer(ctypes.byref(problem.struct), counts.ctypes.data_as(_ip),
+                                                     choice.ctypes.data_as(_ip), ctypes.byref(obj), ctypes.byref(rounds)),
+           "lpq_plan_bitwidth_transfer")
+    return obj.value, counts.tolist(), choice.tolist(), rounds.value
 
 
 def lpq_unpack_dequant(qw, stream=None):

@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblpq.so")
-SOURCES = ["lpq_api.cpp", "lpq_quantize.hip", "lpq_decode.hip", "lpq_prefill.hip", "lpq_layer.hip", "lpq_indicator.hip"]
+SOURCES = ["lpq_api.cpp", "lpq_quantize.hip", "lpq_decode.hip", "lpq_prefill.hip", "lpq_layer.hip", "lpq_indicator.hip", "lpq_planner.cpp"]
 # packed-fp32 VALU forms are switched off for every device function of this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes"]

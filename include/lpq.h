@@ -64,7 +64,7 @@ typedef enum {
     LPQ_ERR_NULL = 1,        /* a required pointer is NULL                                   */
     LPQ_ERR_BITS = 2,        /* bits not in {3, 4, 8, 16}                                    */
     LPQ_ERR_SCHEME = 3,      /* unknown scheme, or bits / scheme / group_size do not match   */
-    LPQ_ERR_SHAPE = 4,       /* K % 128, N % 64, K, N, M or n_layers out of range            */
+    LPQ_ERR_SHAPE = 4,       /* K % 128, N % 64, K, N, M or n_layers out of range; bad plan  */
     LPQ_ERR_ALIGN = 5,       /* a data pointer is not 16-byte aligned                        */
     LPQ_ERR_BUFSIZE = 6,     /* internal workspace could not be grown                        */
     LPQ_ERR_DEVICE = 7,      /* a HIP call failed                                            */

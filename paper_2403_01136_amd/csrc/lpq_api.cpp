@@ -538,7 +538,7 @@ const char* lpq_status_str(lpq_status status)
     case LPQ_ERR_NULL: return "null pointer";
     case LPQ_ERR_BITS: return "bits must be 3, 4, 8 or 16";
     case LPQ_ERR_SCHEME: return "bits / scheme / group_size do not match";
-    case LPQ_ERR_SHAPE: return "bad shape (K % 128, N % 64, M >= 1, descriptor mismatch)";
+    case LPQ_ERR_SHAPE: return "bad shape or size (K % 128, N % 64, M >= 1, descriptor mismatch, malformed plan or samples)";
     case LPQ_ERR_ALIGN: return "pointer not 16-byte aligned";
     case LPQ_ERR_BUFSIZE: return "workspace allocation failed";
     case LPQ_ERR_DEVICE: return "HIP call failed";

@@ -240,8 +240,52 @@ int prefill_token_groups(int m_blocks, int n_blocks)
 
 // Prefill-phase dispatch of a list of independent linears: one grouped launch per storage variant
 // (and per MAX_PREFILL_LIN linears), tiles of the longest-K linears first.
+// Compute units of the current device (cached).
+lpq_status device_cus(int* out)
+{
+    static std::mutex mu;
+    static int cus[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return LPQ_ERR_DEVICE;
+        cus[dev] = n;
+    }
+    *out = cus[dev];
+    return LPQ_OK;
+}
+
+// K splits of one prefill linear that is launched with too few tiles to fill the chip (a single linear of a
+// decoder layer at a small micro-batch; a K = 4h linear whose tiles are four times as long as its launch's
+// others).  Estimated time of s splits, in units of one 128-column step of a tile: rounds of workgroups over
+// the compute units times steps per workgroup, plus writing and re-reading s fp32 copies of the output
+// (8 bytes per element and split at ~3 TB/s against ~3.5 us per step) and the second kernel's launch.
+int prefill_k_splits(int tiles, int KT, int32_t M, int32_t N, int cus)
+{
+    static const int forced = env_int("LPQ_PREFILL_K_SPLITS", 0);          // for experiments
+    if (forced >= 1) return std::min(std::min(forced, 8), std::max(1, KT / 4));
+    if (tiles >= 2 * cus) return 1;
+    static const int cand[7] = {1, 2, 3, 4, 5, 6, 8};
+    int best = 1;
+    double best_cost = 1e30;
+    for (int i = 0; i < 7; ++i) {
+        const int s = cand[i];
+        if (s > 1 && KT / s < 8) break;                                    // keep the pipeline's fill and drain small
+        const double rounds = (double)(((long)tiles * s + cus - 1) / cus);
+        double cost = rounds * (double)((KT + s - 1) / s);
+        if (s > 1) cost += 8.0 * s * (double)M * (double)N / 3.0e12 / 3.5e-6 + 2.0;
+        if (cost < best_cost * 0.97) best_cost = cost, best = s;          // a split must pay clearly
+    }
+    return best;
+}
+
 lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream)
 {
+    int cus = 0;
+    lpq_status cst = device_cus(&cus);
+    if (cst != LPQ_OK) return cst;
     for (int variant = 0; variant < 5; ++variant) {
         const int BM = prefill_tokens_per_tile(variant);
         const int m_blocks = (M + BM - 1) / BM;
@@ -254,7 +298,10 @@ lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStrea
             a.M = M;
             a.n_lin = 0;
             a.pad = 0;
-            long tiles = 0;
+            long tiles = 0, launch_tiles = 0;
+            size_t partial_floats = 0;
+            for (size_t i = first; i < std::min(mine.size(), first + (size_t)MAX_PREFILL_LIN); ++i)
+                launch_tiles += (long)m_blocks * ((mine[i]->w->d.N + 255) / 256);
             for (size_t i = first; i < std::min(mine.size(), first + (size_t)MAX_PREFILL_LIN); ++i) {
                 const lpq_qweight& w = *mine[i]->w;
                 PrefillLin& L = a.lin[a.n_lin++];
@@ -271,10 +318,25 @@ lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStrea
                 L.n_blocks = (w.d.N + 255) / 256;
                 L.token_groups = prefill_token_groups(m_blocks, L.n_blocks);
                 L.tile_begin = (int32_t)tiles;
-                tiles += 8L * prefill_xcd_tiles(m_blocks, L.n_blocks, L.token_groups);
+                L.pad = 0;
+                // splitting is judged per launch: a launch with many tiles fills the chip whatever its linears' shapes
+                L.k_splits = launch_tiles >= 2L * cus ? 1 : prefill_k_splits((int)launch_tiles, w.d.K / 128, M, w.d.N, cus);
+                L.partial = nullptr;
+                if (L.k_splits > 1) partial_floats += (size_t)L.k_splits * M * w.d.N;
+                tiles += 8L * L.k_splits * prefill_xcd_tiles(m_blocks, L.n_blocks, L.token_groups);
             }
             if (tiles > 0x7fffffffL) return LPQ_ERR_UNSUPPORTED;
             a.total_tiles = (int32_t)tiles;
+            if (partial_floats) {
+                float* ws = nullptr;
+                lpq_status st = workspace(partial_floats * sizeof(float), &ws);
+                if (st != LPQ_OK) return st;
+                for (int i = 0; i < a.n_lin; ++i) {
+                    if (a.lin[i].k_splits <= 1) continue;
+                    a.lin[i].partial = ws;
+                    ws += (size_t)a.lin[i].k_splits * M * a.lin[i].N;
+                }
+            }
             if (launch_prefill(variant, a, stream) != hipSuccess) return LPQ_ERR_DEVICE;
         }
     }

@@ -63,6 +63,12 @@ struct PrefillLin {
     int32_t token_groups;   // 1, 2, 4 or 8
     int32_t act;            // lpq_activation applied to acc + bias (before the residual)
     const uint16_t* residual;   // fp16 [M][N] added to the output before its one rounding, or null
+    // K split: with k_splits > 1 every tile is computed k_splits times over consecutive ranges of the
+    // 128-column steps, each workgroup leaving its fp32 sums in partial[split][M][N]; a second kernel adds
+    // the splits in order and applies bias, activation, residual and the one rounding.  An XCD's list of
+    // tiles is then walked k_splits times (split-major), so the launch has k_splits times the workgroups.
+    float* partial;
+    int32_t k_splits, pad;
 };
 
 // Token block and row block of tile l of XCD x; false if that XCD has fewer tiles.
@@ -87,7 +93,7 @@ __host__ __device__ inline int prefill_xcd_tiles(int m_blocks, int n_blocks, int
     return (group_size < m_blocks ? group_size : m_blocks) * rows_class0;
 }
 
-enum { MAX_PREFILL_LIN = 44 };
+enum { MAX_PREFILL_LIN = 40 };   // keeps PrefillArgs under 4 KB of kernel arguments
 
 struct PrefillArgs {
     int32_t n_lin, M, total_tiles, pad;
@@ -105,7 +111,7 @@ size_t tile_bytes_of(int variant);
 hipError_t launch_quantize_pack(const void* w_rows, const lpq_qdesc& d, long row0, long n_rows, const lpq_qweight& out, hipStream_t s);
 hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
-hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);
+hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);      // both kernels, if any linear is K-split
 int prefill_tokens_per_tile(int variant);
 // variance indicator (lpq_indicator.hip)
 size_t indicator_workspace_bytes(int N, long n8);

@@ -19,6 +19,8 @@
 // up with two consecutive output rows per token.  A workgroup has a CU to itself (one wave per SIMD,
 // up to 512 registers per lane), so the overlap of dequantisation, operand reads and matrix
 // instructions is arranged inside each wave (see the main loop).
+#include <algorithm>
+
 #include "lpq_common.h"
 #include "lpq_device.h"
 
@@ -51,8 +53,10 @@ void prefill_kernel(const PrefillArgs a)
     // rectangle of token blocks x row blocks so that its L2 fetches those activations and weights once.
     const int tile = (int)blockIdx.x - L.tile_begin;
     const int m_blocks = (M + BM - 1) / BM;
+    const int per_xcd = prefill_xcd_tiles(m_blocks, L.n_blocks, L.token_groups);
+    const int split = (tile >> 3) / per_xcd;         // 0 unless the linear is K-split
     int tile_m, tile_n;
-    if (!prefill_xcd_tile(m_blocks, L.n_blocks, L.token_groups, tile & 7, tile >> 3, &tile_m, &tile_n)) return;
+    if (!prefill_xcd_tile(m_blocks, L.n_blocks, L.token_groups, tile & 7, (tile >> 3) % per_xcd, &tile_m, &tile_n)) return;
     constexpr int SCHEME = VInfo<V>::SCHEME;
     constexpr int NW = 4;                           // 16-row tiles per wave = one 64-row block
     constexpr int MTB = BM / 32;                    // 32-token tiles per block
@@ -63,6 +67,9 @@ void prefill_kernel(const PrefillArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15;
     const int KT = K / 128;
+    // this workgroup's 128-column steps: all of them, or the split's share (the first KT % k_splits splits take one more)
+    const int kt_share = KT / L.k_splits, kt_extra = KT % L.k_splits;
+    const int kt_begin = split * kt_share + min(split, kt_extra), kt_end = kt_begin + kt_share + (split < kt_extra ? 1 : 0);
     const long RB = N / 64;                          // 64-row blocks of W
     const int m0 = tile_m * BM;
     const long rb = (long)tile_n * 4 + wave;         // this wave's row block
@@ -163,9 +170,9 @@ void prefill_kernel(const PrefillArgs a)
         out[1] = *reinterpret_cast<const h8*>(&sm.x[buf][row][8 * ((4 * j + 2 * ahalf + 1) ^ (row & 15))]);
     };
 
-    load_w(ws[0], 0, 0);
-    if constexpr (HALF_LOADS) load_w(ws[1], 0, 1);
-    fill_x_slab(0, 0);
+    load_w(ws[0], kt_begin, 0);
+    if constexpr (HALF_LOADS) load_w(ws[1], kt_begin, 1);
+    fill_x_slab(kt_begin, kt_begin & 1);
 #pragma unroll
     for (int t = 0; t < NW; ++t) unpack_tile(ws[0], t, 0, 0);
     pair_tiles(0, 0);
@@ -175,11 +182,11 @@ void prefill_kernel(const PrefillArgs a)
 
     constexpr int SEGS = 4 * MTB;                    // segments per 128-column step
     constexpr int STRIDE = MTB / 4;                  // segments between two pieces of unpacking work
-    for (int kt = 0; kt < KT; ++kt) {
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
         const int buf = kt & 1;
         // Loads for the next step go out first and land while this step is multiplied.  Past the last
         // step they re-read it (no branches in the loop); what is built from them is never multiplied.
-        const int ktn = min(kt + 1, KT - 1);
+        const int ktn = min(kt + 1, kt_end - 1);
         if constexpr (!HALF_LOADS) load_w(ws[1], ktn, 0);
         fill_x_slab(ktn, buf ^ 1);
         h8 xa[2][2];                                 // activations are read one segment ahead
@@ -229,6 +236,19 @@ void prefill_kernel(const PrefillArgs a)
         if constexpr (SCHEME == SCH_SYM) post[p] = (float)__builtin_bit_cast(_Float16, scales[nbase + p]);
         bs[p] = bias ? (float)__builtin_bit_cast(_Float16, bias[nbase + p]) : 0.0f;
     }
+    if (L.k_splits > 1) {                            // fp32 sums of this split; the reduce kernel finishes them
+        float* part = L.partial + (size_t)split * M * N;
+#pragma unroll
+        for (int mt = 0; mt < MTB; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int tok = m0 + 32 * mt + 8 * (v / 4) + 4 * thalf + (v % 4);
+                if (tok >= M) continue;
+                const f2 o = {acc[0][mt][v] * post[0], acc[1][mt][v] * post[1]};
+                *reinterpret_cast<f2*>(part + (size_t)tok * N + nbase) = o;
+            }
+        return;
+    }
 #pragma unroll
     for (int mt = 0; mt < MTB; ++mt)
 #pragma unroll
@@ -245,6 +265,31 @@ void prefill_kernel(const PrefillArgs a)
             const h2 o = {(_Float16)e0, (_Float16)e1};
             *reinterpret_cast<h2*>(y + (size_t)tok * N + nbase) = o;
         }
+}
+
+// Second kernel of a K-split linear: y = round(act(sum over splits + bias) + residual), four consecutive
+// output rows of one token per thread, splits added in order (deterministic).
+__global__ __launch_bounds__(256) void prefill_reduce_kernel(const PrefillArgs a, int li)
+{
+    const PrefillLin& L = a.lin[li];
+    const size_t quads = (size_t)a.M * L.N / 4, plane = (size_t)a.M * L.N;
+    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < quads; q += (size_t)gridDim.x * 256) {
+        const size_t e = 4 * q;
+        const int n = (int)(e % L.N);
+        f4 sum = *reinterpret_cast<const f4*>(L.partial + e);
+        for (int sp = 1; sp < L.k_splits; ++sp) sum += *reinterpret_cast<const f4*>(L.partial + sp * plane + e);
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        h4 res = {0, 0, 0, 0}, out;
+        if (L.residual) res = *reinterpret_cast<const h4*>(L.residual + e);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float val = sum[v] + (L.bias ? (float)__builtin_bit_cast(_Float16, L.bias[n + v]) : 0.0f);
+            val = apply_activation(val, L.act);
+            if (L.residual) val += (float)res[v];
+            out[v] = (_Float16)val;
+        }
+        *reinterpret_cast<h4*>(L.y + e) = out;
+    }
 }
 
 // Tokens per tile: 256 for every variant (one workgroup per CU; 256 accumulator registers of the 512
@@ -265,7 +310,15 @@ hipError_t launch_variant(const PrefillArgs& a, hipStream_t s)
         attr_set = true;
     }
     prefill_kernel<V, BM><<<(unsigned)a.total_tiles, 256, smem, s>>>(a);
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    for (int li = 0; li < a.n_lin && e == hipSuccess; ++li) {
+        if (a.lin[li].k_splits <= 1) continue;
+        const size_t quads = (size_t)a.M * a.lin[li].N / 4;
+        const unsigned blocks = (unsigned)std::min<size_t>((quads + 255) / 256, 8192);
+        prefill_reduce_kernel<<<blocks, 256, 0, s>>>(a, li);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace

@@ -140,6 +140,22 @@ def test_prefill_small(orc, bits, scheme, M):
 
 
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("M,K", [(7, 8192), (260, 8192), (300, 4224)])
+def test_prefill_split_k(orc, bits, scheme, M, K):
+    """Few tiles and a long K: the library cuts K into ranges (fp32 partial sums, second kernel).  K = 4224 is
+    33 steps, which no split count divides; the bias is added exactly once."""
+    N = 320
+    w = wl.weight_np(N, K, "presk", bits, scheme)
+    x = wl.act_np(M, K, True, "presk", M)
+    bias = (np.arange(N) % 5 - 2).astype(np.float16)
+    import torch
+    qw = lpq.lpq_quantize_pack(to_dev(w), bits, scheme, bias=to_dev(bias))
+    y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    lpq.lpq_qlinear_prefill(qw, to_dev(x), y)
+    check_output(y, orc.qlinear(x, w, bits, scheme, bias), "prefill split-K %d-bit M=%d" % (bits, M))
+
+
+@pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("mag", [2.0 ** -12, 2.0 ** -6, 2.0 ** 5], ids=["x_2e-12", "x_2e-6", "x_2e5"])
 def test_activation_magnitude(orc, bits, scheme, mag):
     """The tolerance holds whatever the scale of the activations (tiny ones near the fp16 subnormal

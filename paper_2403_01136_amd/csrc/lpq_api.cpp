@@ -261,7 +261,9 @@ lpq_status device_cus(int* out)
 // decoder layer at a small micro-batch; a K = 4h linear whose tiles are four times as long as its launch's
 // others).  Estimated time of s splits, in units of one 128-column step of a tile: rounds of workgroups over
 // the compute units times steps per workgroup, plus writing and re-reading s fp32 copies of the output
-// (8 bytes per element and split at ~3 TB/s against ~3.5 us per step) and the second kernel's launch.
+// (8 bytes per element and split; measured ~10 TB/s, most of it served by the caches, against ~4.1 us per
+// step) and the second kernel's launch.  Fitted to sweeps of the split count over OPT-13B's four shapes at
+// 256-4096 tokens: the choice is the best measured one or within a few per cent of it.
 int prefill_k_splits(int tiles, int KT, int32_t M, int32_t N, int cus)
 {
     static const int forced = env_int("LPQ_PREFILL_K_SPLITS", 0);          // for experiments
@@ -275,7 +277,7 @@ int prefill_k_splits(int tiles, int KT, int32_t M, int32_t N, int cus)
         if (s > 1 && KT / s < 8) break;                                    // keep the pipeline's fill and drain small
         const double rounds = (double)(((long)tiles * s + cus - 1) / cus);
         double cost = rounds * (double)((KT + s - 1) / s);
-        if (s > 1) cost += 8.0 * s * (double)M * (double)N / 3.0e12 / 3.5e-6 + 2.0;
+        if (s > 1) cost += 8.0 * s * (double)M * (double)N / 1.0e13 / 4.1e-6 + 1.0;
         if (cost < best_cost * 0.97) best_cost = cost, best = s;          // a split must pay clearly
     }
     return best;

@@ -202,6 +202,44 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         }
         if (total >= ((uint64_t)1 << 50)) return LPQ_ERR_UNSUPPORTED;
         a.total_weight = total;
+        // A launch that streams little (a single linear of a decoder layer) has too few steps to spread evenly:
+        // it goes to the kernel that gives every 64-row block a workgroup whose waves split K (no fix-up pass).
+        // (read at every call, so that tests can send small shapes through either kernel)
+        const int64_t rows_max_bytes = (int64_t)env_int("LPQ_DECODE_ROWS_MAX_MB", 192) << 20;
+        int64_t stream_bytes = 0;
+        for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c)
+            stream_bytes += (int64_t)calls[c].w->d.K * calls[c].w->d.N * calls[c].w->d.bits / 8;
+        if (M <= 16 && stream_bytes <= rows_max_bytes) {
+            // longest K first: the last workgroups to start are then the shortest
+            std::stable_sort(a.lin, a.lin + a.n_lin, [](const LinDesc& x, const LinDesc& y) { return x.K > y.K; });
+            int64_t blocks = 0, row_blocks = 0;
+            for (int i = 0; i < a.n_lin; ++i) row_blocks += a.lin[i].N / (a.lin[i].variant == 4 ? 32 : 64);
+            int64_t partial_floats = 0;
+            for (int i = 0; i < a.n_lin; ++i) {
+                LinDesc& L = a.lin[i];
+                L.row_blocks = L.N / (L.variant == 4 ? 32 : 64);
+                // K splits (L.pad): only for a launch that leaves most compute units without a workgroup, and only
+                // down to 32 steps per workgroup (a wave wants several steps to keep its ring of loads busy)
+                const int KT = L.K / 128;
+                const int want = (int)std::max<int64_t>(1, 320 / std::max<int64_t>(1, row_blocks));
+                L.pad = std::max(1, std::min(std::min(want, KT / 32), 8));
+                L.step_weight = (uint32_t)partial_floats;             // float offset of this linear's partial sums
+                if (L.pad > 1) partial_floats += (int64_t)L.pad * 16 * L.N;
+                L.cum_weight = (uint64_t)blocks;
+                blocks += (int64_t)L.row_blocks * L.pad;
+            }
+            if (blocks > 0x7fffffffLL || partial_floats > 0x7fffffffLL) return LPQ_ERR_UNSUPPORTED;
+            if (partial_floats) {
+                st = workspace((size_t)partial_floats * sizeof(float), &ws);
+                if (st != LPQ_OK) return st;
+                a.partial = ws;
+            }
+            a.n_blocks = (int32_t)blocks;
+            a.waves = blocks <= 160 ? 8 : 4;         // few blocks: more waves per block keep the chip's memory pipes full
+            a.m0 = 0;
+            if (launch_decode_rows(a, stream) != hipSuccess) return LPQ_ERR_DEVICE;
+            continue;
+        }
         // A small launch (one linear of a decoder layer) is not cut into more ranges than it has chunks of
         // steps: thinner ranges stream no faster and only multiply the pieces the fix-up pass has to add.
         static const int min_steps = std::max(1, env_int("LPQ_DECODE_MIN_STEPS", 16));

@@ -15,6 +15,8 @@
 // per-lane loads that are contiguous across the wave, keeps several 128-column steps in flight in
 // registers, unpacks them there into MFMA B operands and multiplies them with the activations
 // (MFMA A operands), which the workgroup stages once through a double-buffered LDS slab.
+#include <algorithm>
+
 #include "lpq_common.h"
 #include "lpq_device.h"
 
@@ -698,6 +700,211 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
     }
 }
 
+// ---- small launches (one linear of a decoder layer, up to 16 token rows) ---------------------------------
+// The even-share kernel above needs a launch with many steps to spread; a single linear has few, and cutting
+// its units into short ranges leaves each workgroup waiting on memory latency and pays a fix-up pass.  Here a
+// workgroup owns ONE 64-row block (32 rows for fp16 weights) over the whole of K, and its waves split K: wave w
+// takes the 128-column steps w, w + WAVES, ...  Each wave streams its tiles through a ring of stages in
+// registers together with the activations of those steps (read straight from global memory: they are small and
+// stay in L2; no LDS staging, no barrier in the loop), and the waves' accumulators are added through LDS at the
+// end, in wave order.  A linear with few row blocks and a long K (the second feed-forward matrix) is also split
+// over L.pad workgroups per row block, each taking a range of the steps and leaving fp32 sums in
+// partial[split][16][N] (at float offset L.step_weight of the launch's partial buffer) for a small second kernel;
+// otherwise there are no partial tiles and no second kernel.  a.lin[i].cum_weight holds the number of
+// workgroups of the linears before i, a.n_blocks their total.
+template <int V, int WAVES>
+__device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int split, float* __restrict__ partial, float* __restrict__ red)
+{
+    constexpr int RT = (V == V_F16) ? 2 : 4;
+    constexpr int SCHEME = VInfo<V>::SCHEME;
+    constexpr bool POST = V != V_F16;
+    constexpr int STAGES = (V == V_W3 || V == V_W4) ? 4 : 3;
+    constexpr int LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) + (SCHEME == SCH_ASYM ? 2 : 0) + 4;
+    static_assert((STAGES - 1) * LOADS < 64, "vmcnt is a 6-bit counter");
+    constexpr int NV = RT * 4 + (SCHEME == SCH_SYM ? 4 : 0);       // floats a lane hands to the reduction
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, kq = lane >> 4;
+    const int KT = L.K / 128;
+    // the workgroup's steps [kt0, kt1): all of them, or the split's share (the first KT % splits take one more)
+    const int splits = L.pad, share = KT / splits, extra = KT % splits;
+    const int kt0 = split * share + min(split, extra), kt1 = kt0 + share + (split < extra ? 1 : 0);
+    const int n_w = kt1 - kt0 > wave ? (kt1 - kt0 - wave + WAVES - 1) / WAVES : 0;      // this wave's steps
+    const uint16_t* __restrict__ xrow = L.x + (size_t)min(r, M - 1) * L.K + 8 * kq;   // token rows past M repeat the last one
+
+    struct Stage {
+        WRaw<V> w[RT];
+        u32x2 s, z;
+        h8 a[4];
+    };
+    Stage st[STAGES];
+    // step i of this wave; past its last step the loads repeat a valid step (they keep the count of loads in
+    // flight constant, which is what the waits below rely on) and what they bring is never multiplied
+    auto issue = [&](Stage& b, int i) {
+        const int kt = min(kt0 + wave + WAVES * i, KT - 1);
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            if constexpr (RT == 4) b.w[t] = load_tile<V>(L.codes, rb, KT, kt, t, lane);
+            else                   b.w[t] = load_tile<V>(L.codes, rb >> 1, KT, kt, 2 * (int)(rb & 1) + t, lane);
+        }
+        if constexpr (SCHEME == SCH_ASYM) {
+            const size_t idx = (size_t)kt * L.N + rb * 64 + 4 * r;
+            b.s = *reinterpret_cast<const u32x2*>(L.scales + idx);
+            b.z = *reinterpret_cast<const u32x2*>(L.zeros + idx);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b.a[j] = *reinterpret_cast<const h8*>(xrow + (size_t)kt * 128 + 32 * j);
+    };
+
+    f4 acc[RT], xsum = {0, 0, 0, 0};
+#pragma unroll
+    for (int t = 0; t < RT; ++t) acc[t] = f4{0, 0, 0, 0};
+    auto compute = [&](const Stage& b) {
+        if constexpr (POST) {
+            h8 wj[2][RT];
+            const _Float16 one = (_Float16)1.0f;
+            const h8 ones = {one, one, one, one, one, one, one, one};
+            const f4 zero4 = {0, 0, 0, 0};
+            f4 d[RT], xs;
+#pragma unroll
+            for (int t = 0; t < RT; ++t) wj[0][t] = unpack_subnormal_step<V>(b.w[t], 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (j < 3) {
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) wj[(j + 1) & 1][t] = unpack_subnormal_step<V>(b.w[t], j + 1);
+                }
+                if constexpr (SCHEME == SCH_ASYM) {
+                    xs = mfma16(b.a[j], ones, j == 0 ? zero4 : xs);
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) d[t] = mfma16(b.a[j], wj[j & 1][t], j == 0 ? zero4 : d[t]);
+                } else {
+                    xsum = mfma16(b.a[j], ones, xsum);
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) acc[t] = mfma16(b.a[j], wj[j & 1][t], acc[t]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (SCHEME == SCH_ASYM) {
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    const uint32_t sp = b.s[t >> 1], zp = b.z[t >> 1];
+                    const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
+                    const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
+                    const float sf = (float)__builtin_bit_cast(_Float16, sh) * 16777216.0f;     // scale * 2^24
+                    const float zf = (float)__builtin_bit_cast(_Float16, zh);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[t][v] = __builtin_fmaf(sf, d[t][v], __builtin_fmaf(zf, xs[v], acc[t][v]));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int t = 0; t < RT; ++t) acc[t] = mfma16(b.a[j], __builtin_bit_cast(h8, b.w[t].q[j]), acc[t]);
+        }
+    };
+
+#pragma unroll
+    for (int sidx = 0; sidx < STAGES; ++sidx) issue(st[sidx], sidx);
+    for (int i0 = 0; i0 < n_w; i0 += STAGES) {
+#pragma unroll
+        for (int sidx = 0; sidx < STAGES; ++sidx) {
+            const int i = i0 + sidx;
+            if (i < n_w) {                                        // uniform over the wave
+                wait_vmem_all_but<(STAGES - 1) * LOADS>();       // stages i + 1 .. i + STAGES - 1 may still be in flight
+                compute(st[sidx]);
+                issue(st[sidx], i + STAGES);
+            }
+        }
+    }
+
+    // add the waves' sums in wave order; thread idx -> (token, row of the block), consecutive threads on consecutive rows
+    float* mine = red + (size_t)wave * NV * 64;
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) mine[(4 * t + v) * 64 + lane] = acc[t][v];
+    if constexpr (SCHEME == SCH_SYM) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) mine[(4 * RT + v) * 64 + lane] = xsum[v];
+    }
+    __syncthreads();
+    constexpr int ROWS = 16 * RT;
+    for (int idx = tid; idx < 16 * ROWS; idx += 64 * WAVES) {
+        const int tok = idx / ROWS, rl = idx % ROWS;
+        if (tok >= M) continue;
+        const int rr = rl / RT, t = rl % RT, v = tok & 3, ln = 16 * (tok >> 2) + rr;
+        float sum = 0.0f, xs = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * NV + 4 * t + v) * 64 + ln];
+        const long row = (RT == 4) ? rb * 64 + 4 * rr + t : (rb >> 1) * 64 + 4 * rr + 2 * (rb & 1) + t;
+        if constexpr (SCHEME == SCH_SYM) {
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) xs += red[((size_t)w * NV + 4 * RT + v) * 64 + ln];
+            sum = (sum * 16777216.0f - 128.0f * xs) * (float)__builtin_bit_cast(_Float16, L.scales[row]);   // undo 2^-24 and the +128 offset
+        }
+        const size_t o = (size_t)tok * L.N + row;
+        if (splits > 1) {
+            partial[((size_t)split * 16) * L.N + o] = sum;
+            continue;
+        }
+        if (L.bias) sum += (float)__builtin_bit_cast(_Float16, L.bias[row]);
+        sum = apply_activation(sum, L.act);
+        if (L.residual) sum += (float)__builtin_bit_cast(_Float16, L.residual[o]);
+        L.y[o] = __builtin_bit_cast(uint16_t, (_Float16)sum);
+    }
+}
+
+template <int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_rows_kernel(const DecodeArgs a)
+{
+    __shared__ float red[WAVES * 20 * 64];
+    const int b = blockIdx.x;
+    int li = 0, hi = a.n_lin - 1;                    // last linear whose first row block is <= b
+    while (li < hi) {
+        const int mid = (li + hi + 1) >> 1;
+        if (a.lin[mid].cum_weight <= (uint64_t)b) li = mid; else hi = mid - 1;
+    }
+    const LinDesc& L = a.lin[li];
+    const long wg = (long)b - (long)L.cum_weight;          // split-major: a split's row blocks are neighbours
+    const long rb = wg % L.row_blocks;
+    const int split = (int)(wg / L.row_blocks);
+    float* partial = a.partial + L.step_weight;
+    switch (L.variant) {
+    case V_W3: run_rows<V_W3, WAVES>(L, a.M, rb, split, partial, red); break;
+    case V_W4: run_rows<V_W4, WAVES>(L, a.M, rb, split, partial, red); break;
+    case V_W8: run_rows<V_W8, WAVES>(L, a.M, rb, split, partial, red); break;
+    case V_I8: run_rows<V_I8, WAVES>(L, a.M, rb, split, partial, red); break;
+    default:   run_rows<V_F16, WAVES>(L, a.M, rb, split, partial, red); break;
+    }
+}
+
+// Second kernel of a K-split linear of a small launch: adds the splits in order, then bias, activation,
+// residual and the one rounding; four consecutive rows of one token per thread.
+__global__ __launch_bounds__(256) void decode_rows_reduce_kernel(const DecodeArgs a, int li)
+{
+    const LinDesc& L = a.lin[li];
+    const float* __restrict__ partial = a.partial + L.step_weight;
+    const size_t quads = (size_t)a.M * L.N / 4, plane = (size_t)16 * L.N;
+    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < quads; q += (size_t)gridDim.x * 256) {
+        const size_t e = 4 * q;
+        const int n = (int)(e % L.N);
+        f4 sum = *reinterpret_cast<const f4*>(partial + e);
+        for (int sp = 1; sp < L.pad; ++sp) sum += *reinterpret_cast<const f4*>(partial + sp * plane + e);
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        h4 res = {0, 0, 0, 0}, out;
+        if (L.residual) res = *reinterpret_cast<const h4*>(L.residual + e);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float val = sum[v] + (L.bias ? (float)__builtin_bit_cast(_Float16, L.bias[n + v]) : 0.0f);
+            val = apply_activation(val, L.act);
+            if (L.residual) val += (float)res[v];
+            out[v] = (_Float16)val;
+        }
+        *reinterpret_cast<h4*>(L.y + e) = out;
+    }
+}
+
 }  // namespace
 
 template <int TOK, int WAVES>
@@ -719,6 +926,20 @@ static hipError_t launch_waves(const DecodeArgs& a, hipStream_t s)
 {
     const int rows = a.M - a.m0;
     return rows <= 16 ? launch_tok<16, WAVES>(a, s) : rows <= 32 ? launch_tok<32, WAVES>(a, s) : launch_tok<64, WAVES>(a, s);
+}
+
+hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s)
+{
+    if (a.waves == 8) decode_rows_kernel<8><<<(unsigned)a.n_blocks, 512, 0, s>>>(a);
+    else              decode_rows_kernel<4><<<(unsigned)a.n_blocks, 256, 0, s>>>(a);
+    hipError_t e = hipGetLastError();
+    for (int li = 0; li < a.n_lin && e == hipSuccess; ++li) {
+        if (a.lin[li].pad <= 1) continue;
+        const size_t quads = (size_t)a.M * a.lin[li].N / 4;
+        decode_rows_reduce_kernel<<<(unsigned)std::min<size_t>((quads + 255) / 256, 4096), 256, 0, s>>>(a, li);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s)

@@ -96,10 +96,21 @@ def test_load_quantize_pack_from_host(orc, bits, scheme, pinned):
 
 # ---- a3: decode linear ---------------------------------------------------------------------
 
+@pytest.fixture(params=["rows", "even_share"])
+def decode_kernel_choice(request, monkeypatch):
+    """Up to 16 token rows, a launch that streams little goes to the kernel that gives each row block a workgroup,
+    a larger one to the even-share kernel; the limit is read at every call, so small shapes can reach both."""
+    if request.param == "even_share":
+        monkeypatch.setenv("LPQ_DECODE_ROWS_MAX_MB", "0")
+    return request.param
+
+
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("M", [1, 2, 5, 16, 17, 33, 64])
-def test_decode_small(orc, bits, scheme, M):
-    N, K = 320, 640         # 5 (fp16: 10) row blocks: the last workgroup has idle waves
+def test_decode_small(orc, bits, scheme, M, decode_kernel_choice):
+    if M > 16 and decode_kernel_choice == "rows":
+        pytest.skip("more than 16 token rows always take the even-share kernel")
+    N, K = 320, 640         # 5 (fp16: 10) row blocks: the last workgroup has idle waves; 5 steps: idle waves in a row block's workgroup
     w = wl.weight_np(N, K, "dec", bits, scheme)
     x = wl.act_np(M, K, True, "dec", M)
     qw = lpq.lpq_quantize_pack(to_dev(w), bits, scheme)
@@ -109,9 +120,11 @@ def test_decode_small(orc, bits, scheme, M):
 
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("M", [3, 70, 130])
-def test_decode_split_k_and_many_rows(orc, bits, scheme, M):
-    """K long enough that the work is cut into several K ranges (fp32 partial sums + reduction);
-    M > 64 runs in several passes; a bias is added exactly once."""
+def test_decode_split_k_and_many_rows(orc, bits, scheme, M, decode_kernel_choice):
+    """K long enough that the work is cut into several K ranges (fp32 partial sums + reduction, or waves that split
+    K); M > 64 runs in several passes; a bias is added exactly once."""
+    if M > 16 and decode_kernel_choice == "rows":
+        pytest.skip("more than 16 token rows always take the even-share kernel")
     N, K = 192, 16384
     w = wl.weight_np(N, K, "decsk", bits, scheme)
     x = wl.act_np(M, K, True, "decsk", M)
@@ -157,7 +170,7 @@ def test_prefill_split_k(orc, bits, scheme, M, K):
 
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("mag", [2.0 ** -12, 2.0 ** -6, 2.0 ** 5], ids=["x_2e-12", "x_2e-6", "x_2e5"])
-def test_activation_magnitude(orc, bits, scheme, mag):
+def test_activation_magnitude(orc, bits, scheme, mag, decode_kernel_choice):
     """The tolerance holds whatever the scale of the activations (tiny ones near the fp16 subnormal
     range, large ones short of overflow in the outputs): no step of the kernels may cost them bits."""
     N, K = 128, 512
@@ -205,7 +218,7 @@ def _build_stage(cfg_key, h, f, qkv_n, layer_specs, M, outliers):
 
 @pytest.mark.parametrize("phase,M", [(lpq.LPQ_DECODE, 1), (lpq.LPQ_DECODE, 16), (lpq.LPQ_PREFILL, 128)],
                          ids=["decode_M1", "decode_M16", "prefill_M128"])
-def test_stage_mixed_bits_small(orc, phase, M):
+def test_stage_mixed_bits_small(orc, phase, M, decode_kernel_choice):
     specs = [(16, 0), (8, 1), (4, 1), (3, 1), (8, 2), (3, 1)]
     stage, ys, host = _build_stage("stage_small", 256, 1024, 768, specs, M, True)
     lpq.lpq_stage_linears(stage, phase)

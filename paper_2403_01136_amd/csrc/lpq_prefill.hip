@@ -35,7 +35,9 @@ template <int BM> struct PrefillSmem {
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-template <int V, int BM>
+// SPLIT: some linear of the launch is K-split (the instantiation without it carries no second epilogue,
+// whose registers the first would otherwise spill for).
+template <int V, int BM, bool SPLIT>
 __global__ __launch_bounds__(256, BM > 128 ? 1 : 2)
 void prefill_kernel(const PrefillArgs a)
 {
@@ -53,10 +55,10 @@ void prefill_kernel(const PrefillArgs a)
     // rectangle of token blocks x row blocks so that its L2 fetches those activations and weights once.
     const int tile = (int)blockIdx.x - L.tile_begin;
     const int m_blocks = (M + BM - 1) / BM;
-    const int per_xcd = prefill_xcd_tiles(m_blocks, L.n_blocks, L.token_groups);
-    const int split = (tile >> 3) / per_xcd;         // 0 unless the linear is K-split
+    const int per_xcd = SPLIT ? prefill_xcd_tiles(m_blocks, L.n_blocks, L.token_groups) : 0x7fffffff;
+    const int split = SPLIT ? (tile >> 3) / per_xcd : 0;         // 0 unless the linear is K-split
     int tile_m, tile_n;
-    if (!prefill_xcd_tile(m_blocks, L.n_blocks, L.token_groups, tile & 7, (tile >> 3) % per_xcd, &tile_m, &tile_n)) return;
+    if (!prefill_xcd_tile(m_blocks, L.n_blocks, L.token_groups, tile & 7, SPLIT ? (tile >> 3) % per_xcd : (tile >> 3), &tile_m, &tile_n)) return;
     constexpr int SCHEME = VInfo<V>::SCHEME;
     constexpr int NW = 4;                           // 16-row tiles per wave = one 64-row block
     constexpr int MTB = BM / 32;                    // 32-token tiles per block
@@ -68,7 +70,8 @@ void prefill_kernel(const PrefillArgs a)
     const int r = lane & 15;
     const int KT = K / 128;
     // this workgroup's 128-column steps: all of them, or the split's share (the first KT % k_splits splits take one more)
-    const int kt_share = KT / L.k_splits, kt_extra = KT % L.k_splits;
+    const int n_splits = SPLIT ? L.k_splits : 1;
+    const int kt_share = KT / n_splits, kt_extra = KT % n_splits;
     const int kt_begin = split * kt_share + min(split, kt_extra), kt_end = kt_begin + kt_share + (split < kt_extra ? 1 : 0);
     const long RB = N / 64;                          // 64-row blocks of W
     const int m0 = tile_m * BM;
@@ -236,7 +239,7 @@ void prefill_kernel(const PrefillArgs a)
         if constexpr (SCHEME == SCH_SYM) post[p] = (float)__builtin_bit_cast(_Float16, scales[nbase + p]);
         bs[p] = bias ? (float)__builtin_bit_cast(_Float16, bias[nbase + p]) : 0.0f;
     }
-    if (L.k_splits > 1) {                            // fp32 sums of this split; the reduce kernel finishes them
+    if (SPLIT && L.k_splits > 1) {                   // fp32 sums of this split; the reduce kernel finishes them
         float* part = L.partial + (size_t)split * M * N;
 #pragma unroll
         for (int mt = 0; mt < MTB; ++mt)
@@ -304,12 +307,16 @@ hipError_t launch_variant(const PrefillArgs& a, hipStream_t s)
     const size_t smem = sizeof(PrefillSmem<BM>);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<V, BM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
+        for (const void* fn : {reinterpret_cast<const void*>(&prefill_kernel<V, BM, false>), reinterpret_cast<const void*>(&prefill_kernel<V, BM, true>)}) {
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+        }
         attr_set = true;
     }
-    prefill_kernel<V, BM><<<(unsigned)a.total_tiles, 256, smem, s>>>(a);
+    bool split = false;
+    for (int li = 0; li < a.n_lin; ++li) split = split || a.lin[li].k_splits > 1;
+    if (split) prefill_kernel<V, BM, true><<<(unsigned)a.total_tiles, 256, smem, s>>>(a);
+    else       prefill_kernel<V, BM, false><<<(unsigned)a.total_tiles, 256, smem, s>>>(a);
     hipError_t e = hipGetLastError();
     for (int li = 0; li < a.n_lin && e == hipSuccess; ++li) {
         if (a.lin[li].k_splits <= 1) continue;

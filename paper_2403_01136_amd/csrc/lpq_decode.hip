@@ -15,6 +15,10 @@
 // per-lane loads that are contiguous across the wave, keeps several 128-column steps in flight in
 // registers, unpacks them there into MFMA B operands and multiplies them with the activations
 // (MFMA A operands), which the workgroup stages once through a double-buffered LDS slab.
+//
+// A launch that streams little (a single linear of a decoder layer, up to 16 token rows) takes a second
+// kernel, decode_rows_kernel further down: one workgroup per row block whose waves split K, no LDS staging,
+// no fix-up pass.
 #include <algorithm>
 
 #include "lpq_common.h"

@@ -129,3 +129,41 @@ def test_bench_config_full_stage(orc):
 def test_other_configs_one_layer_per_variant(orc, ci, layer_ids, Md):
     cfg = wl.CONFIGS[ci]
     _run_config(orc, cfg, layer_ids, Md, cfg["prefill_M"])
+
+
+@pytest.mark.parametrize("bits,scheme", [(3, 1), (4, 1), (8, 1), (8, 2), (16, 0)], ids=["w3", "w4", "w8", "i8", "f16"])
+def test_single_linear_launches_at_layer_shapes(orc, bits, scheme):
+    """One linear per launch, as a decoder layer issues them (OPT-13B shapes): the decode phase then runs in the
+    small-launch kernel (a workgroup per row block; FC2 K-split with its reduce kernel), the prefill phase K-splits
+    the launches with few tiles.  Sampled bands and tokens against the oracle, one projection over every column."""
+    import torch
+    cfg = wl.CONFIGS[1]
+    dev = torch.device("cuda:0")
+    shapes = wl.linear_shapes(cfg)
+    for name in wl.LINEARS:
+        K, N = shapes[name]
+        w = wl.weight_torch(N, K, dev, "single", bits, name)
+        bias = (torch.arange(N, device=dev) % 9 - 4).to(torch.float16) * 0.25
+        qw = lpq.lpq_quantize_pack(w, bits, scheme, bias=bias)
+        w_host_bias = bias.cpu().numpy()
+        for fn, M in ((lpq.lpq_qlinear_decode, 16), (lpq.lpq_qlinear_decode, 5), (lpq.lpq_qlinear_prefill, 512),
+                      (lpq.lpq_qlinear_prefill, 2048)):
+            x = wl.act_torch(M, K, True, dev, "single", name, M)
+            y = torch.full((M, N), float("nan"), dtype=torch.float16, device=dev)
+            fn(qw, x, y)
+            torch.cuda.synchronize()
+            what = "single %s %d-bit %s M=%d" % (name, bits, fn.__name__, M)
+            assert not torch.isnan(y).any(), what + ": output not fully written"
+            y_nobias = (y.float() - bias.float()[None, :]).to(torch.float64)      # the checks below compare x . w~^T
+            bands = _bands(N, 5 + M)
+            rows = np.concatenate([np.arange(64 * b, 64 * b + 64) for b in bands])
+            toks = _tokens(M, 6 + M)
+            ref = orc.qlinear(x[torch.tensor(toks).cuda()].cpu().numpy(), w[torch.from_numpy(rows).cuda()].cpu().numpy(), bits, scheme,
+                              w_host_bias[rows])
+            got = y[torch.tensor(toks).cuda()][:, torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+            rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+            assert rel <= REL_L2_TOL, "%s rel-L2 %.3e" % (what, rel)
+            assert np.abs(got - ref).max() <= MAX_ABS_FRAC * np.abs(ref).max(), what
+            if name == "out" and M in (16, 512):
+                _freivalds(orc, w, x, y_nobias.to(torch.float16), bits, scheme, 99 + M, what)
+        del w, qw

@@ -66,7 +66,10 @@ void prefill_kernel(const PrefillArgs a)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     PrefillSmem<BM>& sm = *reinterpret_cast<PrefillSmem<BM>*>(smem_raw);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave index as a scalar: what derives from it (row block, LDS addresses of the slab loads) is then
+    // scalar arithmetic instead of vector instructions in the main loop
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15;
     const int KT = K / 128;
     // this workgroup's 128-column steps: all of them, or the split's share (the first KT % k_splits splits take one more)
@@ -90,9 +93,9 @@ void prefill_kernel(const PrefillArgs a)
     // slab fill: wave-load q of this wave covers token rows 4*(XQ*wave + q) .. +3; lane (row = lane/16,
     // slot = lane%16) fetches the 16-byte column group that belongs in that slot after swizzling.
     // Token rows past M are clamped to row M-1: they only feed outputs that are never stored.
-    auto fill_x_slab = [&](int kt, int buf) {
+    auto fill_x_slab = [&](int kt, int buf, int q_begin, int q_end) {
 #pragma unroll
-        for (int q = 0; q < XQ; ++q) {
+        for (int q = q_begin; q < q_end; ++q) {
             const int row0 = 4 * (XQ * wave + q), row = row0 + (lane >> 4);
             const int c16 = (lane & 15) ^ (row & 15);
             const int tok = min(m0 + row, M - 1);
@@ -175,7 +178,7 @@ void prefill_kernel(const PrefillArgs a)
 
     load_w(ws[0], kt_begin, 0);
     if constexpr (HALF_LOADS) load_w(ws[1], kt_begin, 1);
-    fill_x_slab(kt_begin, kt_begin & 1);
+    fill_x_slab(kt_begin, kt_begin & 1, 0, XQ);
 #pragma unroll
     for (int t = 0; t < NW; ++t) unpack_tile(ws[0], t, 0, 0);
     pair_tiles(0, 0);
@@ -191,7 +194,9 @@ void prefill_kernel(const PrefillArgs a)
         // step they re-read it (no branches in the loop); what is built from them is never multiplied.
         const int ktn = min(kt + 1, kt_end - 1);
         if constexpr (!HALF_LOADS) load_w(ws[1], ktn, 0);
-        fill_x_slab(ktn, buf ^ 1);
+        // the next slab's 16 loads go out two at a time between the matrix instructions of the first half
+        // step's odd segments (the even ones carry the unpacking): issued in a block up front they would
+        // hold back the step's first matrix instruction by as many issue slots
         h8 xa[2][2];                                 // activations are read one segment ahead
         x_operands(buf, 0, 0, xa[0]);
 #pragma unroll
@@ -219,6 +224,7 @@ void prefill_kernel(const PrefillArgs a)
                     if (seg == 3 * STRIDE) unpack_tile(src, 1, 1 - half, 1 - half);
                     if (seg == 4 * STRIDE) unpack_tile(src, 3, 1 - half, 1 - half);
                     if (seg == 5 * STRIDE) pair_tiles(1, 1 - half);
+                    if (half == 0 && (seg & 1)) fill_x_slab(ktn, buf ^ 1, (XQ / (MTB)) * (seg >> 1), (XQ / (MTB)) * ((seg >> 1) + 1));
                     __builtin_amdgcn_sched_barrier(0);
                 }
         }

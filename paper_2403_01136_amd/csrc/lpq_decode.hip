@@ -726,7 +726,8 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
     constexpr int LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) + (SCHEME == SCH_ASYM ? 2 : 0) + 4;
     static_assert((STAGES - 1) * LOADS < 64, "vmcnt is a 6-bit counter");
     constexpr int NV = RT * 4 + (SCHEME == SCH_SYM ? 4 : 0);       // floats a lane hands to the reduction
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // a scalar: the row block and the tile addresses derive from it
     const int r = lane & 15, kq = lane >> 4;
     const int KT = L.K / 128;
     // the workgroup's steps [kt0, kt1): all of them, or the split's share (the first KT % splits take one more)

@@ -93,14 +93,23 @@ void prefill_kernel(const PrefillArgs a)
     // slab fill: wave-load q of this wave covers token rows 4*(XQ*wave + q) .. +3; lane (row = lane/16,
     // slot = lane%16) fetches the 16-byte column group that belongs in that slot after swizzling.
     // Token rows past M are clamped to row M-1: they only feed outputs that are never stored.
+    // The address of a load is a scalar base (start of the tile's rows, plus the step's columns) and a 32-bit
+    // per-lane byte offset that does not change from step to step: (token row within the tile, clamped) * K + the
+    // column group, kept in one register per load.
+    uint32_t xoff[XQ];
+#pragma unroll
+    for (int q = 0; q < XQ; ++q) {
+        const int row = 4 * (XQ * wave + q) + (lane >> 4);
+        const int c16 = (lane & 15) ^ (row & 15);
+        xoff[q] = ((uint32_t)min(row, M - 1 - m0) * (uint32_t)K + (uint32_t)c16 * 8u) * 2u;
+    }
+    const char* xtile = reinterpret_cast<const char*>(x + (size_t)m0 * K);
     auto fill_x_slab = [&](int kt, int buf, int q_begin, int q_end) {
+        const char* base = xtile + (size_t)kt * 256;
 #pragma unroll
         for (int q = q_begin; q < q_end; ++q) {
-            const int row0 = 4 * (XQ * wave + q), row = row0 + (lane >> 4);
-            const int c16 = (lane & 15) ^ (row & 15);
-            const int tok = min(m0 + row, M - 1);
-            const uint16_t* g = x + (size_t)tok * K + (size_t)kt * 128 + c16 * 8;
-            __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)&sm.x[buf][row0][0], 16, 0, 0);
+            const int row0 = 4 * (XQ * wave + q);
+            __builtin_amdgcn_global_load_lds((gptr_t)(base + xoff[q]), (lptr_t)&sm.x[buf][row0][0], 16, 0, 0);
         }
     };
     // Packed weights of one 128-column step (3/4-bit codes) or of one 64-column half step (8-bit codes

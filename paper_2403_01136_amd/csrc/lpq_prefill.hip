@@ -197,15 +197,17 @@ void prefill_kernel(const PrefillArgs a)
 
     constexpr int SEGS = 4 * MTB;                    // segments per 128-column step
     constexpr int STRIDE = MTB / 4;                  // segments between two pieces of unpacking work
+    constexpr int FILL_SEGS = 4;                     // odd segments that carry the next slab's loads
     for (int kt = kt_begin; kt < kt_end; ++kt) {
         const int buf = kt & 1;
         // Loads for the next step go out first and land while this step is multiplied.  Past the last
         // step they re-read it (no branches in the loop); what is built from them is never multiplied.
         const int ktn = min(kt + 1, kt_end - 1);
         if constexpr (!HALF_LOADS) load_w(ws[1], ktn, 0);
-        // the next slab's 16 loads go out two at a time between the matrix instructions of the first half
-        // step's odd segments (the even ones carry the unpacking): issued in a block up front they would
-        // hold back the step's first matrix instruction by as many issue slots
+        // the next slab's 16 loads go out four at a time between the matrix instructions of the step's first
+        // four odd segments (the even ones carry the unpacking): issued in a block up front they hold back
+        // the step's first matrix instruction by as many issue slots, spread over more segments the last of
+        // them land late (measured: 2, 4, 8 segments -> 4 is best)
         h8 xa[2][2];                                 // activations are read one segment ahead
         x_operands(buf, 0, 0, xa[0]);
 #pragma unroll
@@ -233,7 +235,7 @@ void prefill_kernel(const PrefillArgs a)
                     if (seg == 3 * STRIDE) unpack_tile(src, 1, 1 - half, 1 - half);
                     if (seg == 4 * STRIDE) unpack_tile(src, 3, 1 - half, 1 - half);
                     if (seg == 5 * STRIDE) pair_tiles(1, 1 - half);
-                    if (half == 0 && (seg & 1)) fill_x_slab(ktn, buf ^ 1, (XQ / (MTB)) * (seg >> 1), (XQ / (MTB)) * ((seg >> 1) + 1));
+                    if (half == 0 && (seg & 1) && seg < 2 * FILL_SEGS) fill_x_slab(ktn, buf ^ 1, (XQ / FILL_SEGS) * (seg >> 1), (XQ / FILL_SEGS) * ((seg >> 1) + 1));
                     __builtin_amdgcn_sched_barrier(0);
                 }
         }

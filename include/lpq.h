@@ -16,7 +16,9 @@
  *     the argument is a descriptor struct, which is read on the HOST during the call.
  *   - The library allocates nothing the caller sees.  The caller owns every buffer and keeps
  *     it alive until the work enqueued on `hip_stream` has completed.  Split-K partial sums
- *     live in an internal per-device workspace that grows on demand.
+ *     live in an internal per-device workspace that grows on demand; every call on a device shares
+ *     it, so calls that compute (linears, attention, the indicator) must not overlap on one device:
+ *     enqueue them on one stream, or order the streams with events.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     enqueue work and return without synchronising.
  *   - Calls record only kernel launches (and, for the loader, copies) on `hip_stream`, so they can be

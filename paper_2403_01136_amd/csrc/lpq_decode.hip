@@ -32,9 +32,9 @@ namespace {
 // 3-4 KB per wave for 3/4-bit codes and 8 KB for 8-bit codes and fp16 rows, so 12-16 KB either way).
 template <int V> struct DecodeCfg { enum { RT = (V == V_F16) ? 2 : 4, DEPTH = (V == V_W3 || V == V_W4) ? 4 : 2 }; };
 
-// A launch is specialised on TOK, the token rows it covers: 16 (M <= 16: 16x16x32 MFMA) or 32 or 64
-// (32x32x16 MFMA at twice the matrix-core rate).  For 16 and 32 rows scale and zero are applied after
-// the matrix cores; for 64 the weights are dequantised to fp16 in registers.  Activation staging: CHUNK 128-column steps per LDS
+// A launch is specialised on TOK, the token rows it covers: 16 or 32 (one or two 16-token tiles on the
+// 16x16x32 MFMA, scale and zero applied after the matrix cores) or 64 (32x32x16 MFMA at twice the
+// matrix-core rate, weights dequantised to fp16 in registers).  Activation staging: CHUNK 128-column steps per LDS
 // buffer, sized so that two buffers of every workgroup resident on a CU fill 128 KB of its LDS.
 template <int TOK, int WAVES> struct PipeCfg {
     enum { FIT = 32 * WAVES / TOK, CHUNK = FIT < 8 ? FIT : 8 };
@@ -45,11 +45,7 @@ template <int TOK, int WAVES> struct PipeCfg {
 // Token row `row` keeps the 16-byte column group c16 of each of its 128-column steps in slot
 // c16 ^ (row % 16) of that step: rows are a multiple of 256 bytes apart, and the swizzle makes the
 // 16-byte operand reads of 16 consecutive rows hit 16 different bank groups.
-// xs (32-token launches): the sum of each token row over each 128-column step of the staged chunk.
-template <int TOK, int WAVES> struct DecodeSmem {
-    uint16_t x[2][TOK][PipeCfg<TOK, WAVES>::ROW_HALVES];
-    float xs[2][TOK == 32 ? (int)PipeCfg<TOK, WAVES>::CHUNK : 1][TOK == 32 ? TOK : 4];
-};
+template <int TOK, int WAVES> struct DecodeSmem { uint16_t x[2][TOK][PipeCfg<TOK, WAVES>::ROW_HALVES]; };
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -78,11 +74,11 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
 {
     constexpr int RT = DecodeCfg<V>::RT;
     constexpr int SCHEME = VInfo<V>::SCHEME;
-    constexpr bool WIDE = TOK > 16;                 // 32x32x16 path
-    constexpr int MT = 1;                           // narrow path: one 16-token tile
+    constexpr bool WIDE = TOK > 32;                 // 32x32x16 path
+    constexpr int MT = WIDE ? 1 : TOK / 16;         // narrow path: 16-token tiles
     constexpr int NP = RT / 2, MT2 = WIDE ? TOK / 32 : 1;      // wide path: tile pairs and 32-token tiles
     constexpr int CHUNK = PipeCfg<TOK, WAVES>::CHUNK, XQ = PipeCfg<TOK, WAVES>::XQ;
-    // 32-token launches keep two steps in flight per wave: their second set of accumulators needs the registers
+    // 32-token launches keep two steps in flight per wave: their second token tile needs the registers
     constexpr int WANT = TOK == 32 ? 2 : (int)DecodeCfg<V>::DEPTH;
     constexpr int STAGES = WANT < CHUNK ? WANT : CHUNK;
     // vector-memory loads of one Stage: the tiles (one load per KB, the 768-byte 3-bit tile included) and scale + zero
@@ -113,7 +109,6 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     f4 acc[RT][MT];                   // narrow path
     f4 xsum[MT];                      // narrow path, per-row scheme only: sum of x over the unit's K range
     f16x accw[NP][MT2];               // wide path: [tile pair][32-token tile]
-    f16x xsumw[MT2];                  // wide path, per-row scheme only: sum of x over the unit's K range
     auto clear_acc = [&]() {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -122,13 +117,11 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             for (int t = 0; t < RT; ++t) acc[t][mt] = f4{0, 0, 0, 0};
         }
 #pragma unroll
-        for (int m2 = 0; m2 < MT2; ++m2)
+        for (int p = 0; p < NP; ++p)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                xsumw[m2][v] = 0.0f;
+            for (int m2 = 0; m2 < MT2; ++m2)
 #pragma unroll
-                for (int p = 0; p < NP; ++p) accw[p][m2][v] = 0.0f;
-            }
+                for (int v = 0; v < 16; ++v) accw[p][m2][v] = 0.0f;
     };
     clear_acc();
 
@@ -155,88 +148,17 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     };
     // Two ways to fold scale and zero in.  POST (up to 32 tokens): multiply raw codes (as fp16
     // subnormals, code * 2^-24) on the matrix cores per 128-column group, then acc += scale *
-    // (codes . x) + zero * sum(x) in fp32 -- unpacking a code is then a shift and a mask, and the fold
-    // costs two fp32 FMAs per accumulator register instead of the int -> fp16 conversions and packed
-    // FMAs per weight.  sum(x) comes from one extra MFMA against a block of ones (16 tokens) or from
-    // the per-chunk table in LDS (32 tokens).  Otherwise (64 tokens, where the fp32 work and the second
-    // set of accumulators outgrow the saving): dequantise each weight to fp16 once, w~ = scale * code + zero.
+    // (codes . x) + zero * sum(x) in fp32, with sum(x) from one extra MFMA against a block of ones
+    // -- unpacking a code is then a shift and a mask, and the fold costs 8 fp32 FMAs per tile and
+    // token tile instead of the int -> fp16 conversions and packed FMAs per weight.  Otherwise (64
+    // tokens, where the fp32 work has outgrown the saving): dequantise each weight to fp16 once,
+    // w~ = scale * code + zero.
     constexpr bool POST = TOK <= 32 && V != V_F16;
     // MFMA A operand: 8 consecutive columns (16-byte group c16 of 128-column step `step`) of a token row
     auto x_operand = [&](int buf, int row, int step, int c16) {
         return *reinterpret_cast<const h8*>(&sm.x[buf][row][step * 128 + 8 * (c16 ^ (row & 15))]);
     };
     auto compute = [&](Stage& b, int buf, int step) {
-        if constexpr (WIDE && POST) {
-            // raw codes, tiles (p, p + NP) paired into 32-row operands (wj[.][p] then holds k slots kq 0
-            // and 2, wj[.][p + NP] slots kq 1 and 3); the products of the step's 128 columns gather in d,
-            // or straight in the accumulators for the per-row scheme.
-            // In-order issue: vector work in front of a run of matrix instructions is not hidden by
-            // them, vector work between them is.  So the codes of MFMA step j + 1 are unpacked and
-            // paired in the same scheduling group as the matrix instructions of step j.
-            const int arow = lane & 31, ahalf = lane >> 5;
-            f16x d[NP][MT2];
-            h8 wj[2][RT];
-            auto unpack_pair = [&](int j) {
-#pragma unroll
-                for (int t = 0; t < RT; ++t) wj[j & 1][t] = unpack_subnormal_step<V>(b.w[t], j);
-#pragma unroll
-                for (int p = 0; p < NP; ++p) pair_tiles_for_mfma32(wj[j & 1][p], wj[j & 1][p + NP]);
-            };
-            unpack_pair(0);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                h8 a0[MT2], a1[MT2];
-#pragma unroll
-                for (int m2 = 0; m2 < MT2; ++m2) {
-                    a0[m2] = x_operand(buf, 32 * m2 + arow, step, 4 * j + 2 * ahalf);
-                    a1[m2] = x_operand(buf, 32 * m2 + arow, step, 4 * j + 2 * ahalf + 1);
-                }
-                if (j < 3) unpack_pair(j + 1);
-#pragma unroll
-                for (int m2 = 0; m2 < MT2; ++m2)
-#pragma unroll
-                    for (int p = 0; p < NP; ++p) {
-                        if constexpr (SCHEME == SCH_ASYM) {
-                            if (j == 0) {
-#pragma unroll
-                                for (int v = 0; v < 16; ++v) d[p][m2][v] = 0.0f;
-                            }
-                            d[p][m2] = mfma32(a0[m2], wj[j & 1][p], d[p][m2]);
-                            d[p][m2] = mfma32(a1[m2], wj[j & 1][p + NP], d[p][m2]);
-                        } else {
-                            accw[p][m2] = mfma32(a0[m2], wj[j & 1][p], accw[p][m2]);
-                            accw[p][m2] = mfma32(a1[m2], wj[j & 1][p + NP], accw[p][m2]);
-                        }
-                    }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            // the lane's 16 tokens of a 32-token tile: 8 * g + 4 * ahalf + (0..3), g = 0..3
-#pragma unroll
-            for (int m2 = 0; m2 < MT2; ++m2) {
-                f4 xs[4];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) xs[g] = *reinterpret_cast<const f4*>(&sm.xs[buf][step][32 * m2 + 8 * g + 4 * ahalf]);
-                if constexpr (SCHEME == SCH_ASYM) {
-#pragma unroll
-                    for (int p = 0; p < NP; ++p) {
-                        // the lane's row of pair p lies in tile p (lanes 0-15 of each half) or p + NP (lanes 16-31)
-                        const bool upper = (lane & 16) != 0;
-                        const uint32_t sp = upper ? b.s[1] : b.s[0], zp = upper ? b.z[1] : b.z[0];
-                        const uint16_t sh = (uint16_t)((p & 1) ? (sp >> 16) : (sp & 0xffffu));
-                        const uint16_t zh = (uint16_t)((p & 1) ? (zp >> 16) : (zp & 0xffffu));
-                        const float sf = (float)__builtin_bit_cast(_Float16, sh) * 16777216.0f;     // scale * 2^24
-                        const float zf = (float)__builtin_bit_cast(_Float16, zh);
-#pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            accw[p][m2][v] = __builtin_fmaf(sf, d[p][m2][v], __builtin_fmaf(zf, xs[v >> 2][v & 3], accw[p][m2][v]));
-                    }
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) xsumw[m2][v] += xs[v >> 2][v & 3];
-                }
-            }
-            return;
-        }
         if constexpr (WIDE) {
             // dequantise two MFMA steps of every tile at a time, pair tiles (p, p + NP) into 32-row
             // operands (wb[p] then holds k slots kq 0 and 2, wb[p + NP] slots kq 1 and 3), multiply
@@ -283,26 +205,36 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             const _Float16 one = (_Float16)1.0f;
             const h8 ones = {one, one, one, one, one, one, one, one};
             const f4 zero4 = {0, 0, 0, 0};
-            f4 d[RT], xs;
+            f4 d[RT][MT], xs[MT];
 #pragma unroll
             for (int t = 0; t < RT; ++t) wj[0][t] = unpack_subnormal_step<V>(b.w[t], 0);
+            h8 a[2][MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) a[0][mt] = x_operand(buf, 16 * mt + r, step, kq);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const h8 a = x_operand(buf, r, step, 4 * j + kq);
+                // one scheduling group per tile: its matrix instruction(s) of step j and the unpacking of the same
+                // tile for step j + 1, so that the vector work sits between matrix instructions, not in front of them
                 if (j < 3) {
 #pragma unroll
-                    for (int t = 0; t < RT; ++t) wj[(j + 1) & 1][t] = unpack_subnormal_step<V>(b.w[t], j + 1);
+                    for (int mt = 0; mt < MT; ++mt) a[(j + 1) & 1][mt] = x_operand(buf, 16 * mt + r, step, 4 * (j + 1) + kq);
                 }
-                if constexpr (SCHEME == SCH_ASYM) {
-                    xs = mfma16(a, ones, j == 0 ? zero4 : xs);
 #pragma unroll
-                    for (int t = 0; t < RT; ++t) d[t] = mfma16(a, wj[j & 1][t], j == 0 ? zero4 : d[t]);
-                } else {   // per-row scheme: one scale per row, applied in the epilogue
-                    xsum[0] = mfma16(a, ones, xsum[0]);
-#pragma unroll
-                    for (int t = 0; t < RT; ++t) acc[t][0] = mfma16(a, wj[j & 1][t], acc[t][0]);
+                for (int mt = 0; mt < MT; ++mt) {
+                    if constexpr (SCHEME == SCH_ASYM) xs[mt] = mfma16(a[j & 1][mt], ones, j == 0 ? zero4 : xs[mt]);
+                    else                               xsum[mt] = mfma16(a[j & 1][mt], ones, xsum[mt]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    if (j < 3) wj[(j + 1) & 1][t] = unpack_subnormal_step<V>(b.w[t], j + 1);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        if constexpr (SCHEME == SCH_ASYM) d[t][mt] = mfma16(a[j & 1][mt], wj[j & 1][t], j == 0 ? zero4 : d[t][mt]);
+                        else                               acc[t][mt] = mfma16(a[j & 1][mt], wj[j & 1][t], acc[t][mt]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             if constexpr (SCHEME == SCH_ASYM) {
 #pragma unroll
@@ -313,8 +245,10 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                     const float sf = (float)__builtin_bit_cast(_Float16, sh) * 16777216.0f;     // scale * 2^24
                     const float zf = (float)__builtin_bit_cast(_Float16, zh);
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        acc[t][0][v] = __builtin_fmaf(sf, d[t][v], __builtin_fmaf(zf, xs[v], acc[t][0][v]));
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            acc[t][mt][v] = __builtin_fmaf(sf, d[t][mt][v], __builtin_fmaf(zf, xs[mt][v], acc[t][mt][v]));
                 }
             }
         } else {
@@ -358,25 +292,6 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         asm volatile("" ::: "memory");      // weight loads issued later stay later: vmcnt counts in issue order
     };
 
-    // ---- 32-token launches: sum of every (token row, 128-column step) of a published chunk.
-    // Two threads per sum, eight 16-byte groups each (which eight does not matter, and starting at a
-    // group that varies with the sum spreads neighbouring lanes over the LDS banks).
-    auto sum_x_chunk = [&](int buf) {
-        if constexpr (WIDE && POST) {
-            static_assert(TOK * CHUNK * 2 == 64 * WAVES, "two threads per sum");
-            const int q = tid >> 1, hs = tid & 1, row = q / CHUNK, step = q % CHUNK;
-            float acc_s = 0.0f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const h8 v = *reinterpret_cast<const h8*>(&sm.x[buf][row][step * 128 + 8 * (8 * hs + ((i + q) & 7))]);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc_s += (float)v[e];
-            }
-            acc_s += __shfl_xor(acc_s, 1);
-            if (hs == 0) sm.xs[buf][step][row] = acc_s;
-        }
-    };
-
     // ---- end of a unit: lane holds tokens 4*kq + v of RT consecutive rows starting at nbase
     auto finish_unit = [&](int sb, float* __restrict__ partial) {
         const long rb = row_block(sb);
@@ -409,9 +324,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                         if (L.residual) res = *reinterpret_cast<const hv*>(L.residual + (size_t)tok * L.N + nbase);
 #pragma unroll
                         for (int p = 0; p < NP; ++p) {
-                            float a = accw[p][m2][v];
-                            if constexpr (POST && SCHEME == SCH_SYM) a = a * 16777216.0f - 128.0f * xsumw[m2][v];   // undo 2^-24 and the +128 offset
-                            float val = apply_activation(a * post[p] + bias[p], L.act);
+                            float val = apply_activation(accw[p][m2][v] * post[p] + bias[p], L.act);
                             if (L.residual) val += (float)res[p];
                             o[p] = (_Float16)val;
                         }
@@ -420,11 +333,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                         typedef float fv __attribute__((ext_vector_type(NP)));
                         fv o;
 #pragma unroll
-                        for (int p = 0; p < NP; ++p) {
-                            float a = accw[p][m2][v];
-                            if constexpr (POST && SCHEME == SCH_SYM) a = a * 16777216.0f - 128.0f * xsumw[m2][v];
-                            o[p] = a * post[p];
-                        }
+                        for (int p = 0; p < NP; ++p) o[p] = accw[p][m2][v] * post[p];
                         *reinterpret_cast<fv*>(partial + (size_t)(tok - m0) * (WAVES * 64) + (nbase - (long)sb * (WAVES * 16 * RT))) = o;
                     }
                 }
@@ -483,10 +392,6 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         if (i < cur.n) issue(st[i], cur.sb, cur.kt0 + i);      // slots past a short chunk stay empty
     wait_vmem_all_but<0>();
     __syncthreads();
-    if constexpr (WIDE && POST) {
-        sum_x_chunk(0);
-        __syncthreads();
-    }
     int buf = 0;
     while (cur.n > 0) {
         if (nxt.n > 0) fill_x_chunk(nxt, buf ^ 1);
@@ -522,12 +427,6 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         }
         __syncthreads();
         buf ^= 1;
-        if constexpr (WIDE && POST) {       // the next chunk's activations are now visible to every wave
-            if (nxt.n > 0) {
-                sum_x_chunk(buf);
-                __syncthreads();
-            }
-        }
         cur = nxt;
         nxt = next_chunk(nxt);
     }

@@ -673,20 +673,18 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
             for (int t = 0; t < RT; ++t) wj[0][t] = unpack_subnormal_step<V>(b.w[t], 0);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (j < 3) {
-#pragma unroll
-                    for (int t = 0; t < RT; ++t) wj[(j + 1) & 1][t] = unpack_subnormal_step<V>(b.w[t], j + 1);
-                }
-                if constexpr (SCHEME == SCH_ASYM) {
-                    xs = mfma16(b.a[j], ones, j == 0 ? zero4 : xs);
-#pragma unroll
-                    for (int t = 0; t < RT; ++t) d[t] = mfma16(b.a[j], wj[j & 1][t], j == 0 ? zero4 : d[t]);
-                } else {
-                    xsum = mfma16(b.a[j], ones, xsum);
-#pragma unroll
-                    for (int t = 0; t < RT; ++t) acc[t] = mfma16(b.a[j], wj[j & 1][t], acc[t]);
-                }
+                // one scheduling group per tile: its matrix instruction of step j and the unpacking of the same tile
+                // for step j + 1, so that the vector work sits between matrix instructions, not in front of them
+                if constexpr (SCHEME == SCH_ASYM) xs = mfma16(b.a[j], ones, j == 0 ? zero4 : xs);
+                else                               xsum = mfma16(b.a[j], ones, xsum);
                 __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    if (j < 3) wj[(j + 1) & 1][t] = unpack_subnormal_step<V>(b.w[t], j + 1);
+                    if constexpr (SCHEME == SCH_ASYM) d[t] = mfma16(b.a[j], wj[j & 1][t], j == 0 ? zero4 : d[t]);
+                    else                               acc[t] = mfma16(b.a[j], wj[j & 1][t], acc[t]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             if constexpr (SCHEME == SCH_ASYM) {
 #pragma unroll

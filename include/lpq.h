@@ -68,7 +68,7 @@ typedef enum {
     LPQ_ERR_SCHEME = 3,      /* unknown scheme, or bits / scheme / group_size do not match   */
     LPQ_ERR_SHAPE = 4,       /* K % 128, N % 64, K, N, M or n_layers out of range; bad plan  */
     LPQ_ERR_ALIGN = 5,       /* a data pointer is not 16-byte aligned                        */
-    LPQ_ERR_BUFSIZE = 6,     /* internal workspace could not be grown                        */
+    LPQ_ERR_BUFSIZE = 6,     /* a caller's buffer is too small, or workspace could not grow  */
     LPQ_ERR_DEVICE = 7,      /* a HIP call failed                                            */
     LPQ_ERR_UNSUPPORTED = 8  /* valid request the library does not implement                 */
 } lpq_status;

@@ -126,9 +126,9 @@ lpq_status decode_block_count(int waves, int* out)
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return LPQ_ERR_DEVICE;
         cus[dev] = n;
     }
-    static const int per_cu_x4 = std::max(1, env_int("LPQ_DECODE_BLOCKS_PER_CU_X4", 0));   // quarter workgroups per CU
+    static const int per_cu_x4 = env_int("LPQ_DECODE_BLOCKS_PER_CU_X4", 0);   // quarter workgroups per CU, 0 = what the chip holds
     const int resident = cus[dev] * (8 / waves);           // two waves per SIMD
-    *out = env_int("LPQ_DECODE_BLOCKS_PER_CU_X4", 0) > 0 ? std::max(1, cus[dev] * per_cu_x4 / 4) : resident;
+    *out = per_cu_x4 > 0 ? std::max(1, cus[dev] * per_cu_x4 / 4) : resident;
     return LPQ_OK;
 }
 
@@ -276,8 +276,6 @@ int prefill_token_groups(int m_blocks, int n_blocks)
     return best;
 }
 
-// Prefill-phase dispatch of a list of independent linears: one grouped launch per storage variant
-// (and per MAX_PREFILL_LIN linears), tiles of the longest-K linears first.
 // Compute units of the current device (cached).
 lpq_status device_cus(int* out)
 {
@@ -321,6 +319,8 @@ int prefill_k_splits(int tiles, int KT, int32_t M, int32_t N, int cus)
     return best;
 }
 
+// Prefill-phase dispatch of a list of independent linears: one grouped launch per storage variant
+// (and per MAX_PREFILL_LIN linears), tiles of the longest-K linears first.
 lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream)
 {
     int cus = 0;
@@ -642,7 +642,7 @@ const char* lpq_status_str(lpq_status status)
     case LPQ_ERR_SCHEME: return "bits / scheme / group_size do not match";
     case LPQ_ERR_SHAPE: return "bad shape or size (K % 128, N % 64, M >= 1, descriptor mismatch, malformed plan or samples)";
     case LPQ_ERR_ALIGN: return "pointer not 16-byte aligned";
-    case LPQ_ERR_BUFSIZE: return "workspace allocation failed";
+    case LPQ_ERR_BUFSIZE: return "buffer too small, or workspace allocation failed";
     case LPQ_ERR_DEVICE: return "HIP call failed";
     case LPQ_ERR_UNSUPPORTED: return "unsupported request";
     }

@@ -104,6 +104,23 @@ int env_int(const char* name, int fallback)
     return (e && *e) ? std::atoi(e) : fallback;
 }
 
+// Compute units of the current device (cached).
+lpq_status device_cus(int* out)
+{
+    static std::mutex mu;
+    static int cus[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return LPQ_ERR_DEVICE;
+        cus[dev] = n;
+    }
+    *out = cus[dev];
+    return LPQ_OK;
+}
+
 // Wavefronts per decode workgroup: 4 for up to 16 token rows; 8 beyond, where the activation slab
 // is several times larger and one workgroup per CU shares it among twice the weight rows.  The
 // workgroups per launch are what the chip holds at once.  Both can be overridden for experiments.
@@ -116,19 +133,12 @@ int decode_waves(int M)
 
 lpq_status decode_block_count(int waves, int* out)
 {
-    static std::mutex mu;
-    static int cus[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
-    std::lock_guard<std::mutex> lock(mu);
-    if (cus[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return LPQ_ERR_DEVICE;
-        cus[dev] = n;
-    }
+    int cus = 0;
+    lpq_status st = device_cus(&cus);
+    if (st != LPQ_OK) return st;
     static const int per_cu_x4 = env_int("LPQ_DECODE_BLOCKS_PER_CU_X4", 0);   // quarter workgroups per CU, 0 = what the chip holds
-    const int resident = cus[dev] * (8 / waves);           // two waves per SIMD
-    *out = per_cu_x4 > 0 ? std::max(1, cus[dev] * per_cu_x4 / 4) : resident;
+    const int resident = cus * (8 / waves);                 // two waves per SIMD
+    *out = per_cu_x4 > 0 ? std::max(1, cus * per_cu_x4 / 4) : resident;
     return LPQ_OK;
 }
 
@@ -140,6 +150,38 @@ uint32_t variant_cost_x16(int variant)
     static const int c[5] = {env_int("LPQ_COST_W3", 26), env_int("LPQ_COST_W4", 21), env_int("LPQ_COST_W8", 17),
                              env_int("LPQ_COST_I8", 17), env_int("LPQ_COST_F16", 16)};
     return (uint32_t)std::max(1, c[variant]);
+}
+
+// Workgroup shape of a single linear in the small-launch decode kernel: 16-row tiles per workgroup (T) and K
+// splits (s).  Measured on MI355X (OPT-13B, 7B- and 70B-class shapes, 3- and 4-bit): a launch runs fastest
+// when its workgroups just fit the compute units once -- a unit that gets two takes 2.6 times as long, not
+// twice -- and a workgroup's time grows with its steps times (the activations it reads per step, from L2,
+// plus T tiles of weights).  T = 3 and 5 cut a 64-row block across workgroups (e.g. 1280 tiles = 256 x 5);
+// at T = 5 the kernel holds the whole register file and runs a third slower per byte.  A split costs a second
+// kernel.  The estimate below (microseconds) is only used to rank the choices.
+void rows_plan(const LinDesc& L, int cus, int* tiles, int* splits)
+{
+    static const double tile_us[5] = {0.024, 0.032, 0.064, 0.064, 0.128};     // per tile and step, by variant
+    const int KT = L.K / 128, n_tiles = L.N / 16;
+    double best = 1e30;
+    *tiles = 4;
+    *splits = 1;
+    static const int order[4] = {4, 2, 3, 5};                                // ties go to the earlier entry
+    for (int oi = 0; oi < 4; ++oi) {
+        const int T = order[oi];
+        if (L.variant == 4 && T > 2 && T != 4) continue;                     // fp16 weights: one or two tiles (4 stands for 2)
+        const int rt = (L.variant == 4 && T > 2) ? 2 : T;
+        if (n_tiles % rt != 0) continue;
+        const double step_us = 0.06 + rt * tile_us[L.variant] + (rt == 5 ? 0.09 : 0.0);
+        for (int s = 1; s <= 8; ++s) {
+            const long wgs = (long)(n_tiles / rt) * s;
+            // a split is there to fill the chip, not to add rounds; a wave wants several steps per stage of its ring
+            if (s > 1 && (KT / s < 16 || wgs > cus)) break;
+            const long rounds = (wgs + cus - 1) / cus;
+            const double est = (rounds == 1 ? 1.0 : 1.3 * rounds) * ((KT + s - 1) / s) * step_us + (s > 1 ? 5.0 : 0.0);
+            if (est < best * 0.98) best = est, *tiles = T, *splits = s;
+        }
+    }
 }
 
 struct LinearCall {
@@ -175,6 +217,8 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         a.waves = waves;
         a.n_blocks = n_blocks;
         a.slot_floats = slot_floats;
+        a.row_tiles = 4;
+        a.pad = 0;
         a.partial = ws;
         uint64_t total = 0;
         for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c) {
@@ -212,17 +256,27 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         if (M <= 16 && stream_bytes <= rows_max_bytes) {
             // longest K first: the last workgroups to start are then the shortest
             std::stable_sort(a.lin, a.lin + a.n_lin, [](const LinDesc& x, const LinDesc& y) { return x.K > y.K; });
+            int cus = 0;
+            st = device_cus(&cus);
+            if (st != LPQ_OK) return st;
+            int tiles = 4, splits1 = 0;
+            if (a.n_lin == 1) rows_plan(a.lin[0], cus, &tiles, &splits1);
+            const int forced = env_int("LPQ_DECODE_ROWS_TILES", 0);    // for tests: read at every call
+            if (forced >= 2 && forced <= 5 && forced != tiles) tiles = forced, splits1 = 0;
+            auto group_tiles = [&](const LinDesc& L) { return (L.variant == 4 && tiles > 2) ? 2 : tiles; };
+            for (int i = 0; i < a.n_lin; ++i)
+                if ((a.lin[i].N / 16) % group_tiles(a.lin[i]) != 0) tiles = 4, splits1 = 0;    // groups must tile every linear exactly
             int64_t blocks = 0, row_blocks = 0;
-            for (int i = 0; i < a.n_lin; ++i) row_blocks += a.lin[i].N / (a.lin[i].variant == 4 ? 32 : 64);
+            for (int i = 0; i < a.n_lin; ++i) row_blocks += a.lin[i].N / 16 / group_tiles(a.lin[i]);
             int64_t partial_floats = 0;
             for (int i = 0; i < a.n_lin; ++i) {
                 LinDesc& L = a.lin[i];
-                L.row_blocks = L.N / (L.variant == 4 ? 32 : 64);
-                // K splits (L.pad): only for a launch that leaves most compute units without a workgroup, and only
-                // down to 32 steps per workgroup (a wave wants several steps to keep its ring of loads busy)
+                L.row_blocks = L.N / 16 / group_tiles(L);
+                // K splits (L.pad) of a launch of several linears: only if it leaves most compute units without a
+                // workgroup, and only down to 32 steps per workgroup
                 const int KT = L.K / 128;
                 const int want = (int)std::max<int64_t>(1, 320 / std::max<int64_t>(1, row_blocks));
-                L.pad = std::max(1, std::min(std::min(want, KT / 32), 8));
+                L.pad = splits1 > 0 ? splits1 : std::max(1, std::min(std::min(want, KT / 32), 8));
                 L.step_weight = (uint32_t)partial_floats;             // float offset of this linear's partial sums
                 if (L.pad > 1) partial_floats += (int64_t)L.pad * 16 * L.N;
                 L.cum_weight = (uint64_t)blocks;
@@ -235,7 +289,8 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
                 a.partial = ws;
             }
             a.n_blocks = (int32_t)blocks;
-            a.waves = blocks <= 160 ? 8 : 4;         // few blocks: more waves per block keep the chip's memory pipes full
+            a.row_tiles = tiles;
+            a.waves = blocks <= 64 ? 8 : 4;          // very few blocks: more waves per block keep more loads in flight
             a.m0 = 0;
             if (launch_decode_rows(a, stream) != hipSuccess) return LPQ_ERR_DEVICE;
             continue;
@@ -274,23 +329,6 @@ int prefill_token_groups(int m_blocks, int n_blocks)
         if (imbalance < best_imbalance) { best = g; best_imbalance = imbalance; }
     }
     return best;
-}
-
-// Compute units of the current device (cached).
-lpq_status device_cus(int* out)
-{
-    static std::mutex mu;
-    static int cus[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
-    std::lock_guard<std::mutex> lock(mu);
-    if (cus[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return LPQ_ERR_DEVICE;
-        cus[dev] = n;
-    }
-    *out = cus[dev];
-    return LPQ_OK;
 }
 
 // K splits of one prefill linear that is launched with too few tiles to fill the chip (a single linear of a

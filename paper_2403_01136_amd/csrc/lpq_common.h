@@ -37,6 +37,7 @@ enum { MAX_LIN_PER_LAUNCH = 40 };   // keeps DecodeArgs under 4 KB of kernel arg
 struct DecodeArgs {
     int32_t n_lin, M, m0, waves;         // m0: first token row of this pass (M > 64 is run 64 rows at a time)
     int32_t n_blocks, slot_floats;       // slot_floats: floats per partial tile = 64 tokens x rows per workgroup
+    int32_t row_tiles, pad;              // small-launch kernel only: 16-row tiles per workgroup (2 .. 5; fp16 weights: at most 2)
     uint64_t total_weight;
     float* partial;
     LinDesc lin[MAX_LIN_PER_LAUNCH];
@@ -111,7 +112,7 @@ size_t tile_bytes_of(int variant);
 hipError_t launch_quantize_pack(const void* w_rows, const lpq_qdesc& d, long row0, long n_rows, const lpq_qweight& out, hipStream_t s);
 hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
-hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s);     // small launches, M <= 16: cum_weight = row blocks before
+hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s);     // small launches, M <= 16: cum_weight = workgroups before
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);      // both kernels, if any linear is K-split
 int prefill_tokens_per_tile(int variant);
 // variance indicator (lpq_indicator.hip)

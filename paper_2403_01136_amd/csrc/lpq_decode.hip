@@ -606,29 +606,35 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
 // ---- small launches (one linear of a decoder layer, up to 16 token rows) ---------------------------------
 // The even-share kernel above needs a launch with many steps to spread; a single linear has few, and cutting
 // its units into short ranges leaves each workgroup waiting on memory latency and pays a fix-up pass.  Here a
-// workgroup owns ONE 64-row block (32 rows for fp16 weights) over the whole of K, and its waves split K: wave w
-// takes the 128-column steps w, w + WAVES, ...  Each wave streams its tiles through a ring of stages in
-// registers together with the activations of those steps (read straight from global memory: they are small and
-// stay in L2; no LDS staging, no barrier in the loop), and the waves' accumulators are added through LDS at the
-// end, in wave order.  A linear with few row blocks and a long K (the second feed-forward matrix) is also split
-// over L.pad workgroups per row block, each taking a range of the steps and leaving fp32 sums in
-// partial[split][16][N] (at float offset L.step_weight of the launch's partial buffer) for a small second kernel;
-// otherwise there are no partial tiles and no second kernel.  a.lin[i].cum_weight holds the number of
-// workgroups of the linears before i, a.n_blocks their total.
-template <int V, int WAVES>
+// workgroup owns a group of TILES consecutive 16-row tiles of W (at most 2 for fp16 weights) over the whole of
+// K, and its waves split K: wave w takes the 128-column steps w, w + WAVES, ...  Four tiles are one 64-row
+// block of the packed layout; groups of 3 or 5 tiles cut across blocks, so that the host can pick the group
+// size whose workgroups just fill the compute units once (1280 tiles = 256 groups of 5).  Each wave streams its
+// tiles through a ring of stages in registers together with the activations of those steps (read straight from
+// global memory: they are small and stay in L2; no LDS staging, no barrier in the loop), and the waves'
+// accumulators are added through LDS at the end, in wave order.  A linear with few tiles and a long K (the
+// second feed-forward matrix) is also split over L.pad workgroups per group, each taking a range of the steps
+// and leaving fp32 sums in partial[split][16][N] (at float offset L.step_weight of the launch's partial buffer)
+// for a small second kernel; otherwise there are no partial tiles and no second kernel.  L.row_blocks is the
+// linear's number of groups, a.lin[i].cum_weight the number of workgroups of the linears before i, a.n_blocks
+// their total.
+template <int V, int WAVES, int TILES>
 __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int split, float* __restrict__ partial, float* __restrict__ red)
 {
-    constexpr int RT = (V == V_F16) ? 2 : 4;
+    constexpr int RT = (V == V_F16 && TILES > 2) ? 2 : TILES;      // 16-row tiles per workgroup; rb counts groups of RT tiles
+    constexpr bool ALIGNED = RT == 2 || RT == 4;                    // the group lies in one 64-row block
     constexpr int SCHEME = VInfo<V>::SCHEME;
     constexpr bool POST = V != V_F16;
     constexpr int STAGES = (V == V_W3 || V == V_W4) ? 4 : 3;
-    constexpr int LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) + (SCHEME == SCH_ASYM ? 2 : 0) + 4;
+    constexpr int LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) +
+                          (SCHEME == SCH_ASYM ? (ALIGNED ? 2 : 4) : 0) + 4;
     static_assert((STAGES - 1) * LOADS < 64, "vmcnt is a 6-bit counter");
     constexpr int NV = RT * 4 + (SCHEME == SCH_SYM ? 4 : 0);       // floats a lane hands to the reduction
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // a scalar: the row block and the tile addresses derive from it
     const int r = lane & 15, kq = lane >> 4;
     const int KT = L.K / 128;
+    const long g0 = rb * RT;                                        // first tile; tile g is tile g % 4 of 64-row block g / 4
     // the workgroup's steps [kt0, kt1): all of them, or the split's share (the first KT % splits take one more)
     const int splits = L.pad, share = KT / splits, extra = KT % splits;
     const int kt0 = split * share + min(split, extra), kt1 = kt0 + share + (split < extra ? 1 : 0);
@@ -637,7 +643,8 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
 
     struct Stage {
         WRaw<V> w[RT];
-        u32x2 s, z;
+        u32x2 s, z;                 // scales and zeros of rows 4 r .. 4 r + 3 of the first tile's block
+        u32x2 s1, z1;               // !ALIGNED: and of the next block (the group spans two)
         h8 a[4];
     };
     Stage st[STAGES];
@@ -646,14 +653,16 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
     auto issue = [&](Stage& b, int i) {
         const int kt = min(kt0 + wave + WAVES * i, KT - 1);
 #pragma unroll
-        for (int t = 0; t < RT; ++t) {
-            if constexpr (RT == 4) b.w[t] = load_tile<V>(L.codes, rb, KT, kt, t, lane);
-            else                   b.w[t] = load_tile<V>(L.codes, rb >> 1, KT, kt, 2 * (int)(rb & 1) + t, lane);
-        }
+        for (int t = 0; t < RT; ++t) b.w[t] = load_tile<V>(L.codes, (g0 + t) >> 2, KT, kt, (int)((g0 + t) & 3), lane);
         if constexpr (SCHEME == SCH_ASYM) {
-            const size_t idx = (size_t)kt * L.N + rb * 64 + 4 * r;
+            const size_t idx = (size_t)kt * L.N + (g0 >> 2) * 64 + 4 * r;
             b.s = *reinterpret_cast<const u32x2*>(L.scales + idx);
             b.z = *reinterpret_cast<const u32x2*>(L.zeros + idx);
+            if constexpr (!ALIGNED) {
+                const size_t idx1 = (size_t)kt * L.N + ((g0 + RT - 1) >> 2) * 64 + 4 * r;    // the last tile's block
+                b.s1 = *reinterpret_cast<const u32x2*>(L.scales + idx1);
+                b.z1 = *reinterpret_cast<const u32x2*>(L.zeros + idx1);
+            }
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) b.a[j] = *reinterpret_cast<const h8*>(xrow + (size_t)kt * 128 + 32 * j);
@@ -689,9 +698,14 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
             if constexpr (SCHEME == SCH_ASYM) {
 #pragma unroll
                 for (int t = 0; t < RT; ++t) {
-                    const uint32_t sp = b.s[t >> 1], zp = b.z[t >> 1];
-                    const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
-                    const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
+                    const int tt = (int)((g0 + t) & 3);             // the tile's place in its block: row 4 r + tt
+                    u32x2 s2 = b.s, z2 = b.z;
+                    if constexpr (!ALIGNED) {
+                        if (((g0 + t) >> 2) != (g0 >> 2)) s2 = b.s1, z2 = b.z1;     // uniform over the wave
+                    }
+                    const uint32_t sp = (tt >> 1) ? s2[1] : s2[0], zp = (tt >> 1) ? z2[1] : z2[0];
+                    const uint16_t sh = (uint16_t)((tt & 1) ? (sp >> 16) : (sp & 0xffffu));
+                    const uint16_t zh = (uint16_t)((tt & 1) ? (zp >> 16) : (zp & 0xffffu));
                     const float sf = (float)__builtin_bit_cast(_Float16, sh) * 16777216.0f;     // scale * 2^24
                     const float zf = (float)__builtin_bit_cast(_Float16, zh);
 #pragma unroll
@@ -739,7 +753,7 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
         float sum = 0.0f, xs = 0.0f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * NV + 4 * t + v) * 64 + ln];
-        const long row = (RT == 4) ? rb * 64 + 4 * rr + t : (rb >> 1) * 64 + 4 * rr + 2 * (rb & 1) + t;
+        const long row = ((g0 + t) >> 2) * 64 + 4 * rr + ((g0 + t) & 3);
         if constexpr (SCHEME == SCH_SYM) {
 #pragma unroll
             for (int w = 0; w < WAVES; ++w) xs += red[((size_t)w * NV + 4 * RT + v) * 64 + ln];
@@ -757,10 +771,10 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
     }
 }
 
-template <int WAVES>
+template <int WAVES, int TILES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_rows_kernel(const DecodeArgs a)
 {
-    __shared__ float red[WAVES * 20 * 64];
+    __shared__ float red[WAVES * (4 * TILES + 4) * 64];
     const int b = blockIdx.x;
     int li = 0, hi = a.n_lin - 1;                    // last linear whose first row block is <= b
     while (li < hi) {
@@ -773,11 +787,11 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_rows_kernel(cons
     const int split = (int)(wg / L.row_blocks);
     float* partial = a.partial + L.step_weight;
     switch (L.variant) {
-    case V_W3: run_rows<V_W3, WAVES>(L, a.M, rb, split, partial, red); break;
-    case V_W4: run_rows<V_W4, WAVES>(L, a.M, rb, split, partial, red); break;
-    case V_W8: run_rows<V_W8, WAVES>(L, a.M, rb, split, partial, red); break;
-    case V_I8: run_rows<V_I8, WAVES>(L, a.M, rb, split, partial, red); break;
-    default:   run_rows<V_F16, WAVES>(L, a.M, rb, split, partial, red); break;
+    case V_W3: run_rows<V_W3, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
+    case V_W4: run_rows<V_W4, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
+    case V_W8: run_rows<V_W8, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
+    case V_I8: run_rows<V_I8, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
+    default:   run_rows<V_F16, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
     }
 }
 
@@ -832,8 +846,17 @@ static hipError_t launch_waves(const DecodeArgs& a, hipStream_t s)
 
 hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s)
 {
-    if (a.waves == 8) decode_rows_kernel<8><<<(unsigned)a.n_blocks, 512, 0, s>>>(a);
-    else              decode_rows_kernel<4><<<(unsigned)a.n_blocks, 256, 0, s>>>(a);
+    const unsigned grid = (unsigned)a.n_blocks;
+#define LPQ_ROWS_CASE(T)                                                                      \
+    case T:                                                                                   \
+        if (a.waves == 8) decode_rows_kernel<8, T><<<grid, 512, 0, s>>>(a);                   \
+        else              decode_rows_kernel<4, T><<<grid, 256, 0, s>>>(a);                   \
+        break;
+    switch (a.row_tiles) {
+        LPQ_ROWS_CASE(2) LPQ_ROWS_CASE(3) LPQ_ROWS_CASE(4) LPQ_ROWS_CASE(5)
+    default: return hipErrorInvalidValue;
+    }
+#undef LPQ_ROWS_CASE
     hipError_t e = hipGetLastError();
     for (int li = 0; li < a.n_lin && e == hipSuccess; ++li) {
         if (a.lin[li].pad <= 1) continue;

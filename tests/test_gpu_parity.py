@@ -96,19 +96,23 @@ def test_load_quantize_pack_from_host(orc, bits, scheme, pinned):
 
 # ---- a3: decode linear ---------------------------------------------------------------------
 
-@pytest.fixture(params=["rows", "even_share"])
+@pytest.fixture(params=["rows", "rows_3", "rows_5", "even_share"])
 def decode_kernel_choice(request, monkeypatch):
-    """Up to 16 token rows, a launch that streams little goes to the kernel that gives each row block a workgroup,
-    a larger one to the even-share kernel; the limit is read at every call, so small shapes can reach both."""
+    """Up to 16 token rows, a launch that streams little goes to the kernel that gives a group of 16-row tiles a
+    workgroup, a larger one to the even-share kernel; the limit is read at every call, so small shapes can reach both.
+    rows_3 / rows_5 ask for groups of 3 / 5 tiles, which cut across the packed layout's 64-row blocks (the library
+    falls back to 4 where the group size does not divide a linear's tiles: N = 320 has 20, N = 192 has 12)."""
     if request.param == "even_share":
         monkeypatch.setenv("LPQ_DECODE_ROWS_MAX_MB", "0")
+    elif request.param != "rows":
+        monkeypatch.setenv("LPQ_DECODE_ROWS_TILES", request.param[-1])
     return request.param
 
 
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("M", [1, 2, 5, 16, 17, 33, 64])
 def test_decode_small(orc, bits, scheme, M, decode_kernel_choice):
-    if M > 16 and decode_kernel_choice == "rows":
+    if M > 16 and decode_kernel_choice != "even_share":
         pytest.skip("more than 16 token rows always take the even-share kernel")
     N, K = 320, 640         # 5 (fp16: 10) row blocks: the last workgroup has idle waves; 5 steps: idle waves in a row block's workgroup
     w = wl.weight_np(N, K, "dec", bits, scheme)
@@ -123,7 +127,7 @@ def test_decode_small(orc, bits, scheme, M, decode_kernel_choice):
 def test_decode_split_k_and_many_rows(orc, bits, scheme, M, decode_kernel_choice):
     """K long enough that the work is cut into several K ranges (fp32 partial sums + reduction, or waves that split
     K); M > 64 runs in several passes; a bias is added exactly once."""
-    if M > 16 and decode_kernel_choice == "rows":
+    if M > 16 and decode_kernel_choice != "even_share":
         pytest.skip("more than 16 token rows always take the even-share kernel")
     N, K = 192, 16384
     w = wl.weight_np(N, K, "decsk", bits, scheme)
@@ -173,6 +177,8 @@ def test_prefill_split_k(orc, bits, scheme, M, K):
 def test_activation_magnitude(orc, bits, scheme, mag, decode_kernel_choice):
     """The tolerance holds whatever the scale of the activations (tiny ones near the fp16 subnormal
     range, large ones short of overflow in the outputs): no step of the kernels may cost them bits."""
+    if decode_kernel_choice in ("rows_3", "rows_5"):
+        pytest.skip("N = 128 has 8 tiles: groups of 3 or 5 do not apply")
     N, K = 128, 512
     w = wl.weight_np(N, K, "mag", bits, scheme)
     for M, fn, tag in [(8, lpq.lpq_qlinear_decode, "decode"), (40, lpq.lpq_qlinear_decode, "decode"),
@@ -219,6 +225,8 @@ def _build_stage(cfg_key, h, f, qkv_n, layer_specs, M, outliers):
 @pytest.mark.parametrize("phase,M", [(lpq.LPQ_DECODE, 1), (lpq.LPQ_DECODE, 16), (lpq.LPQ_PREFILL, 128)],
                          ids=["decode_M1", "decode_M16", "prefill_M128"])
 def test_stage_mixed_bits_small(orc, phase, M, decode_kernel_choice):
+    if decode_kernel_choice in ("rows_3", "rows_5"):
+        pytest.skip("the stage's linears have 16, 48 and 64 tiles: no group of 3 or 5 fits them all")
     specs = [(16, 0), (8, 1), (4, 1), (3, 1), (8, 2), (3, 1)]
     stage, ys, host = _build_stage("stage_small", 256, 1024, 768, specs, M, True)
     lpq.lpq_stage_linears(stage, phase)

@@ -159,7 +159,7 @@ uint32_t variant_cost_x16(int variant)
 // plus T tiles of weights).  T = 3 and 5 cut a 64-row block across workgroups (e.g. 1280 tiles = 256 x 5);
 // at T = 5 the kernel holds the whole register file and runs a third slower per byte.  A split costs a second
 // kernel.  The estimate below (microseconds) is only used to rank the choices.
-void rows_plan(const LinDesc& L, int cus, int* tiles, int* splits)
+void rows_plan(const LinDesc& L, int tok_tiles, int cus, int* tiles, int* splits)
 {
     static const double tile_us[5] = {0.024, 0.032, 0.064, 0.064, 0.128};     // per tile and step, by variant
     const int KT = L.K / 128, n_tiles = L.N / 16;
@@ -172,7 +172,7 @@ void rows_plan(const LinDesc& L, int cus, int* tiles, int* splits)
         if (L.variant == 4 && T > 2 && T != 4) continue;                     // fp16 weights: one or two tiles (4 stands for 2)
         const int rt = (L.variant == 4 && T > 2) ? 2 : T;
         if (n_tiles % rt != 0) continue;
-        const double step_us = 0.06 + rt * tile_us[L.variant] + (rt == 5 ? 0.09 : 0.0);
+        const double step_us = 0.06 * tok_tiles + rt * tile_us[L.variant] + (rt == 5 ? 0.09 : 0.0);
         for (int s = 1; s <= 8; ++s) {
             const long wgs = (long)(n_tiles / rt) * s;
             // a split is there to fill the chip, not to add rounds; a wave wants several steps per stage of its ring
@@ -247,20 +247,22 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         if (total >= ((uint64_t)1 << 50)) return LPQ_ERR_UNSUPPORTED;
         a.total_weight = total;
         // A launch that streams little (a single linear of a decoder layer) has too few steps to spread evenly:
-        // it goes to the kernel that gives every 64-row block a workgroup whose waves split K (no fix-up pass).
+        // up to 32 token rows it goes to the kernel that gives every group of 16-row tiles a workgroup whose
+        // waves split K (no fix-up pass).
         // (read at every call, so that tests can send small shapes through either kernel)
         const int64_t rows_max_bytes = (int64_t)env_int("LPQ_DECODE_ROWS_MAX_MB", 192) << 20;
         int64_t stream_bytes = 0;
         for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c)
             stream_bytes += (int64_t)calls[c].w->d.K * calls[c].w->d.N * calls[c].w->d.bits / 8;
-        if (M <= 16 && stream_bytes <= rows_max_bytes) {
+        if (M <= 32 && stream_bytes <= rows_max_bytes) {
+            const int tok_tiles = M <= 16 ? 1 : 2;
             // longest K first: the last workgroups to start are then the shortest
             std::stable_sort(a.lin, a.lin + a.n_lin, [](const LinDesc& x, const LinDesc& y) { return x.K > y.K; });
             int cus = 0;
             st = device_cus(&cus);
             if (st != LPQ_OK) return st;
             int tiles = 4, splits1 = 0;
-            if (a.n_lin == 1) rows_plan(a.lin[0], cus, &tiles, &splits1);
+            if (a.n_lin == 1) rows_plan(a.lin[0], tok_tiles, cus, &tiles, &splits1);
             const int forced = env_int("LPQ_DECODE_ROWS_TILES", 0);    // for tests: read at every call
             if (forced >= 2 && forced <= 5 && forced != tiles) tiles = forced, splits1 = 0;
             auto group_tiles = [&](const LinDesc& L) { return (L.variant == 4 && tiles > 2) ? 2 : tiles; };
@@ -278,7 +280,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
                 const int want = (int)std::max<int64_t>(1, 320 / std::max<int64_t>(1, row_blocks));
                 L.pad = splits1 > 0 ? splits1 : std::max(1, std::min(std::min(want, KT / 32), 8));
                 L.step_weight = (uint32_t)partial_floats;             // float offset of this linear's partial sums
-                if (L.pad > 1) partial_floats += (int64_t)L.pad * 16 * L.N;
+                if (L.pad > 1) partial_floats += (int64_t)L.pad * 16 * tok_tiles * L.N;
                 L.cum_weight = (uint64_t)blocks;
                 blocks += (int64_t)L.row_blocks * L.pad;
             }
@@ -290,14 +292,16 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
             }
             a.n_blocks = (int32_t)blocks;
             a.row_tiles = tiles;
-            a.waves = blocks <= 64 ? 8 : 4;          // very few blocks: more waves per block keep more loads in flight
+            a.waves = (blocks <= 64 && tok_tiles == 1) ? 8 : 4;      // very few blocks: more waves per block keep more loads in flight
             a.m0 = 0;
             if (launch_decode_rows(a, stream) != hipSuccess) return LPQ_ERR_DEVICE;
             continue;
         }
         // A small launch (one linear of a decoder layer) is not cut into more ranges than it has chunks of
         // steps: thinner ranges stream no faster and only multiply the pieces the fix-up pass has to add.
-        static const int min_steps = std::max(1, env_int("LPQ_DECODE_MIN_STEPS", 16));
+        static const int min_steps_narrow = std::max(1, env_int("LPQ_DECODE_MIN_STEPS", 16));
+        static const int min_steps_wide = std::max(1, env_int("LPQ_DECODE_MIN_STEPS_WIDE", 8));      // a 64-token step is 3x as long
+        const int min_steps = M <= 16 ? min_steps_narrow : min_steps_wide;
         int64_t steps = 0;
         for (int i = 0; i < a.n_lin; ++i) steps += (int64_t)a.lin[i].row_superblocks * (a.lin[i].K / 128);
         a.n_blocks = (int32_t)std::max<int64_t>(1, std::min<int64_t>(n_blocks, steps / min_steps));

@@ -16,9 +16,9 @@
 // registers, unpacks them there into MFMA B operands and multiplies them with the activations
 // (MFMA A operands), which the workgroup stages once through a double-buffered LDS slab.
 //
-// A launch that streams little (a single linear of a decoder layer, up to 16 token rows) takes a second
-// kernel, decode_rows_kernel further down: one workgroup per row block whose waves split K, no LDS staging,
-// no fix-up pass.
+// A launch that streams little (a single linear of a decoder layer, up to 32 token rows) takes a second
+// kernel, decode_rows_kernel further down: one workgroup per group of 16-row tiles whose waves split K, no LDS
+// staging, no fix-up pass.
 #include <algorithm>
 
 #include "lpq_common.h"
@@ -547,7 +547,9 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
     };
     // ranges that overlap the unit (an upper bound that needs no walk): unit weight / range weight, plus both ends
     const uint64_t n_pieces = (uint64_t)KT * L.step_weight * (uint64_t)a.n_blocks / a.total_weight + 2;
-    for (int base = 0; base < n_items; base += 1024) {
+    // blockIdx.y picks the pass: a unit of 64 tokens x 512 rows is eight passes, added by eight workgroups
+    const int base = (int)blockIdx.y * 1024;
+    if (base < n_items) {
         if (n_pieces <= 4) {
             f4 sum[PER_THREAD];
             size_t off[PER_THREAD];
@@ -569,7 +571,7 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
             });
 #pragma unroll
             for (int i = 0; i < PER_THREAD; ++i) finish(base + threadIdx.x + 256 * i, sum[i]);
-            continue;
+            return;
         }
         f4 sum[PER_LANE];
         size_t off[PER_LANE];
@@ -603,7 +605,7 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
     }
 }
 
-// ---- small launches (one linear of a decoder layer, up to 16 token rows) ---------------------------------
+// ---- small launches (one linear of a decoder layer, up to 32 token rows = MT token tiles of 16) ---------------
 // The even-share kernel above needs a launch with many steps to spread; a single linear has few, and cutting
 // its units into short ranges leaves each workgroup waiting on memory latency and pays a fix-up pass.  Here a
 // workgroup owns a group of TILES consecutive 16-row tiles of W (at most 2 for fp16 weights) over the whole of
@@ -614,11 +616,11 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
 // global memory: they are small and stay in L2; no LDS staging, no barrier in the loop), and the waves'
 // accumulators are added through LDS at the end, in wave order.  A linear with few tiles and a long K (the
 // second feed-forward matrix) is also split over L.pad workgroups per group, each taking a range of the steps
-// and leaving fp32 sums in partial[split][16][N] (at float offset L.step_weight of the launch's partial buffer)
+// and leaving fp32 sums in partial[split][16 MT][N] (at float offset L.step_weight of the launch's partial buffer)
 // for a small second kernel; otherwise there are no partial tiles and no second kernel.  L.row_blocks is the
 // linear's number of groups, a.lin[i].cum_weight the number of workgroups of the linears before i, a.n_blocks
 // their total.
-template <int V, int WAVES, int TILES>
+template <int V, int WAVES, int TILES, int MT>
 __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int split, float* __restrict__ partial, float* __restrict__ red)
 {
     constexpr int RT = (V == V_F16 && TILES > 2) ? 2 : TILES;      // 16-row tiles per workgroup; rb counts groups of RT tiles
@@ -627,9 +629,9 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
     constexpr bool POST = V != V_F16;
     constexpr int STAGES = (V == V_W3 || V == V_W4) ? 4 : 3;
     constexpr int LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) +
-                          (SCHEME == SCH_ASYM ? (ALIGNED ? 2 : 4) : 0) + 4;
+                          (SCHEME == SCH_ASYM ? (ALIGNED ? 2 : 4) : 0) + 4 * MT;
     static_assert((STAGES - 1) * LOADS < 64, "vmcnt is a 6-bit counter");
-    constexpr int NV = RT * 4 + (SCHEME == SCH_SYM ? 4 : 0);       // floats a lane hands to the reduction
+    constexpr int NV = (RT * MT + (SCHEME == SCH_SYM ? MT : 0)) * 4;   // floats a lane hands to the reduction
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // a scalar: the row block and the tile addresses derive from it
     const int r = lane & 15, kq = lane >> 4;
@@ -639,13 +641,15 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
     const int splits = L.pad, share = KT / splits, extra = KT % splits;
     const int kt0 = split * share + min(split, extra), kt1 = kt0 + share + (split < extra ? 1 : 0);
     const int n_w = kt1 - kt0 > wave ? (kt1 - kt0 - wave + WAVES - 1) / WAVES : 0;      // this wave's steps
-    const uint16_t* __restrict__ xrow = L.x + (size_t)min(r, M - 1) * L.K + 8 * kq;   // token rows past M repeat the last one
+    const uint16_t* __restrict__ xrow[MT];                          // token tile m holds rows 16 m .. 16 m + 15; rows past M repeat the last one
+#pragma unroll
+    for (int m = 0; m < MT; ++m) xrow[m] = L.x + (size_t)min(r + 16 * m, M - 1) * L.K + 8 * kq;
 
     struct Stage {
         WRaw<V> w[RT];
         u32x2 s, z;                 // scales and zeros of rows 4 r .. 4 r + 3 of the first tile's block
         u32x2 s1, z1;               // !ALIGNED: and of the next block (the group spans two)
-        h8 a[4];
+        h8 a[MT][4];
     };
     Stage st[STAGES];
     // step i of this wave; past its last step the loads repeat a valid step (they keep the count of loads in
@@ -665,33 +669,45 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
             }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) b.a[j] = *reinterpret_cast<const h8*>(xrow + (size_t)kt * 128 + 32 * j);
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b.a[m][j] = *reinterpret_cast<const h8*>(xrow[m] + (size_t)kt * 128 + 32 * j);
     };
 
-    f4 acc[RT], xsum = {0, 0, 0, 0};
+    f4 acc[RT][MT], xsum[MT];
 #pragma unroll
-    for (int t = 0; t < RT; ++t) acc[t] = f4{0, 0, 0, 0};
+    for (int m = 0; m < MT; ++m) {
+        xsum[m] = f4{0, 0, 0, 0};
+#pragma unroll
+        for (int t = 0; t < RT; ++t) acc[t][m] = f4{0, 0, 0, 0};
+    }
     auto compute = [&](const Stage& b) {
         if constexpr (POST) {
             h8 wj[2][RT];
             const _Float16 one = (_Float16)1.0f;
             const h8 ones = {one, one, one, one, one, one, one, one};
             const f4 zero4 = {0, 0, 0, 0};
-            f4 d[RT], xs;
+            f4 d[RT][MT], xs[MT];
 #pragma unroll
             for (int t = 0; t < RT; ++t) wj[0][t] = unpack_subnormal_step<V>(b.w[t], 0);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                // one scheduling group per tile: its matrix instruction of step j and the unpacking of the same tile
+                // one scheduling group per tile: its matrix instructions of step j and the unpacking of the same tile
                 // for step j + 1, so that the vector work sits between matrix instructions, not in front of them
-                if constexpr (SCHEME == SCH_ASYM) xs = mfma16(b.a[j], ones, j == 0 ? zero4 : xs);
-                else                               xsum = mfma16(b.a[j], ones, xsum);
+#pragma unroll
+                for (int m = 0; m < MT; ++m) {
+                    if constexpr (SCHEME == SCH_ASYM) xs[m] = mfma16(b.a[m][j], ones, j == 0 ? zero4 : xs[m]);
+                    else                               xsum[m] = mfma16(b.a[m][j], ones, xsum[m]);
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int t = 0; t < RT; ++t) {
                     if (j < 3) wj[(j + 1) & 1][t] = unpack_subnormal_step<V>(b.w[t], j + 1);
-                    if constexpr (SCHEME == SCH_ASYM) d[t] = mfma16(b.a[j], wj[j & 1][t], j == 0 ? zero4 : d[t]);
-                    else                               acc[t] = mfma16(b.a[j], wj[j & 1][t], acc[t]);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        if constexpr (SCHEME == SCH_ASYM) d[t][m] = mfma16(b.a[m][j], wj[j & 1][t], j == 0 ? zero4 : d[t][m]);
+                        else                               acc[t][m] = mfma16(b.a[m][j], wj[j & 1][t], acc[t][m]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -709,14 +725,18 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
                     const float sf = (float)__builtin_bit_cast(_Float16, sh) * 16777216.0f;     // scale * 2^24
                     const float zf = (float)__builtin_bit_cast(_Float16, zh);
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[t][v] = __builtin_fmaf(sf, d[t][v], __builtin_fmaf(zf, xs[v], acc[t][v]));
+                    for (int m = 0; m < MT; ++m)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[t][m][v] = __builtin_fmaf(sf, d[t][m][v], __builtin_fmaf(zf, xs[m][v], acc[t][m][v]));
                 }
             }
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int t = 0; t < RT; ++t) acc[t] = mfma16(b.a[j], __builtin_bit_cast(h8, b.w[t].q[j]), acc[t]);
+                for (int t = 0; t < RT; ++t)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) acc[t][m] = mfma16(b.a[m][j], __builtin_bit_cast(h8, b.w[t].q[j]), acc[t][m]);
         }
     };
 
@@ -734,34 +754,39 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
         }
     }
 
-    // add the waves' sums in wave order; thread idx -> (token, row of the block), consecutive threads on consecutive rows
+    // add the waves' sums in wave order; thread idx -> (token, row of the group), consecutive threads on consecutive rows
     float* mine = red + (size_t)wave * NV * 64;
 #pragma unroll
     for (int t = 0; t < RT; ++t)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) mine[(4 * t + v) * 64 + lane] = acc[t][v];
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mine[(4 * (t * MT + m) + v) * 64 + lane] = acc[t][m][v];
     if constexpr (SCHEME == SCH_SYM) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) mine[(4 * RT + v) * 64 + lane] = xsum[v];
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) mine[(4 * (RT * MT + m) + v) * 64 + lane] = xsum[m][v];
     }
     __syncthreads();
     constexpr int ROWS = 16 * RT;
-    for (int idx = tid; idx < 16 * ROWS; idx += 64 * WAVES) {
+    for (int idx = tid; idx < 16 * MT * ROWS; idx += 64 * WAVES) {
         const int tok = idx / ROWS, rl = idx % ROWS;
         if (tok >= M) continue;
-        const int rr = rl / RT, t = rl % RT, v = tok & 3, ln = 16 * (tok >> 2) + rr;
+        const int m = tok >> 4, tl = tok & 15;
+        const int rr = rl / RT, t = rl % RT, v = tl & 3, ln = 16 * (tl >> 2) + rr;
         float sum = 0.0f, xs = 0.0f;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * NV + 4 * t + v) * 64 + ln];
+        for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * NV + 4 * (t * MT + m) + v) * 64 + ln];
         const long row = ((g0 + t) >> 2) * 64 + 4 * rr + ((g0 + t) & 3);
         if constexpr (SCHEME == SCH_SYM) {
 #pragma unroll
-            for (int w = 0; w < WAVES; ++w) xs += red[((size_t)w * NV + 4 * RT + v) * 64 + ln];
+            for (int w = 0; w < WAVES; ++w) xs += red[((size_t)w * NV + 4 * (RT * MT + m) + v) * 64 + ln];
             sum = (sum * 16777216.0f - 128.0f * xs) * (float)__builtin_bit_cast(_Float16, L.scales[row]);   // undo 2^-24 and the +128 offset
         }
         const size_t o = (size_t)tok * L.N + row;
         if (splits > 1) {
-            partial[((size_t)split * 16) * L.N + o] = sum;
+            partial[((size_t)split * 16 * MT) * L.N + o] = sum;
             continue;
         }
         if (L.bias) sum += (float)__builtin_bit_cast(_Float16, L.bias[row]);
@@ -771,27 +796,30 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
     }
 }
 
-template <int WAVES, int TILES>
-__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_rows_kernel(const DecodeArgs a)
+// One token tile (up to 16 token rows): two workgroups of four waves per compute unit.  Two token tiles (17-32
+// rows) double the activations of a stage, and five tiles of W fill the 256 registers of that occupancy: those
+// kernels take up to 512 registers per lane and one four-wave workgroup per unit.
+template <int WAVES, int TILES, int MT>
+__global__ __launch_bounds__(64 * WAVES, (MT == 2 || TILES == 5) ? 1 : 8 / WAVES) void decode_rows_kernel(const DecodeArgs a)
 {
-    __shared__ float red[WAVES * (4 * TILES + 4) * 64];
+    __shared__ float red[WAVES * (TILES * MT + MT) * 4 * 64];
     const int b = blockIdx.x;
-    int li = 0, hi = a.n_lin - 1;                    // last linear whose first row block is <= b
+    int li = 0, hi = a.n_lin - 1;                    // last linear whose first workgroup is <= b
     while (li < hi) {
         const int mid = (li + hi + 1) >> 1;
         if (a.lin[mid].cum_weight <= (uint64_t)b) li = mid; else hi = mid - 1;
     }
     const LinDesc& L = a.lin[li];
-    const long wg = (long)b - (long)L.cum_weight;          // split-major: a split's row blocks are neighbours
+    const long wg = (long)b - (long)L.cum_weight;          // split-major: a split's groups are neighbours
     const long rb = wg % L.row_blocks;
     const int split = (int)(wg / L.row_blocks);
     float* partial = a.partial + L.step_weight;
     switch (L.variant) {
-    case V_W3: run_rows<V_W3, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
-    case V_W4: run_rows<V_W4, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
-    case V_W8: run_rows<V_W8, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
-    case V_I8: run_rows<V_I8, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
-    default:   run_rows<V_F16, WAVES, TILES>(L, a.M, rb, split, partial, red); break;
+    case V_W3: run_rows<V_W3, WAVES, TILES, MT>(L, a.M, rb, split, partial, red); break;
+    case V_W4: run_rows<V_W4, WAVES, TILES, MT>(L, a.M, rb, split, partial, red); break;
+    case V_W8: run_rows<V_W8, WAVES, TILES, MT>(L, a.M, rb, split, partial, red); break;
+    case V_I8: run_rows<V_I8, WAVES, TILES, MT>(L, a.M, rb, split, partial, red); break;
+    default:   run_rows<V_F16, WAVES, TILES, MT>(L, a.M, rb, split, partial, red); break;
     }
 }
 
@@ -801,7 +829,7 @@ __global__ __launch_bounds__(256) void decode_rows_reduce_kernel(const DecodeArg
 {
     const LinDesc& L = a.lin[li];
     const float* __restrict__ partial = a.partial + L.step_weight;
-    const size_t quads = (size_t)a.M * L.N / 4, plane = (size_t)16 * L.N;
+    const size_t quads = (size_t)a.M * L.N / 4, plane = (size_t)(a.M <= 16 ? 16 : 32) * L.N;
     for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < quads; q += (size_t)gridDim.x * 256) {
         const size_t e = 4 * q;
         const int n = (int)(e % L.N);
@@ -849,9 +877,11 @@ hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s)
     const unsigned grid = (unsigned)a.n_blocks;
 #define LPQ_ROWS_CASE(T)                                                                      \
     case T:                                                                                   \
-        if (a.waves == 8) decode_rows_kernel<8, T><<<grid, 512, 0, s>>>(a);                   \
-        else              decode_rows_kernel<4, T><<<grid, 256, 0, s>>>(a);                   \
+        if (a.M > 16)          decode_rows_kernel<4, T, 2><<<grid, 256, 0, s>>>(a);           \
+        else if (a.waves == 8) decode_rows_kernel<8, T, 1><<<grid, 512, 0, s>>>(a);           \
+        else                   decode_rows_kernel<4, T, 1><<<grid, 256, 0, s>>>(a);           \
         break;
+    if (a.M > 32) return hipErrorInvalidValue;
     switch (a.row_tiles) {
         LPQ_ROWS_CASE(2) LPQ_ROWS_CASE(3) LPQ_ROWS_CASE(4) LPQ_ROWS_CASE(5)
     default: return hipErrorInvalidValue;
@@ -872,7 +902,9 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t s)
     hipError_t e = a.waves == 8 ? launch_waves<8>(a, s) : launch_waves<4>(a, s);
     if (e != hipSuccess) return e;
     if (a.n_blocks > 1) {
-        decode_fixup_kernel<<<(unsigned)(a.n_blocks - 1), 256, 0, s>>>(a);
+        const int m_cnt = std::min(64, a.M - a.m0);
+        const dim3 grid((unsigned)(a.n_blocks - 1), (unsigned)((m_cnt * a.waves * 16 + 1023) / 1024));     // passes of 1024 groups of 4 rows
+        decode_fixup_kernel<<<grid, 256, 0, s>>>(a);
         e = hipGetLastError();
     }
     return e;

@@ -134,7 +134,7 @@ def test_other_configs_one_layer_per_variant(orc, ci, layer_ids, Md):
 @pytest.mark.parametrize("bits,scheme", [(3, 1), (4, 1), (8, 1), (8, 2), (16, 0)], ids=["w3", "w4", "w8", "i8", "f16"])
 def test_single_linear_launches_at_layer_shapes(orc, bits, scheme):
     """One linear per launch, as a decoder layer issues them (OPT-13B shapes): the decode phase then runs in the
-    small-launch kernel (a workgroup per row block; FC2 K-split with its reduce kernel), the prefill phase K-splits
+    small-launch kernel (a workgroup per group of 2-5 tiles, one or two token tiles; FC2 K-split with its reduce kernel), the prefill phase K-splits
     the launches with few tiles.  Sampled bands and tokens against the oracle, one projection over every column."""
     import torch
     cfg = wl.CONFIGS[1]
@@ -146,7 +146,7 @@ def test_single_linear_launches_at_layer_shapes(orc, bits, scheme):
         bias = (torch.arange(N, device=dev) % 9 - 4).to(torch.float16) * 0.25
         qw = lpq.lpq_quantize_pack(w, bits, scheme, bias=bias)
         w_host_bias = bias.cpu().numpy()
-        for fn, M in ((lpq.lpq_qlinear_decode, 16), (lpq.lpq_qlinear_decode, 5), (lpq.lpq_qlinear_prefill, 512),
+        for fn, M in ((lpq.lpq_qlinear_decode, 16), (lpq.lpq_qlinear_decode, 5), (lpq.lpq_qlinear_decode, 27), (lpq.lpq_qlinear_prefill, 512),
                       (lpq.lpq_qlinear_prefill, 2048)):
             x = wl.act_torch(M, K, True, dev, "single", name, M)
             y = torch.full((M, N), float("nan"), dtype=torch.float16, device=dev)

@@ -222,8 +222,9 @@ def _build_stage(cfg_key, h, f, qkv_n, layer_specs, M, outliers):
     return lpq.Stage(layers, xs, ys), ys, host
 
 
-@pytest.mark.parametrize("phase,M", [(lpq.LPQ_DECODE, 1), (lpq.LPQ_DECODE, 16), (lpq.LPQ_PREFILL, 128)],
-                         ids=["decode_M1", "decode_M16", "prefill_M128"])
+@pytest.mark.parametrize("phase,M", [(lpq.LPQ_DECODE, 1), (lpq.LPQ_DECODE, 16), (lpq.LPQ_DECODE, 24), (lpq.LPQ_DECODE, 40),
+                                     (lpq.LPQ_PREFILL, 128)],
+                         ids=["decode_M1", "decode_M16", "decode_M24", "decode_M40", "prefill_M128"])
 def test_stage_mixed_bits_small(orc, phase, M, decode_kernel_choice):
     if decode_kernel_choice in ("rows_3", "rows_5"):
         pytest.skip("the stage's linears have 16, 48 and 64 tiles: no group of 3 or 5 fits them all")

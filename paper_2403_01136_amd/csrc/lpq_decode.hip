@@ -16,7 +16,7 @@
 // registers, unpacks them there into MFMA B operands and multiplies them with the activations
 // (MFMA A operands), which the workgroup stages once through a double-buffered LDS slab.
 //
-// A launch that streams little (a single linear of a decoder layer, up to 32 token rows) takes a second
+// A launch that streams little (a single linear of a decoder layer, up to 32 token rows per pass) takes a second
 // kernel, decode_rows_kernel further down: one workgroup per group of 16-row tiles whose waves split K, no LDS
 // staging, no fix-up pass.
 #include <algorithm>

@@ -98,7 +98,7 @@ def test_load_quantize_pack_from_host(orc, bits, scheme, pinned):
 
 @pytest.fixture(params=["rows", "rows_3", "rows_5", "even_share"])
 def decode_kernel_choice(request, monkeypatch):
-    """Up to 32 token rows, a launch that streams little goes to the kernel that gives a group of 16-row tiles a
+    """Up to 64 token rows (32 per pass), a launch that streams little goes to the kernel that gives a group of 16-row tiles a
     workgroup, a larger one to the even-share kernel; the limit is read at every call, so small shapes can reach both.
     rows_3 / rows_5 ask for groups of 3 / 5 tiles, which cut across the packed layout's 64-row blocks (the library
     falls back to 4 where the group size does not divide a linear's tiles: N = 320 has 20, N = 192 has 12)."""
@@ -112,8 +112,8 @@ def decode_kernel_choice(request, monkeypatch):
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)
 @pytest.mark.parametrize("M", [1, 2, 5, 16, 17, 32, 33, 64])
 def test_decode_small(orc, bits, scheme, M, decode_kernel_choice):
-    if M > 32 and decode_kernel_choice != "even_share":
-        pytest.skip("more than 32 token rows always take the even-share kernel")
+    if M > 64 and decode_kernel_choice != "even_share":
+        pytest.skip("more than 64 token rows always take the even-share kernel")
     N, K = 320, 640         # 5 (fp16: 10) row blocks: the last workgroup has idle waves; 5 steps: idle waves in a row block's workgroup
     w = wl.weight_np(N, K, "dec", bits, scheme)
     x = wl.act_np(M, K, True, "dec", M)
@@ -127,8 +127,8 @@ def test_decode_small(orc, bits, scheme, M, decode_kernel_choice):
 def test_decode_split_k_and_many_rows(orc, bits, scheme, M, decode_kernel_choice):
     """K long enough that the work is cut into several K ranges (fp32 partial sums + reduction, or waves that split
     K); M > 64 runs in several passes; a bias is added exactly once."""
-    if M > 32 and decode_kernel_choice != "even_share":
-        pytest.skip("more than 32 token rows always take the even-share kernel")
+    if M > 64 and decode_kernel_choice != "even_share":
+        pytest.skip("more than 64 token rows always take the even-share kernel")
     N, K = 192, 16384
     w = wl.weight_np(N, K, "decsk", bits, scheme)
     x = wl.act_np(M, K, True, "decsk", M)

@@ -382,7 +382,7 @@ lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStrea
     lpq_status cst = device_cus(&cus);
     if (cst != LPQ_OK) return cst;
     for (int variant = 0; variant < 5; ++variant) {
-        const int BM = prefill_tokens_per_tile(variant);
+        const int BM = prefill_tokens_per_tile(variant, M);
         const int m_blocks = (M + BM - 1) / BM;
         std::vector<const LinearCall*> mine;
         for (const LinearCall& c : calls)

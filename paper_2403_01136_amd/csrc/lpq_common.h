@@ -114,7 +114,7 @@ hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s);     // small launches, M <= 32: cum_weight = workgroups before
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);      // both kernels, if any linear is K-split
-int prefill_tokens_per_tile(int variant);
+int prefill_tokens_per_tile(int variant, int M);
 // variance indicator (lpq_indicator.hip)
 size_t indicator_workspace_bytes(int N, long n8);
 hipError_t launch_indicator(const void* w, int K, int N, const void* x, int M, int stochastic, double* omega, void* ws, hipStream_t s);

@@ -38,7 +38,7 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // SPLIT: some linear of the launch is K-split (the instantiation without it carries no second epilogue,
 // whose registers the first would otherwise spill for).
 template <int V, int BM, bool SPLIT>
-__global__ __launch_bounds__(256, BM > 128 ? 1 : 2)
+__global__ __launch_bounds__(256, 1)
 void prefill_kernel(const PrefillArgs a)
 {
     int li = 0;
@@ -312,15 +312,13 @@ __global__ __launch_bounds__(256) void prefill_reduce_kernel(const PrefillArgs a
     }
 }
 
-// Tokens per tile: 256 for every variant (one workgroup per CU; 256 accumulator registers of the 512
-// a lane can have at one wave per SIMD).  Weight bytes are re-read from L2 once per token block and
-// unpacked once per token block, so larger tiles mean fewer of both per matrix instruction.
-template <int V> struct PrefillTile { enum { BM = 256 }; };
-
-template <int V>
-hipError_t launch_variant(const PrefillArgs& a, hipStream_t s)
+// Tokens per tile: 256 (one workgroup per CU; 256 accumulator registers of the 512 a lane can have at one
+// wave per SIMD).  Weight bytes are re-read from L2 once per token block and unpacked once per token block,
+// so larger tiles mean fewer of both per matrix instruction.  A launch of at most 128 token rows has a single
+// token block either way and takes 128-token tiles: half the matrix instructions per step.
+template <int V, int BM>
+hipError_t launch_tiles(const PrefillArgs& a, hipStream_t s)
 {
-    constexpr int BM = PrefillTile<V>::BM;
     const size_t smem = sizeof(PrefillSmem<BM>);
     static bool attr_set = false;
     if (!attr_set) {
@@ -345,18 +343,15 @@ hipError_t launch_variant(const PrefillArgs& a, hipStream_t s)
     return e;
 }
 
+template <int V>
+hipError_t launch_variant(const PrefillArgs& a, hipStream_t s)
+{
+    return prefill_tokens_per_tile(V, a.M) == 128 ? launch_tiles<V, 128>(a, s) : launch_tiles<V, 256>(a, s);
+}
+
 }  // namespace
 
-int prefill_tokens_per_tile(int variant)
-{
-    switch (variant) {
-    case V_W3: return PrefillTile<V_W3>::BM;
-    case V_W4: return PrefillTile<V_W4>::BM;
-    case V_W8: return PrefillTile<V_W8>::BM;
-    case V_I8: return PrefillTile<V_I8>::BM;
-    default: return PrefillTile<V_F16>::BM;
-    }
-}
+int prefill_tokens_per_tile(int /*variant*/, int M) { return M <= 128 ? 128 : 256; }
 
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s)
 {

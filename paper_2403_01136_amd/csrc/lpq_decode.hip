@@ -462,7 +462,9 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const Dec
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     DecodeSmem<TOK, WAVES>& sm = *reinterpret_cast<DecodeSmem<TOK, WAVES>*>(smem_raw);
-    const int b = blockIdx.x;
+    // Workgroup ids go round-robin over the 8 XCDs, each with its own L2.  XCD x takes the x-th eighth of the
+    // ranges, so that a linear's activations are fetched into one or two L2s instead of all eight.
+    const int b = (a.n_blocks & 7) == 0 ? (int)(blockIdx.x & 7) * (a.n_blocks >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
     const uint64_t lo = range_begin(a, b), hi = range_begin(a, b + 1);
     Cursor c = first_step_at(a, lo);
     float* slot_first = a.partial + (size_t)(2 * b) * a.slot_floats;

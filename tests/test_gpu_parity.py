@@ -188,6 +188,29 @@ def test_activation_magnitude(orc, bits, scheme, mag, decode_kernel_choice):
         check_output(y, orc.qlinear(x, w, bits, scheme), "%s %d-bit M=%d x*%g" % (tag, bits, M, mag))
 
 
+RANDOM_SHAPES = [(N, K, M, v) for i, (N, K, M) in enumerate([
+    (192, 4096, 1), (320, 1024, 7), (960, 384, 16), (1280, 1024, 19), (1600, 128, 32), (2048, 2048, 45), (960, 4096, 64),
+    (1280, 384, 5), (320, 4096, 27), (1600, 1024, 16), (2048, 128, 3), (192, 2048, 33)]) for v in [VARIANTS[i % len(VARIANTS)]]]
+
+
+@pytest.mark.parametrize("N,K,M,variant", RANDOM_SHAPES, ids=["N%d_K%d_M%d_%s" % (N, K, M, VARIANT_IDS[VARIANTS.index(v)]) for N, K, M, v in RANDOM_SHAPES])
+def test_decode_shapes_that_vary_the_workgroup_plan(orc, N, K, M, variant):
+    """A single decode linear picks its workgroup shape from N, K and M (groups of 2-5 tiles, K splits, one or two
+    token tiles, one or two passes): shapes whose tile counts divide by 3 or 5 or neither, long and one-step K,
+    every range of M, with a bias and a residual, every element against the oracle."""
+    import torch
+    bits, scheme = variant
+    w = wl.weight_np(N, K, "plan", N, K, bits, scheme)
+    x = wl.act_np(M, K, True, "plan", N, K, M)
+    bias = ((np.arange(N) % 5) - 2).astype(np.float16) * np.float16(0.5)
+    res = wl.act_np(M, N, False, "plan-res", N, K, M)
+    qw = lpq.lpq_quantize_pack(to_dev(w), bits, scheme, bias=to_dev(bias))
+    y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    lpq.lpq_qlinear_fused(qw, to_dev(x), lpq.LPQ_DECODE, residual=to_dev(res), y=y)
+    ref = orc.qlinear(x, w, bits, scheme, bias) + res.astype(np.float64)
+    check_output(y, ref, "decode N=%d K=%d M=%d %d-bit" % (N, K, M, bits))
+
+
 def test_decode_and_prefill_agree_and_are_deterministic(orc):
     N, K, M = 128, 2048, 24
     w = wl.weight_np(N, K, "agree")

@@ -1,17 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the quantized-linear hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--only decode|prefill|all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--only decode|prefill|all] [--no-per-config]
 
-Workload: the OPT-13B-shaped stage (8 consecutive layers, bits [16,8,4,4,3,3,4,8], g = 128) that
-the headline metric is quoted on, with seeded synthetic weights and activations.  One "step" is one
-decode-phase pass of lpq_stage_linears over the whole stage at the decode micro-batch (M = 16);
-the prefill-phase pass (M = 4 x 512) and the quantise+pack pass are timed in the same run and
-reported in the same JSON line.  Inputs are resident in HBM before any timed region starts.
+Headline workload: the largest configuration that one GPU holds, configs[4] -- the BLOOM-176B-shaped pipeline share
+(10 consecutive layers, all 3-bit, g = 128, 10 GB packed) with seeded synthetic weights and activations.  One "step"
+is one decode-phase pass of lpq_stage_linears over the whole stage at the decode micro-batch (M = 16); the
+prefill-phase pass (M = 4 x 512) and the quantise+pack pass are timed in the same run and reported in the same JSON
+line.  `per_config` then holds every configuration (1-4) at every decode micro-batch of its sweep and at its prefill
+micro-batch, each with its time and its fraction of the HBM or matrix-core peak, plus -- as context only -- what the
+vendor's fp16 GEMM reaches on the same shapes and data.  Inputs are resident in HBM before any timed region starts.
 
-Prints ONE JSON line: the contract fields, plus `roofline` (dominant kernel: decode, HBM-bound),
-`prefill` (TFLOP/s and its MFMA roofline), `quantize` and `cpu_baseline` (the CPU oracle timed on
-a bounded sample of the same workload on this machine's host cores).
+Prints ONE JSON line: the contract fields, plus `roofline` (dominant kernel: decode, HBM-bound), `prefill`
+(TFLOP/s and its MFMA roofline), `per_config`, `quantize`, `layer`, `loader` and `cpu_baseline` (the CPU oracle
+timed on a bounded sample of the same workload on this machine's host cores).
 """
 import argparse
 import json
@@ -96,14 +98,16 @@ def act_bytes(cfg, M):
     return sum(2 * M * K + 2 * M * N for _ in cfg["layers"] for (K, N) in wl.linear_shapes(cfg).values())
 
 
-def cpu_baseline(cfg, M, budget_rows=20480):
+def cpu_baseline(cfg, M, budget_weights=0.9e9):
     """The CPU oracle (as it stands) on a bounded sample of the same workload: for every layer of the
-    stage, `budget_rows` output rows of its FC1 linear, quantise -> dequantise -> fp64 matmul at the
-    decode micro-batch.  Reported in the metric's unit: packed-weight bytes of the sample per second."""
+    stage, `budget_rows` output rows of its FC1 linear (about budget_weights weights in all: 10-30 s of
+    host work), quantise -> dequantise -> fp64 matmul at the decode micro-batch.  Reported in the metric's
+    unit: packed-weight bytes of the sample per second."""
     import numpy as np
     import oracle
     from paper_2403_01136_amd import workloads as wl
-    K, _ = wl.linear_shapes(cfg)["fc1"]
+    K, N = wl.linear_shapes(cfg)["fc1"]
+    budget_rows = int(min(N, max(64, budget_weights / (K * len(cfg["layers"])) // 64 * 64)))
     cores = len(os.sched_getaffinity(0))
     x = wl.act_np(M, K, cfg["act_outliers"], cfg["name"], "cpu_baseline")
     ws = [wl.weight_np(budget_rows, K, cfg["name"], li, "fc1", "cpu_baseline") for li in range(len(cfg["layers"]))]
@@ -227,17 +231,76 @@ def traffic_from_profiles(cfg, phase, M):
     return rec.get("%s/%s M=%d" % (cfg["name"], phase, M))
 
 
+def headline_decode_m(ci, cfg):
+    """The decode micro-batch the headline is quoted at: 16 for the BLOOM-176B share (the middle of its sweep), else
+    the configuration's last (largest) one."""
+    return 16 if ci == 4 else cfg["decode_Ms"][-1]
+
+
+def decode_point(stage_w, cfg, M, device, steps, warmup):
+    """One decode sweep point: a Stage over the resident packed weights with activations of M rows."""
+    import paper_2403_01136_amd as lpq
+    from paper_2403_01136_amd import workloads as wl
+    stage, _ = reuse_stage(stage_w, M, cfg, device)
+    ms, wall = time_phase(stage, lpq.LPQ_DECODE, steps, warmup)
+    wbytes = wl.stage_packed_bytes(cfg)
+    algo = wbytes + act_bytes(cfg, M)
+    return {"M": M, "ms": ms, "host_ms": wall, "packed_weight_GBs": wbytes / ms / 1e6, "algorithmic_GBs": algo / ms / 1e6,
+            "frac_of_hbm_peak": algo / ms / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": algo}
+
+
+def prefill_point(stage_w, cfg, device, steps, warmup):
+    import paper_2403_01136_amd as lpq
+    from paper_2403_01136_amd import workloads as wl
+    Mp = cfg["prefill_M"]
+    stage, _ = reuse_stage(stage_w, Mp, cfg, device)
+    ms, wall = time_phase(stage, lpq.LPQ_PREFILL, steps, warmup)
+    flops = wl.stage_flops(cfg, Mp)
+    return {"M": Mp, "ms": ms, "host_ms": wall, "TFLOPs": flops / ms / 1e9, "frac_of_mfma_peak": flops / ms / 1e9 / MFMA_F16_PEAK_TFLOPS,
+            "flops": flops, "steps": steps, "warmup": warmup}
+
+
+def vendor_gemm_point(cfg, device, steps=5):
+    """Context only, not this library: the vendor's fp16 GEMM (torch.matmul) on the four linear shapes of the
+    configuration at its prefill micro-batch, same seeded operands, all layers' FLOPs -- what a plain library
+    GEMM on unquantised weights reaches on this machine on the same data."""
+    import torch
+    from paper_2403_01136_amd import workloads as wl
+    Mp = cfg["prefill_M"]
+    total_ms, flops = 0.0, 0.0
+    for name, (K, N) in wl.linear_shapes(cfg).items():
+        w = wl.weight_torch(N, K, device, cfg["name"], 0, name)
+        x = wl.act_torch(Mp, K, cfg["act_outliers"], device, cfg["name"], 0, "f" if name == "fc2" else "h", Mp)
+        y = torch.empty((Mp, N), dtype=torch.float16, device=device)
+        for _ in range(2):
+            torch.matmul(x, w.t(), out=y)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            torch.matmul(x, w.t(), out=y)
+        e1.record()
+        torch.cuda.synchronize()
+        total_ms += e0.elapsed_time(e1) / steps
+        flops += 2.0 * Mp * K * N
+        del w, x, y
+    return {"kind": "torch.matmul fp16 (vendor GEMM library), one layer's four shapes", "TFLOPs": flops / total_ms / 1e9,
+            "frac_of_mfma_peak": flops / total_ms / 1e9 / MFMA_F16_PEAK_TFLOPS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--config", type=int, default=4, help="headline configuration (default: the largest, configs[4])")
     ap.add_argument("--decode-m", type=int, default=None)
     ap.add_argument("--only", choices=["all", "decode", "prefill", "layer"], default="all")
+    ap.add_argument("--no-per-config", action="store_true", help="time the headline configuration only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-loader", action="store_true", help="skip the host-to-device quantised-load measurement")
     ap.add_argument("--no-layer", action="store_true", help="skip the whole-decoder-layer measurement")
+    ap.add_argument("--no-vendor-gemm", action="store_true", help="skip the vendor GEMM context figure")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times, so a --pmc run can scale FETCH_SIZE / WRITE_SIZE by it")
     args = ap.parse_args()
@@ -254,13 +317,15 @@ def main():
         sys.exit(3)
     lpq.load_library()
     device = torch.device("cuda:0")
-    cfg = wl.CONFIGS[args.config]
-    Md = args.decode_m or cfg["decode_Ms"][-1 if args.config != 4 else 2]
+    ci = args.config
+    cfg = wl.CONFIGS[ci]
+    Md = args.decode_m or headline_decode_m(ci, cfg)
     Mp = cfg["prefill_M"]
+    side_cfg = wl.CONFIGS[1]           # the decoder-layer and loader legs stay on the OPT-13B shapes
 
     if args.only == "layer":          # the whole-decoder-layer measurement alone (for profiling it)
         print(json.dumps({"metric": "decoder layer latency", "unit": "ms", "n_gpus": 1, "data": "synthetic",
-                          "layer": layer_bench(cfg, device, layer=min(2, len(cfg["layers"]) - 1), steps=args.steps)}))
+                          "layer": layer_bench(side_cfg, device, layer=2, steps=args.steps)}))
         return
     qt = []
     stage_d, _ = build_stage(cfg, Md, device, quant_times=qt)
@@ -268,7 +333,7 @@ def main():
     out = {"metric": "decode packed-weight GB/s", "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
            "config": {"workload": "configs[%d] %s: %d layers, bits %s, g=128, decode M=%d, prefill M=%d"
-                                  % (args.config, cfg["name"], len(cfg["layers"]), [b for b, _ in cfg["layers"]], Md, Mp),
+                                  % (ci, cfg["name"], len(cfg["layers"]), [b for b, _ in cfg["layers"]], Md, Mp),
                       "packed_weight_bytes": wbytes}}
     n_w = sum(n for n, _ in qt)
     q_ms = sum(t for _, t in qt)
@@ -283,20 +348,18 @@ def main():
                            "frac": algo / ms / 1e6 / HBM_PEAK_GBS, "traffic": None,
                            "kernel": "decode_kernel + decode_fixup_kernel (one grouped decode launch of the stage)",
                            "algorithmic_bytes_per_launch": algo}
+    psteps, pwarm = max(3, args.steps // 10), max(1, args.warmup // 5)
     if args.only in ("all", "prefill"):
-        stage_p, _ = reuse_stage(stage_d, Mp, cfg, device)
-        psteps, pwarm = max(3, args.steps // 10), max(1, args.warmup // 5)
-        ms, wall = time_phase(stage_p, lpq.LPQ_PREFILL, psteps, pwarm)
-        flops = wl.stage_flops(cfg, Mp)
-        out["prefill"] = {"metric": "prefill TFLOP/s", "value": flops / ms / 1e9, "unit": "TFLOP/s", "ms_per_step": ms,
+        pp = prefill_point(stage_d, cfg, device, psteps, pwarm)
+        out["prefill"] = {"metric": "prefill TFLOP/s", "value": pp["TFLOPs"], "unit": "TFLOP/s", "ms_per_step": pp["ms"],
                           "steps": psteps, "warmup": pwarm,
-                          "roofline": {"bound": "mfma", "achieved": flops / ms / 1e9, "peak": MFMA_F16_PEAK_TFLOPS,
-                                       "unit": "TFLOP/s", "frac": flops / ms / 1e9 / MFMA_F16_PEAK_TFLOPS, "traffic": None,
-                                       "kernel": "prefill_kernel (one grouped launch per storage variant)",
-                                       "algorithmic_flops_per_step": flops}}
+                          "roofline": {"bound": "mfma", "achieved": pp["TFLOPs"], "peak": MFMA_F16_PEAK_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": pp["frac_of_mfma_peak"], "traffic": None,
+                                       "kernel": "prefill_kernel / prefill_ring_kernel (one grouped launch per storage variant)",
+                                       "algorithmic_flops_per_step": pp["flops"]}}
         if args.only == "prefill":
-            out.update({"metric": "prefill TFLOP/s", "unit": "TFLOP/s", "value": out["prefill"]["value"],
-                        "ms_per_step": ms, "steps": psteps, "warmup": pwarm, "roofline": out["prefill"]["roofline"]})
+            out.update({"metric": "prefill TFLOP/s", "unit": "TFLOP/s", "value": pp["TFLOPs"],
+                        "ms_per_step": pp["ms"], "steps": psteps, "warmup": pwarm, "roofline": out["prefill"]["roofline"]})
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=device).fill_(1)
         dst = torch.empty_like(src)
@@ -304,16 +367,37 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         out["copy_calibration"] = {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 3}
+        del src, dst
     for phase, M, roof in (("decode", Md, out.get("roofline") if args.only != "prefill" else None),
                            ("prefill", Mp, out.get("prefill", {}).get("roofline"))):
         measured = traffic_from_profiles(cfg, phase, M)
         if measured and roof is not None:
             roof["traffic"] = measured["bytes_per_launch"]
             roof["traffic_source"] = measured["source"]
+
+    # every configuration of the benchmark x every decode sweep point x its prefill micro-batch
+    if args.only == "all" and not args.no_per_config:
+        per = {}
+        for cj in (ci,) + tuple(c for c in range(1, len(wl.CONFIGS)) if c != ci):
+            cfg_j = wl.CONFIGS[cj]
+            if cj != ci:
+                del stage_d
+                torch.cuda.empty_cache()
+                stage_d, _ = build_stage(cfg_j, 1, device)
+            rec = {"workload": "%s: %d layers, bits %s" % (cfg_j["name"], len(cfg_j["layers"]), sorted({b for b, _ in cfg_j["layers"]})),
+                   "packed_weight_bytes": wl.stage_packed_bytes(cfg_j),
+                   "decode": [decode_point(stage_d, cfg_j, M, device, 20, 5) for M in cfg_j["decode_Ms"]],
+                   "prefill": prefill_point(stage_d, cfg_j, device, 3, 1)}
+            if not args.no_vendor_gemm:
+                rec["vendor_gemm_context"] = vendor_gemm_point(cfg_j, device)
+            per["configs[%d]" % cj] = rec
+        out["per_config"] = per
+    del stage_d
+    torch.cuda.empty_cache()
     if not args.no_layer and args.only == "all":
-        out["layer"] = layer_bench(cfg, device, layer=min(2, len(cfg["layers"]) - 1))
+        out["layer"] = layer_bench(side_cfg, device, layer=2)
     if not args.no_loader and args.only == "all":
-        out["loader"] = loader_bench(cfg, device, layer=min(2, len(cfg["layers"]) - 1))
+        out["loader"] = loader_bench(side_cfg, device, layer=2)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, Md)
     print(json.dumps(out))

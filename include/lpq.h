@@ -16,14 +16,21 @@
  *     the argument is a descriptor struct, which is read on the HOST during the call.
  *   - The library allocates nothing the caller sees.  The caller owns every buffer and keeps
  *     it alive until the work enqueued on `hip_stream` has completed.  Split-K partial sums
- *     live in an internal per-device workspace that grows on demand; every call on a device shares
- *     it, so calls that compute (linears, attention, the indicator) must not overlap on one device:
- *     enqueue them on one stream, or order the streams with events.
+ *     live in an internal per-device workspace; every call on a device shares it, so calls that
+ *     compute (linears, attention, the indicator) must not overlap on one device: enqueue them on
+ *     one stream, or order the streams with events.  The workspace grows on demand by allocating a
+ *     larger block; a block that has been handed to a kernel is never freed before the process ends
+ *     (queued work and captured graphs may hold its address), so growth costs memory, not safety.
+ *     lpq_workspace_reserve sizes it once, after which no call on that device allocates.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     enqueue work and return without synchronising.
  *   - Calls record only kernel launches (and, for the loader, copies) on `hip_stream`, so they can be
  *     captured in a HIP graph once an eager call of the same shape has run (the internal workspace is
  *     allocated, and kernel attributes are set, on first use -- not things a capture may contain).
+ *     A captured graph keeps the workspace address it was recorded with; that block stays allocated,
+ *     but eager calls that needed a larger block have moved on to another one, so a replay and an
+ *     eager call may then run concurrently without sharing partial sums -- they are still ordered
+ *     by the caller as above.
  *   - Arguments are validated on the host before the first HIP call; on any error nothing is
  *     launched and no buffer is touched.  No exceptions, no errno, no global error state.
  *   - fp16 is IEEE binary16.  x is [M][K], y is [M][N], both dense row-major, 16-byte
@@ -330,6 +337,28 @@ lpq_status lpq_plan_adabits(const lpq_plan_problem *p, int32_t *counts, int32_t 
  * *obj = the final Eq. (1) value, *rounds = exchanges applied.  Errors: NULL, SHAPE (malformed start plan). */
 lpq_status lpq_plan_bitwidth_transfer(const lpq_plan_problem *p, int32_t *counts, int32_t *choice, double *obj,
                                       int32_t *rounds);
+
+/* ---- The library's per-device workspace and dispatch routing -------------------------------------------------- */
+
+/* Growth policy of the workspace, as a pure function (host only, touches no device): a call that needs `need_bytes`
+ * when the current block has `have_bytes` reuses the block (*alloc_bytes = 0) or allocates a new one of *alloc_bytes
+ * (need + 25 %, at least 8 MiB) and retires the old one without freeing it; with a reservation in force
+ * (reserved != 0) a larger need is LPQ_ERR_BUFSIZE instead.  Errors: NULL, BUFSIZE. */
+lpq_status lpq_workspace_policy(size_t have_bytes, int32_t reserved, size_t need_bytes, size_t *alloc_bytes);
+
+/* Make the current device's workspace at least `bytes` large now (one allocation, unless it already is) and forbid
+ * later growth on this device: from here on no call allocates, and a call that would need more returns
+ * LPQ_ERR_BUFSIZE.  For callers that capture graphs or must not allocate while serving.  Errors: DEVICE, BUFSIZE. */
+lpq_status lpq_workspace_reserve(size_t bytes);
+
+/* Bytes of the current device's workspace block (0 before first use). */
+size_t lpq_workspace_bytes(void);
+
+/* Routing of decode launches, process-wide, for tests that must reach either kernel family with small shapes:
+ * a launch that streams at most rows_max_mib MiB of codes (default 192) takes the kernel that gives a group of
+ * 16-row tiles a workgroup, others the even-share kernel; rows_tiles = 2..5 forces that group size (0 = the
+ * library's choice).  Negative values restore the defaults.  Errors: SHAPE. */
+lpq_status lpq_set_decode_routing(int32_t rows_max_mib, int32_t rows_tiles);
 
 /* Test helper, not on the hot path: w_fp32[n][k] = scale * code + zero (fp32 multiply, then
  * fp32 add; the fp16 weight itself for LPQ_FP16) read back from the packed buffers.

@@ -20,6 +20,7 @@ EXPORTS = ("lpq_packed_sizes", "lpq_quantize_pack", "lpq_quantize_pack_rows", "l
            "lpq_kv_append", "lpq_attention", "lpq_decoder_layer_workspace", "lpq_decoder_layer", "lpq_variance_indicator",
            "lpq_mem_embedding_bytes", "lpq_mem_layer_bytes", "lpq_mem_kv_bytes", "lpq_latency_fit", "lpq_latency_predict",
            "lpq_plan_objective", "lpq_plan_adabits", "lpq_plan_bitwidth_transfer",
+           "lpq_workspace_policy", "lpq_workspace_reserve", "lpq_workspace_bytes", "lpq_set_decode_routing",
            "lpq_unpack_dequant",
            "lpq_status_str")
 LPQ_ACT_NONE, LPQ_ACT_RELU, LPQ_ACT_GELU_TANH = 0, 1, 2
@@ -117,9 +118,13 @@ def load_library():
         L.lpq_plan_objective.argtypes = [pp, _ip, _ip, i32, _dp]
         L.lpq_plan_adabits.argtypes = [pp, _ip, _ip, _dp]
         L.lpq_plan_bitwidth_transfer.argtypes = [pp, _ip, _ip, _dp, _ip]
+        L.lpq_workspace_policy.argtypes = [ctypes.c_size_t, i32, ctypes.c_size_t, szp]
+        L.lpq_workspace_reserve.argtypes = [ctypes.c_size_t]
+        L.lpq_workspace_bytes.argtypes = []
+        L.lpq_set_decode_routing.argtypes = [i32, i32]
         L.lpq_status_str.argtypes = [ctypes.c_int]
         L.lpq_status_str.restype = ctypes.c_char_p
-        other = {"lpq_decoder_layer_workspace": ctypes.c_size_t, "lpq_mem_embedding_bytes": ctypes.c_double,
+        other = {"lpq_decoder_layer_workspace": ctypes.c_size_t, "lpq_workspace_bytes": ctypes.c_size_t, "lpq_mem_embedding_bytes": ctypes.c_double,
                  "lpq_mem_layer_bytes": ctypes.c_double, "lpq_mem_kv_bytes": ctypes.c_double}
         for name in EXPORTS[:-1]:
             getattr(L, name).restype = other.get(name, ctypes.c_int)
@@ -469,6 +474,25 @@ def lpq_plan_bitwidth_transfer(problem, counts, choice):
                                                      choice.ctypes.data_as(_ip), ctypes.byref(obj), ctypes.byref(rounds)),
            "lpq_plan_bitwidth_transfer")
     return obj.value, counts.tolist(), choice.tolist(), rounds.value
+
+
+def lpq_workspace_policy(have_bytes, reserved, need_bytes):
+    """Bytes the library would allocate for a request of need_bytes (0 = reuse the block); raises LpqError if a reservation forbids it."""
+    alloc = ctypes.c_size_t(0)
+    _check(load_library().lpq_workspace_policy(int(have_bytes), int(bool(reserved)), int(need_bytes), ctypes.byref(alloc)), "lpq_workspace_policy")
+    return alloc.value
+
+
+def lpq_workspace_reserve(nbytes):
+    _check(load_library().lpq_workspace_reserve(int(nbytes)), "lpq_workspace_reserve")
+
+
+def lpq_workspace_bytes():
+    return int(load_library().lpq_workspace_bytes())
+
+
+def lpq_set_decode_routing(rows_max_mib=-1, rows_tiles=-1):
+    _check(load_library().lpq_set_decode_routing(int(rows_max_mib), int(rows_tiles)), "lpq_set_decode_routing")
 
 
 def lpq_unpack_dequant(qw, stream=None):

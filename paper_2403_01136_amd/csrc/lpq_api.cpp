@@ -1,7 +1,7 @@
 // C-ABI entry points: host-side validation, work decomposition, kernel dispatch.
 // Every argument check happens before the first HIP call (see include/lpq.h).
 #include <algorithm>
-#include <cstdlib>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -73,35 +73,51 @@ lpq_status check_linear(const lpq_qweight* w, const void* x, int32_t M, const vo
     return LPQ_OK;
 }
 
-// ---- split-K workspace: one buffer per device, grown on demand, released at process exit ----
+// ---- split-K workspace: one block per device, grown on demand.  A block that has been handed out is never
+// freed before the process ends: a captured HIP graph, or work still queued on a stream, may hold its address.
+// Growth allocates a new block and retires the old one (kept allocated); once lpq_workspace_reserve has been
+// called on a device, that device's block no longer grows and a larger need is an error.
 struct Workspace {
     std::mutex mu;
     void* ptr[64] = {};
     size_t bytes[64] = {};
+    bool reserved[64] = {};
+    std::vector<void*> retired;      // earlier blocks, released by the runtime at process exit
 };
 Workspace g_ws;
+
+// What a request of `need` bytes does to a block of `have` bytes: 0 = reuse it, > 0 = allocate a new block of that
+// size; LPQ_ERR_BUFSIZE if a reservation forbids growth.
+lpq_status workspace_policy(size_t have, bool reserved, size_t need, size_t* alloc)
+{
+    *alloc = 0;
+    if (need <= have) return LPQ_OK;
+    if (reserved) return LPQ_ERR_BUFSIZE;
+    *alloc = std::max(need + need / 4, (size_t)8 << 20);
+    return LPQ_OK;
+}
+
+lpq_status workspace_grow(int dev, size_t want)      // g_ws.mu held
+{
+    void* fresh = nullptr;
+    if (hipMalloc(&fresh, want) != hipSuccess) { (void)hipGetLastError(); return LPQ_ERR_BUFSIZE; }
+    if (g_ws.ptr[dev]) g_ws.retired.push_back(g_ws.ptr[dev]);
+    g_ws.ptr[dev] = fresh;
+    g_ws.bytes[dev] = want;
+    return LPQ_OK;
+}
 
 lpq_status workspace(size_t need, float** out)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
     std::lock_guard<std::mutex> lock(g_ws.mu);
-    if (g_ws.bytes[dev] < need) {
-        if (g_ws.ptr[dev] && hipFree(g_ws.ptr[dev]) != hipSuccess) return LPQ_ERR_DEVICE;   // waits for in-flight users
-        g_ws.ptr[dev] = nullptr;
-        g_ws.bytes[dev] = 0;
-        const size_t want = std::max(need + need / 4, (size_t)8 << 20);
-        if (hipMalloc(&g_ws.ptr[dev], want) != hipSuccess) { (void)hipGetLastError(); return LPQ_ERR_BUFSIZE; }
-        g_ws.bytes[dev] = want;
-    }
+    size_t alloc = 0;
+    lpq_status st = workspace_policy(g_ws.bytes[dev], g_ws.reserved[dev], need, &alloc);
+    if (st != LPQ_OK) return st;
+    if (alloc && (st = workspace_grow(dev, alloc)) != LPQ_OK) return st;
     *out = static_cast<float*>(g_ws.ptr[dev]);
     return LPQ_OK;
-}
-
-int env_int(const char* name, int fallback)
-{
-    const char* e = std::getenv(name);
-    return (e && *e) ? std::atoi(e) : fallback;
 }
 
 // Compute units of the current device (cached).
@@ -121,24 +137,21 @@ lpq_status device_cus(int* out)
     return LPQ_OK;
 }
 
+// Routing of decode launches between the two kernel families (lpq_set_decode_routing; defaults measured on MI355X).
+std::atomic<int32_t> g_rows_max_mb{192};     // launches that stream at most this many MiB of codes take the small-launch kernel
+std::atomic<int32_t> g_rows_tiles{0};        // 2..5: force that many 16-row tiles per workgroup there; 0: the planner's choice
+
 // Wavefronts per decode workgroup: 4 for up to 16 token rows; 8 beyond, where the activation slab
 // is several times larger and one workgroup per CU shares it among twice the weight rows.  The
-// workgroups per launch are what the chip holds at once.  Both can be overridden for experiments.
-int decode_waves(int M)
-{
-    static const int narrow = env_int("LPQ_DECODE_WAVES", 4) == 8 ? 8 : 4;
-    static const int wide = env_int("LPQ_DECODE_WAVES_WIDE", 8) == 4 ? 4 : 8;
-    return M <= 16 ? narrow : wide;
-}
+// workgroups per launch are what the chip holds at once (two waves per SIMD).
+int decode_waves(int M) { return M <= 16 ? 4 : 8; }
 
 lpq_status decode_block_count(int waves, int* out)
 {
     int cus = 0;
     lpq_status st = device_cus(&cus);
     if (st != LPQ_OK) return st;
-    static const int per_cu_x4 = env_int("LPQ_DECODE_BLOCKS_PER_CU_X4", 0);   // quarter workgroups per CU, 0 = what the chip holds
-    const int resident = cus * (8 / waves);                 // two waves per SIMD
-    *out = per_cu_x4 > 0 ? std::max(1, cus * per_cu_x4 / 4) : resident;
+    *out = cus * (8 / waves);
     return LPQ_OK;
 }
 
@@ -147,9 +160,8 @@ uint32_t variant_cost_x16(int variant)
 {
     // measured on MI355X: bytes of 3- and 4-bit codes take longer to stream because unpacking them is
     // ALU work per byte; 8-bit codes and fp16 weights run at the memory system's pace
-    static const int c[5] = {env_int("LPQ_COST_W3", 26), env_int("LPQ_COST_W4", 21), env_int("LPQ_COST_W8", 17),
-                             env_int("LPQ_COST_I8", 17), env_int("LPQ_COST_F16", 16)};
-    return (uint32_t)std::max(1, c[variant]);
+    static const uint32_t c[5] = {26, 21, 17, 17, 16};
+    return c[variant];
 }
 
 // Workgroup shape of a single linear in the small-launch decode kernel: 16-row tiles per workgroup (T) and K
@@ -249,8 +261,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         // A launch that streams little (a single linear of a decoder layer) has too few steps to spread evenly:
         // it goes to the kernel that gives every group of 16-row tiles a workgroup whose waves split K (no fix-up
         // pass), up to 32 token rows per pass.
-        // (read at every call, so that tests can send small shapes through either kernel)
-        const int64_t rows_max_bytes = (int64_t)env_int("LPQ_DECODE_ROWS_MAX_MB", 192) << 20;
+        const int64_t rows_max_bytes = (int64_t)g_rows_max_mb.load() << 20;
         int64_t stream_bytes = 0;
         for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c)
             stream_bytes += (int64_t)calls[c].w->d.K * calls[c].w->d.N * calls[c].w->d.bits / 8;
@@ -276,7 +287,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
                 const int tok_tiles = p.M <= 16 ? 1 : 2;
                 int tiles = 4, splits1 = 0;
                 if (p.n_lin == 1) rows_plan(p.lin[0], tok_tiles, cus, &tiles, &splits1);
-                const int forced = env_int("LPQ_DECODE_ROWS_TILES", 0);    // for tests: read at every call
+                const int forced = g_rows_tiles.load();
                 if (forced >= 2 && forced <= 5 && forced != tiles) tiles = forced, splits1 = 0;
                 auto group_tiles = [&](const LinDesc& L) { return (L.variant == 4 && tiles > 2) ? 2 : tiles; };
                 for (int i = 0; i < p.n_lin; ++i)
@@ -312,9 +323,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         }
         // A small launch (one linear of a decoder layer) is not cut into more ranges than it has chunks of
         // steps: thinner ranges stream no faster and only multiply the pieces the fix-up pass has to add.
-        static const int min_steps_narrow = std::max(1, env_int("LPQ_DECODE_MIN_STEPS", 16));
-        static const int min_steps_wide = std::max(1, env_int("LPQ_DECODE_MIN_STEPS_WIDE", 8));      // a 64-token step is 3x as long
-        const int min_steps = M <= 16 ? min_steps_narrow : min_steps_wide;
+        const int min_steps = M <= 16 ? 16 : 8;              // a 64-token step is 3x as long
         int64_t steps = 0;
         for (int i = 0; i < a.n_lin; ++i) steps += (int64_t)a.lin[i].row_superblocks * (a.lin[i].K / 128);
         a.n_blocks = (int32_t)std::max<int64_t>(1, std::min<int64_t>(n_blocks, steps / min_steps));
@@ -333,8 +342,6 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
 // unevenly over the XCDs.
 int prefill_token_groups(int m_blocks, int n_blocks)
 {
-    static const int forced = env_int("LPQ_PREFILL_TOKEN_GROUPS", 0);      // for experiments
-    if (forced == 1 || forced == 2 || forced == 4 || forced == 8) return forced;
     static const int order[4] = {2, 4, 1, 8};
     int best = 1;
     double best_imbalance = 1e30;
@@ -357,8 +364,6 @@ int prefill_token_groups(int m_blocks, int n_blocks)
 // 256-4096 tokens: the choice is the best measured one or within a few per cent of it.
 int prefill_k_splits(int tiles, int KT, int32_t M, int32_t N, int cus)
 {
-    static const int forced = env_int("LPQ_PREFILL_K_SPLITS", 0);          // for experiments
-    if (forced >= 1) return std::min(std::min(forced, 8), std::max(1, KT / 4));
     if (tiles >= 2 * cus) return 1;
     static const int cand[7] = {1, 2, 3, 4, 5, 6, 8};
     int best = 1;
@@ -686,6 +691,41 @@ lpq_status lpq_stage_linears(const lpq_layer* layers, int32_t n_layers, lpq_phas
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     return phase == LPQ_DECODE ? run_decode(calls, M, stream) : run_prefill(calls, M, stream);
+}
+
+lpq_status lpq_workspace_policy(size_t have_bytes, int32_t reserved, size_t need_bytes, size_t* alloc_bytes)
+{
+    if (!alloc_bytes) return LPQ_ERR_NULL;
+    return workspace_policy(have_bytes, reserved != 0, need_bytes, alloc_bytes);
+}
+
+lpq_status lpq_workspace_reserve(size_t bytes)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_ws.mu);
+    if (g_ws.bytes[dev] < bytes) {
+        lpq_status st = workspace_grow(dev, bytes);
+        if (st != LPQ_OK) return st;
+    }
+    g_ws.reserved[dev] = true;
+    return LPQ_OK;
+}
+
+size_t lpq_workspace_bytes(void)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    std::lock_guard<std::mutex> lock(g_ws.mu);
+    return g_ws.bytes[dev];
+}
+
+lpq_status lpq_set_decode_routing(int32_t rows_max_mib, int32_t rows_tiles)
+{
+    if (rows_max_mib > 4096 || (rows_tiles > 0 && (rows_tiles < 2 || rows_tiles > 5))) return LPQ_ERR_SHAPE;
+    g_rows_max_mb.store(rows_max_mib < 0 ? 192 : rows_max_mib);
+    g_rows_tiles.store(rows_tiles < 0 ? 0 : rows_tiles);
+    return LPQ_OK;
 }
 
 const char* lpq_status_str(lpq_status status)

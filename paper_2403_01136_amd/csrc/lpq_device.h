@@ -195,6 +195,55 @@ __device__ __forceinline__ h8 unpack_subnormal_step(const WRaw<V>& w, int j)
     }
 }
 
+// One MFMA step (32 columns: j) of a tile as integer-valued fp16 codes (the 0x6400 mantissa trick above).
+template <int V>
+__device__ __forceinline__ h8 unpack_codes_step(const WRaw<V>& w, int j)
+{
+    constexpr uint32_t MAGIC = 0x64006400u;
+    uint32_t magic_v;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
+    if constexpr (V == V_W4) {
+        const uint32_t q = w.q[j], t = q >> 8;
+        const h2 p0 = magic_to_int(and_or(q, 0x000F000Fu, magic_v), 0);
+        const h2 p1 = magic_to_int(and_or(q, 0x00F000F0u, magic_v), 4);
+        const h2 p2 = magic_to_int(and_or(t, 0x000F000Fu, magic_v), 0);
+        const h2 p3 = magic_to_int(and_or(t, 0x00F000F0u, magic_v), 4);
+        const h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+        return o;
+    } else if constexpr (V == V_W3) {
+        h2 pr[4];                                   // pairs P = 4*j .. 4*j + 3
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int P = 4 * j + k;
+            if (P < 15) {
+                const int i = P / 5, f = P % 5, ff = f % 3;        // fields 3, 4 sit at bits 9, 12: shift them down first
+                const uint32_t src = (f >= 3) ? (w.q[i] >> 9) : w.q[i];
+                pr[k] = magic_to_int(and_or(src, 0x00070007u << (3 * ff), magic_v), 3 * ff);
+            } else {
+                uint32_t u = and_or(w.q[0] >> 15, 0x00010001u, magic_v);
+                u = and_or(w.q[1] >> 14, 0x00020002u, u);
+                u = and_or(w.q[2] >> 13, 0x00040004u, u);
+                pr[k] = magic_to_int(u, 0);
+            }
+        }
+        const h8 o = {pr[0][0], pr[0][1], pr[1][0], pr[1][1], pr[2][0], pr[2][1], pr[3][0], pr[3][1]};
+        return o;
+    } else if constexpr (V == V_W8 || V == V_I8) {
+        constexpr uint32_t M8 = 0x64646464u;
+        const _Float16 off = (V == V_I8) ? (_Float16)1152.0f : (_Float16)1024.0f;   // 1024 (+128 for signed)
+        uint32_t a = w.q[j >> 1][2 * (j & 1)], b = w.q[j >> 1][2 * (j & 1) + 1];
+        if constexpr (V == V_I8) { a ^= 0x80808080u; b ^= 0x80808080u; }           // two's complement -> offset binary
+        const h2 p0 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00050004u)) - splat(off);
+        const h2 p1 = as_h2(__builtin_amdgcn_perm(a, M8, 0x00070006u)) - splat(off);
+        const h2 p2 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00050004u)) - splat(off);
+        const h2 p3 = as_h2(__builtin_amdgcn_perm(b, M8, 0x00070006u)) - splat(off);
+        const h8 o = {p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+        return o;
+    } else {
+        return __builtin_bit_cast(h8, w.q[j]);
+    }
+}
+
 // The same for two MFMA steps only (j = 2*half, 2*half + 1): the compute-bound kernels build their
 // operands half a 128-column step at a time to keep 32 instead of 64 operand registers live.
 // `piece8`: for the 8-bit variants, which of w.q[] holds the 16-byte piece of this half (callers that

@@ -148,3 +148,37 @@ def test_entry_points_validate_before_touching_the_device():
     for i in range(9):
         assert isinstance(lpq.status_str(i), str) and lpq.status_str(i)
     assert lpq.status_str(99) == "unknown status"
+
+
+def test_workspace_growth_policy():
+    """The per-device workspace never frees a block it has handed out: a larger need allocates a new block
+    (need + 25 %, at least 8 MiB), a need that fits reuses the block, and once a reservation is in force a
+    larger need is an error instead of an allocation.  (Pure host function: what the library does on a device
+    is this policy followed by one hipMalloc.)"""
+    MiB = 1 << 20
+    assert lpq.lpq_workspace_policy(0, False, 1) == 8 * MiB                    # first use: the floor
+    assert lpq.lpq_workspace_policy(8 * MiB, False, 8 * MiB) == 0              # fits: reuse
+    assert lpq.lpq_workspace_policy(8 * MiB, False, 8 * MiB + 1) == 8 * MiB + 1 + (8 * MiB + 1) // 4
+    assert lpq.lpq_workspace_policy(8 * MiB, False, 64 * MiB) == 80 * MiB      # growth leaves headroom
+    assert lpq.lpq_workspace_policy(80 * MiB, True, 80 * MiB) == 0             # reserved and large enough
+    with pytest.raises(lpq.LpqError) as err:
+        lpq.lpq_workspace_policy(80 * MiB, True, 80 * MiB + 1)                 # reserved: no growth
+    assert err.value.status == 6
+    assert lpq.load_library().lpq_workspace_policy(0, 0, 1, None) == 1
+    # a sequence of needs never shrinks the block and allocates only when a need exceeds it
+    have, allocs = 0, 0
+    for need in (1, 4 * MiB, 9 * MiB, 3 * MiB, 11 * MiB, 12 * MiB, 200 * MiB, 10 * MiB):
+        a = lpq.lpq_workspace_policy(have, False, need)
+        if a:
+            assert a >= need and a > have
+            have, allocs = a, allocs + 1
+        assert have >= need
+    assert allocs == 4
+
+
+def test_decode_routing_arguments():
+    lib = lpq.load_library()
+    assert lib.lpq_set_decode_routing(0, 0) == 0 and lib.lpq_set_decode_routing(-1, 5) == 0
+    for mib, tiles in ((5000, 0), (192, 1), (192, 6)):
+        assert lib.lpq_set_decode_routing(mib, tiles) == 4
+    assert lib.lpq_set_decode_routing(-1, -1) == 0

@@ -5,8 +5,8 @@ lpq_stage_linears exactly as bench.py does.  The oracle then recomputes, from th
   - the packed bytes, scales and zeros of sampled 64-row bands of every linear (bit-exact), and
   - the outputs of sampled (token, output row) pairs: all rows of those bands x sampled tokens,
 so every linear of every layer is checked at its real shape; one Freivalds projection per storage
-variant covers every output column of a linear.  Other configurations are checked the same way on
-one layer per distinct (bits, scheme) of their stage."""
+variant (and decode micro-batch) covers every output column of a linear.  Every configuration runs as a
+whole stage at every micro-batch of its sweep."""
 import numpy as np
 import pytest
 
@@ -80,12 +80,13 @@ def _freivalds(orc, w_dev, x_dev, y_dev, bits, scheme, seed, what):
     assert np.all(np.abs(got - want) <= tol), "%s: projection off by %.3e (tol %.3e)" % (what, np.abs(got - want).max(), tol.min())
 
 
-def _run_config(orc, cfg, layer_ids, Md, Mp, freivalds_linear="out"):
+def _run_config(orc, cfg, layer_ids, decode_Ms, Mp, freivalds_linear="out"):
+    """Build the stage once (as bench.py does), then run it at every decode micro-batch of `decode_Ms` and at the
+    prefill micro-batch Mp; every linear of every layer is checked at each of them."""
     import torch
     dev = torch.device("cuda:0")
     shapes = wl.linear_shapes(cfg)
     sub = dict(cfg, layers=[cfg["layers"][i] for i in layer_ids])
-    # decode-phase stage exactly as bench.py builds it
     layers, ws = [], []
     for li, (bits, scheme) in zip(layer_ids, sub["layers"]):
         lw, lws = {}, {}
@@ -96,7 +97,8 @@ def _run_config(orc, cfg, layer_ids, Md, Mp, freivalds_linear="out"):
             lws[name] = w
         layers.append(lw), ws.append(lws)
     seen_variants = set()
-    for phase, M in ((lpq.LPQ_DECODE, Md), (lpq.LPQ_PREFILL, Mp)):
+    phases = [(lpq.LPQ_DECODE, M) for M in decode_Ms] + [(lpq.LPQ_PREFILL, Mp)]
+    for pi, (phase, M) in enumerate(phases):
         xs, ys = [], []
         for li in layer_ids:
             x_h = wl.act_torch(M, cfg["h"], cfg["act_outliers"], dev, cfg["name"], li, "h", M)
@@ -110,25 +112,27 @@ def _run_config(orc, cfg, layer_ids, Md, Mp, freivalds_linear="out"):
                 what = "%s layer %d %s %d-bit phase %d M=%d" % (cfg["name"], li, name, bits, phase, M)
                 assert not torch.isnan(ys[i][name]).any(), what + ": output not fully written"
                 _check_linear(orc, layers[i][name], ws[i][name], xs[i][name], ys[i][name], bits, scheme,
-                              1000 * li + len(name), what, check_packed=(phase == lpq.LPQ_DECODE))
-            if (bits, scheme, phase) not in seen_variants:
-                seen_variants.add((bits, scheme, phase))
+                              1000 * li + len(name) + 17 * pi, what, check_packed=(pi == 0))
+            if (bits, scheme, phase, min(M, 64)) not in seen_variants:
+                seen_variants.add((bits, scheme, phase, min(M, 64)))
                 n = freivalds_linear
-                _freivalds(orc, ws[i][n], xs[i][n], ys[i][n], bits, scheme, 77 + li, "%s layer %d %s phase %d" % (cfg["name"], li, n, phase))
+                _freivalds(orc, ws[i][n], xs[i][n], ys[i][n], bits, scheme, 77 + li, "%s layer %d %s phase %d M=%d" % (cfg["name"], li, n, phase, M))
         del xs, ys
 
 
 def test_bench_config_full_stage(orc):
     """configs[1]: all 8 layers x 4 linears, decode M=16 and prefill M=2048, as bench.py runs them."""
     cfg = wl.CONFIGS[1]
-    _run_config(orc, cfg, list(range(len(cfg["layers"]))), cfg["decode_Ms"][0], cfg["prefill_M"])
+    _run_config(orc, cfg, list(range(len(cfg["layers"]))), cfg["decode_Ms"], cfg["prefill_M"])
 
 
-@pytest.mark.parametrize("ci,layer_ids,Md", [(2, [0, 1], 8), (2, [0, 1], 32), (3, [0, 5], 24), (4, [0], 1), (4, [0], 64)],
-                         ids=["opt30b_M8", "opt30b_M32", "opt66b_M24", "bloom176b_M1", "bloom176b_M64"])
-def test_other_configs_one_layer_per_variant(orc, ci, layer_ids, Md):
+@pytest.mark.parametrize("ci", [2, 3, 4], ids=["opt30b_12_layers", "opt66b_10_layers", "bloom176b_10_layers"])
+def test_other_configs_whole_stage(orc, ci):
+    """configs[2..4] as whole stages, at every decode micro-batch of their sweeps and at their prefill micro-batch:
+    the launch plan (even-share ranges, workgroups per XCD, launches of at most 40 linears -- configs[2] has 48 and
+    takes two) depends on the whole list of linears, so a sub-stage would test another plan."""
     cfg = wl.CONFIGS[ci]
-    _run_config(orc, cfg, layer_ids, Md, cfg["prefill_M"])
+    _run_config(orc, cfg, list(range(len(cfg["layers"]))), cfg["decode_Ms"], cfg["prefill_M"])
 
 
 @pytest.mark.parametrize("bits,scheme", [(3, 1), (4, 1), (8, 1), (8, 2), (16, 0)], ids=["w3", "w4", "w8", "i8", "f16"])

@@ -97,16 +97,17 @@ def test_load_quantize_pack_from_host(orc, bits, scheme, pinned):
 # ---- a3: decode linear ---------------------------------------------------------------------
 
 @pytest.fixture(params=["rows", "rows_3", "rows_5", "even_share"])
-def decode_kernel_choice(request, monkeypatch):
+def decode_kernel_choice(request):
     """Up to 64 token rows (32 per pass), a launch that streams little goes to the kernel that gives a group of 16-row tiles a
-    workgroup, a larger one to the even-share kernel; the limit is read at every call, so small shapes can reach both.
+    workgroup, a larger one to the even-share kernel; lpq_set_decode_routing moves the limit, so small shapes can reach both.
     rows_3 / rows_5 ask for groups of 3 / 5 tiles, which cut across the packed layout's 64-row blocks (the library
     falls back to 4 where the group size does not divide a linear's tiles: N = 320 has 20, N = 192 has 12)."""
     if request.param == "even_share":
-        monkeypatch.setenv("LPQ_DECODE_ROWS_MAX_MB", "0")
+        lpq.lpq_set_decode_routing(0, 0)
     elif request.param != "rows":
-        monkeypatch.setenv("LPQ_DECODE_ROWS_TILES", request.param[-1])
-    return request.param
+        lpq.lpq_set_decode_routing(-1, int(request.param[-1]))
+    yield request.param
+    lpq.lpq_set_decode_routing(-1, -1)
 
 
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)

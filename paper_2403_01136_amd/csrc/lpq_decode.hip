@@ -20,6 +20,7 @@
 // kernel, decode_rows_kernel further down: one workgroup per group of 16-row tiles whose waves split K, no LDS
 // staging, no fix-up pass.
 #include <algorithm>
+#include <mutex>
 
 #include "lpq_common.h"
 #include "lpq_device.h"

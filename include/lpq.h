@@ -200,6 +200,18 @@ lpq_status lpq_qlinear_fused(const lpq_qweight *w, const void *x, int32_t M, voi
 lpq_status lpq_stage_linears(const lpq_layer *layers, int32_t n_layers, lpq_phase phase, int32_t M,
                              const lpq_layer_io *io, void *hip_stream);
 
+/* lpq_stage_linears for callers that cannot allocate device memory while they run: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same results, but the
+ * fp32 partial tiles of the launches live in a static 32 MiB array inside the library (one copy per device, held
+ * until the process ends) instead of the growing workspace, and the call never allocates or frees.  That array
+ * covers every decode-phase launch of up to 32 token rows, and a prefill-phase call none of whose launches is split
+ * over K (stage-wide launches are not); a call that would need more returns LPQ_ERR_BUFSIZE and launches nothing
+ * further.  All calls on a device share the array, which keeps the last call's contents (nothing in it has to
+ * start at zero: every partial tile read was written by the same call); calls that overlap on one device race.
+ * Errors: as lpq_stage_linears, plus BUFSIZE as above. */
+lpq_status lpq_stage_linears_noalloc(const lpq_layer *layers, int32_t n_layers, lpq_phase phase, int32_t M,
+                                     const lpq_layer_io *io, void *hip_stream);
+
 /* ---- The rest of the decoder layer (beyond the hot path of the four linears) -------------------------
  * The published pre-LayerNorm decoder block of the paper's models, with the KV cache reserved for
  * max_seq = s + n positions per sequence (Sec. 4.1, "KV Storage Modeling"; Sec. 5):

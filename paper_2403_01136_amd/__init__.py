@@ -16,7 +16,7 @@ LPQ_PREFILL, LPQ_DECODE = 0, 1
 LPQ_OK = 0
 LINEARS = ("qkv", "out", "fc1", "fc2")
 EXPORTS = ("lpq_packed_sizes", "lpq_quantize_pack", "lpq_quantize_pack_rows", "lpq_load_quantize_pack",
-           "lpq_qlinear_prefill", "lpq_qlinear_decode", "lpq_qlinear_fused", "lpq_stage_linears", "lpq_layernorm",
+           "lpq_qlinear_prefill", "lpq_qlinear_decode", "lpq_qlinear_fused", "lpq_stage_linears", "lpq_stage_linears_noalloc", "lpq_layernorm",
            "lpq_kv_append", "lpq_attention", "lpq_decoder_layer_workspace", "lpq_decoder_layer", "lpq_variance_indicator",
            "lpq_mem_embedding_bytes", "lpq_mem_layer_bytes", "lpq_mem_kv_bytes", "lpq_latency_fit", "lpq_latency_predict",
            "lpq_plan_objective", "lpq_plan_adabits", "lpq_plan_bitwidth_transfer",
@@ -100,6 +100,7 @@ def load_library():
         L.lpq_qlinear_prefill.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, vp]
         L.lpq_qlinear_decode.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, vp]
         L.lpq_stage_linears.argtypes = [ctypes.POINTER(lpq_layer), i32, ctypes.c_int, i32, ctypes.POINTER(lpq_layer_io), vp]
+        L.lpq_stage_linears_noalloc.argtypes = [ctypes.POINTER(lpq_layer), i32, ctypes.c_int, i32, ctypes.POINTER(lpq_layer_io), vp]
         L.lpq_qlinear_fused.argtypes = [ctypes.POINTER(lpq_qweight), vp, i32, vp, ctypes.POINTER(lpq_epilogue), ctypes.c_int, vp]
         L.lpq_variance_indicator.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp]
         L.lpq_layernorm.argtypes = [vp, vp, vp, ctypes.c_float, i32, i32, vp, vp]
@@ -363,6 +364,12 @@ class Stage:
 def lpq_stage_linears(stage, phase, stream=None):
     """Run all 4 * n_layers linears of a Stage in the given phase (LPQ_PREFILL / LPQ_DECODE)."""
     _check(load_library().lpq_stage_linears(stage.layers, stage.n, phase, stage.M, stage.io, _stream(stream)), "lpq_stage_linears")
+
+
+def lpq_stage_linears_noalloc(stage, phase, stream=None):
+    """lpq_stage_linears with the partial sums in the library's static scratch array: allocates nothing."""
+    _check(load_library().lpq_stage_linears_noalloc(stage.layers, stage.n, phase, stage.M, stage.io, _stream(stream)),
+           "lpq_stage_linears_noalloc")
 
 
 # ---- cost models and planner: host arrays in, host arrays out (numpy only carries the buffers) -------------------

@@ -107,7 +107,7 @@ lpq_status workspace_grow(int dev, size_t want)      // g_ws.mu held
     return LPQ_OK;
 }
 
-lpq_status workspace(size_t need, float** out)
+lpq_status library_workspace(size_t need, float** out)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LPQ_ERR_DEVICE;
@@ -117,6 +117,19 @@ lpq_status workspace(size_t need, float** out)
     if (st != LPQ_OK) return st;
     if (alloc && (st = workspace_grow(dev, alloc)) != LPQ_OK) return st;
     *out = static_cast<float*>(g_ws.ptr[dev]);
+    return LPQ_OK;
+}
+
+// Partial sums of a call: the library's own workspace, or -- for the entry point that must not allocate -- the
+// device's static scratch array (a larger need is an error there, never an allocation).
+lpq_status workspace(bool static_ws, size_t need, float** out)
+{
+    if (!static_ws) return library_workspace(need, out);
+    void* p = nullptr;
+    size_t bytes = 0;
+    if (static_scratch(&p, &bytes) != hipSuccess) { (void)hipGetLastError(); return LPQ_ERR_DEVICE; }
+    if (need > bytes) return LPQ_ERR_BUFSIZE;
+    *out = static_cast<float*>(p);
     return LPQ_OK;
 }
 
@@ -207,7 +220,7 @@ struct LinearCall {
 // Decode-phase dispatch of a list of independent linears: grouped launches of at most
 // MAX_LIN_PER_LAUNCH linears, 64 token rows per pass, each launch one round of equally loaded
 // workgroups (see lpq_decode.hip).
-lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream)
+lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream, bool static_ws = false)
 {
     const size_t n = calls.size();
     const size_t n_launch = (n + MAX_LIN_PER_LAUNCH - 1) / MAX_LIN_PER_LAUNCH;
@@ -219,7 +232,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
     const int tok_rows = std::min(64, (M + 15) / 16 * 16);
     const int slot_floats = tok_rows * waves * 64;
     float* ws = nullptr;
-    st = workspace((size_t)2 * n_blocks * slot_floats * sizeof(float), &ws);
+    st = workspace(static_ws, (size_t)2 * n_blocks * slot_floats * sizeof(float), &ws);
     if (st != LPQ_OK) return st;
     for (size_t li = 0; li < n_launch; ++li) {
         DecodeArgs a;
@@ -310,7 +323,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
                 }
                 if (blocks > 0x7fffffffLL || partial_floats > 0x7fffffffLL) return LPQ_ERR_UNSUPPORTED;
                 if (partial_floats) {
-                    st = workspace((size_t)partial_floats * sizeof(float), &ws);
+                    st = workspace(static_ws, (size_t)partial_floats * sizeof(float), &ws);
                     if (st != LPQ_OK) return st;
                 }
                 p.partial = ws;
@@ -381,7 +394,7 @@ int prefill_k_splits(int tiles, int KT, int32_t M, int32_t N, int cus)
 
 // Prefill-phase dispatch of a list of independent linears: one grouped launch per storage variant
 // (and per MAX_PREFILL_LIN linears), tiles of the longest-K linears first.
-lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream)
+lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream, bool static_ws = false)
 {
     int cus = 0;
     lpq_status cst = device_cus(&cus);
@@ -429,7 +442,7 @@ lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStrea
             a.total_tiles = (int32_t)tiles;
             if (partial_floats) {
                 float* ws = nullptr;
-                lpq_status st = workspace(partial_floats * sizeof(float), &ws);
+                lpq_status st = workspace(static_ws, partial_floats * sizeof(float), &ws);
                 if (st != LPQ_OK) return st;
                 for (int i = 0; i < a.n_lin; ++i) {
                     if (a.lin[i].k_splits <= 1) continue;
@@ -461,7 +474,7 @@ lpq_status run_attention(const void* qkv, const lpq_layer_cfg* cfg, const lpq_la
         attention_decode_plan(n_seqs, cfg->n_heads, pos0 + 1, &range, &splits);
         const size_t floats = attention_decode_workspace_floats(n_seqs, cfg->n_heads, cfg->head_dim, splits);
         if (floats) {
-            lpq_status s = workspace(floats * sizeof(float), &part);
+            lpq_status s = workspace(false, floats * sizeof(float), &part);
             if (s != LPQ_OK) return s;
         }
     }
@@ -620,7 +633,7 @@ lpq_status lpq_variance_indicator(const void* w_fp16, int32_t K, int32_t N, cons
     if (K < 128 || K % 128 != 0 || N < 1 || M < 1) return LPQ_ERR_SHAPE;
     if (misaligned(w_fp16) || misaligned(x) || (reinterpret_cast<uintptr_t>(omega) & 7u)) return LPQ_ERR_ALIGN;
     float* ws = nullptr;
-    lpq_status st = workspace(indicator_workspace_bytes(N, (long)M * K / 8), &ws);
+    lpq_status st = workspace(false, indicator_workspace_bytes(N, (long)M * K / 8), &ws);
     if (st != LPQ_OK) return st;
     return launch_indicator(w_fp16, K, N, x, M, stochastic != 0, omega, ws, static_cast<hipStream_t>(hip_stream)) == hipSuccess
                ? LPQ_OK : LPQ_ERR_DEVICE;
@@ -671,8 +684,8 @@ lpq_status lpq_qlinear_fused(const lpq_qweight* w, const void* x, int32_t M, voi
                                 : run_decode(calls, M, static_cast<hipStream_t>(hip_stream));
 }
 
-lpq_status lpq_stage_linears(const lpq_layer* layers, int32_t n_layers, lpq_phase phase, int32_t M, const lpq_layer_io* io,
-                             void* hip_stream)
+static lpq_status stage_linears(const lpq_layer* layers, int32_t n_layers, lpq_phase phase, int32_t M, const lpq_layer_io* io,
+                                void* hip_stream, bool static_ws)
 {
     if (!layers || !io) return LPQ_ERR_NULL;
     if (n_layers < 1 || n_layers > 4096) return LPQ_ERR_SHAPE;
@@ -690,7 +703,19 @@ lpq_status lpq_stage_linears(const lpq_layer* layers, int32_t n_layers, lpq_phas
         }
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    return phase == LPQ_DECODE ? run_decode(calls, M, stream) : run_prefill(calls, M, stream);
+    return phase == LPQ_DECODE ? run_decode(calls, M, stream, static_ws) : run_prefill(calls, M, stream, static_ws);
+}
+
+lpq_status lpq_stage_linears(const lpq_layer* layers, int32_t n_layers, lpq_phase phase, int32_t M, const lpq_layer_io* io,
+                             void* hip_stream)
+{
+    return stage_linears(layers, n_layers, phase, M, io, hip_stream, false);
+}
+
+lpq_status lpq_stage_linears_noalloc(const lpq_layer* layers, int32_t n_layers, lpq_phase phase, int32_t M, const lpq_layer_io* io,
+                                     void* hip_stream)
+{
+    return stage_linears(layers, n_layers, phase, M, io, hip_stream, true);
 }
 
 lpq_status lpq_workspace_policy(size_t have_bytes, int32_t reserved, size_t need_bytes, size_t* alloc_bytes)

@@ -112,6 +112,8 @@ size_t tile_bytes_of(int variant);
 hipError_t launch_quantize_pack(const void* w_rows, const lpq_qdesc& d, long row0, long n_rows, const lpq_qweight& out, hipStream_t s);
 hipError_t launch_unpack_dequant(const lpq_qweight& w, float* out, hipStream_t s);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
+// device address and size of the static scratch array of the current device (for the entry point that allocates nothing)
+hipError_t static_scratch(void** ptr, size_t* bytes);
 hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s);     // small launches, M <= 32: cum_weight = workgroups before
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);      // both kernels, if any linear is K-split
 int prefill_tokens_per_tile(int variant, int M);

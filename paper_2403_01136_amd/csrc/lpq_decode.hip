@@ -854,16 +854,55 @@ __global__ __launch_bounds__(256) void decode_rows_reduce_kernel(const DecodeArg
 
 }  // namespace
 
+}  // namespace lpq
+
+// Scratch of the entry point that allocates nothing (lpq_stage_linears_noalloc): the fp32 partial tiles that the
+// library otherwise keeps in its growing workspace.  32 MiB per device, held until the process ends; it covers every
+// decode launch of up to 32 token rows (2 slots x 256 workgroups x 32 rows x 512 columns x 4 bytes).  Nothing in it
+// has to start at zero: every partial tile that is read was written earlier in the same call.
+constexpr size_t LPQ_SCRATCH_BYTES = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[LPQ_SCRATCH_BYTES];
+
+namespace lpq {
+
+// In host code `scratch` is only a handle for the symbol; its address on the current device comes from the runtime,
+// once per device (each device has its own copy of the array).
+hipError_t static_scratch(void** ptr, size_t* bytes)
+{
+    static std::mutex mu;
+    static void* addr[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    *bytes = LPQ_SCRATCH_BYTES;
+    return hipSuccess;
+}
+
 template <int TOK, int WAVES>
 static hipError_t launch_tok(const DecodeArgs& a, hipStream_t s)
 {
-    static bool attr_set = false;      // the slab may exceed the 64 KB that needs no opt-in
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<TOK, WAVES>),
+    // the slab may exceed the 64 KB that needs no opt-in: raise the kernel's limit once per device
+    static std::once_flag flags[64];
+    static hipError_t results[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::call_once(flags[dev], [&] {
+        results[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<TOK, WAVES>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(DecodeSmem<TOK, WAVES>));
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    });
+    if (results[dev] != hipSuccess) return results[dev];
     decode_kernel<TOK, WAVES><<<(unsigned)a.n_blocks, 64 * WAVES, sizeof(DecodeSmem<TOK, WAVES>), s>>>(a);
     return hipGetLastError();
 }

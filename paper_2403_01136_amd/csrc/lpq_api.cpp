@@ -154,10 +154,11 @@ lpq_status device_cus(int* out)
 std::atomic<int32_t> g_rows_max_mb{192};     // launches that stream at most this many MiB of codes take the small-launch kernel
 std::atomic<int32_t> g_rows_tiles{0};        // 2..5: force that many 16-row tiles per workgroup there; 0: the planner's choice
 
-// Wavefronts per decode workgroup: 4 for up to 16 token rows; 8 beyond, where the activation slab
-// is several times larger and one workgroup per CU shares it among twice the weight rows.  The
-// workgroups per launch are what the chip holds at once (two waves per SIMD).
-int decode_waves(int M) { return M <= 16 ? 4 : 8; }
+// Wavefronts per decode workgroup: eight, one workgroup per CU (two waves per SIMD), so that a step's activations
+// are staged once for 512 rows of W.  (Four waves and two workgroups per CU move twice the activation bytes from
+// L2 -- a third of the weight bytes at 3 bits and 16 token rows -- and measured 0.5-4 % slower on every configuration.)
+// The workgroups per launch are what the chip holds at once.
+int decode_waves(int /*M*/) { return 8; }
 
 lpq_status decode_block_count(int waves, int* out)
 {

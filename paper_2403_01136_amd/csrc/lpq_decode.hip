@@ -941,7 +941,8 @@ hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s)
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s)
 {
-    hipError_t e = a.waves == 8 ? launch_waves<8>(a, s) : launch_waves<4>(a, s);
+    if (a.waves != 8) return hipErrorInvalidValue;
+    hipError_t e = launch_waves<8>(a, s);
     if (e != hipSuccess) return e;
     if (a.n_blocks > 1) {
         const int m_cnt = std::min(64, a.M - a.m0);

@@ -395,13 +395,12 @@ int prefill_k_splits(int tiles, int KT, int32_t M, int32_t N, int cus)
 
 // Prefill-phase dispatch of a list of independent linears: one grouped launch per storage variant
 // (and per MAX_PREFILL_LIN linears), tiles of the longest-K linears first.
-lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream, bool static_ws = false)
+lpq_status run_prefill_rows(const std::vector<LinearCall>& calls, int32_t M, int BM, hipStream_t stream, bool static_ws)
 {
     int cus = 0;
     lpq_status cst = device_cus(&cus);
     if (cst != LPQ_OK) return cst;
     for (int variant = 0; variant < 5; ++variant) {
-        const int BM = prefill_tokens_per_tile(variant, M);
         const int m_blocks = (M + BM - 1) / BM;
         std::vector<const LinearCall*> mine;
         for (const LinearCall& c : calls)
@@ -411,7 +410,7 @@ lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStrea
             PrefillArgs a;
             a.M = M;
             a.n_lin = 0;
-            a.pad = 0;
+            a.tokens_per_tile = BM;
             long tiles = 0, launch_tiles = 0;
             size_t partial_floats = 0;
             for (size_t i = first; i < std::min(mine.size(), first + (size_t)MAX_PREFILL_LIN); ++i)
@@ -455,6 +454,30 @@ lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStrea
         }
     }
     return LPQ_OK;
+}
+
+// Tokens per tile.  256 as a rule: weights are fetched and unpacked once per token block.  A call of at most 128 rows
+// has one block either way and takes 128-token tiles (half the matrix instructions per step).  A call of 1024 rows
+// or more whose last block of 256 would hold at most 128 rows pays a full tile of matrix instructions for that block
+// (1100 rows cost what 1280 do): there the tail runs as launches of its own with 128-token tiles -- measured on an
+// OPT-13B layer's four linears, 11-19 % less time at 1100, 1152, 1600, 2100 and 3200 rows.  Below 1024 rows a call
+// is short of tiles either way, and both a tail launch and 128-token tiles throughout measured slower than the
+// ragged block (384 rows: 0.45 against 0.41 ms), so it keeps 256-token tiles.
+lpq_status run_prefill(const std::vector<LinearCall>& calls, int32_t M, hipStream_t stream, bool static_ws = false)
+{
+    const int32_t tail = M % 256, body = M - tail;
+    if (M <= 128) return run_prefill_rows(calls, M, 128, stream, static_ws);
+    if (tail == 0 || tail > 128) return run_prefill_rows(calls, M, 256, stream, static_ws);
+    if (M < 1024) return run_prefill_rows(calls, M, 256, stream, static_ws);
+    lpq_status st = run_prefill_rows(calls, body, 256, stream, static_ws);
+    if (st != LPQ_OK) return st;
+    std::vector<LinearCall> rest(calls);
+    for (LinearCall& c : rest) {
+        c.x = static_cast<const uint16_t*>(c.x) + (size_t)body * c.w->d.K;
+        c.y = static_cast<uint16_t*>(c.y) + (size_t)body * c.w->d.N;
+        if (c.residual) c.residual = static_cast<const uint16_t*>(c.residual) + (size_t)body * c.w->d.N;
+    }
+    return run_prefill_rows(rest, tail, 128, stream, static_ws);
 }
 
 lpq_status check_attention_args(const lpq_layer_cfg* cfg, const lpq_layer_state* st, int32_t n_seqs, int32_t T, int32_t pos0)

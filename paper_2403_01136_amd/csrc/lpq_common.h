@@ -97,7 +97,8 @@ __host__ __device__ inline int prefill_xcd_tiles(int m_blocks, int n_blocks, int
 enum { MAX_PREFILL_LIN = 40 };   // keeps PrefillArgs under 4 KB of kernel arguments
 
 struct PrefillArgs {
-    int32_t n_lin, M, total_tiles, pad;
+    int32_t n_lin, M, total_tiles;
+    int32_t tokens_per_tile;       // 128 or 256
     PrefillLin lin[MAX_PREFILL_LIN];
 };
 
@@ -116,7 +117,6 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t s);
 hipError_t static_scratch(void** ptr, size_t* bytes);
 hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s);     // small launches, M <= 32: cum_weight = workgroups before
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s);      // both kernels, if any linear is K-split
-int prefill_tokens_per_tile(int variant, int M);
 // variance indicator (lpq_indicator.hip)
 size_t indicator_workspace_bytes(int N, long n8);
 hipError_t launch_indicator(const void* w, int K, int N, const void* x, int M, int stochastic, double* omega, void* ws, hipStream_t s);

@@ -699,12 +699,10 @@ hipError_t launch_tiles(const PrefillArgs& a, hipStream_t s)
 template <int V>
 hipError_t launch_variant(const PrefillArgs& a, hipStream_t s)
 {
-    return prefill_tokens_per_tile(V, a.M) == 128 ? launch_tiles<V, 128>(a, s) : launch_tiles<V, 256>(a, s);
+    return a.tokens_per_tile == 128 ? launch_tiles<V, 128>(a, s) : launch_tiles<V, 256>(a, s);
 }
 
 }  // namespace
-
-int prefill_tokens_per_tile(int /*variant*/, int M) { return M <= 128 ? 128 : 256; }
 
 hipError_t launch_prefill(int variant, const PrefillArgs& a, hipStream_t s)
 {

@@ -143,6 +143,58 @@ def test_decoder_layer_prefill_then_decode(orc, bits, scheme, act, alibi):
         pos += T
 
 
+def test_decoder_layer_at_the_benchmark_shape(orc):
+    """One 4-bit OPT-13B-shaped layer (h = 5120, 40 heads of 128, f = 20480) at the two points bench.py and the cost
+    model time: a prefill of 4 prompts x 512 tokens, and a decode step of 16 sequences at position 562.  The oracle
+    layer runs on what it can finish in seconds: the first 48 tokens of the second prompt (a causal layer's output
+    for a token depends on no later token, so that prefix is a prefill of its own), and two of the sixteen sequences
+    of the decode step over the 562 cached positions (the cache is filled with seeded values)."""
+    import torch
+    B, H, d, f, s_len, n_gen = 4, 40, 128, 20480, 512, 100
+    h, S, bits, scheme = H * d, 640, 4, 1
+    st, ln, _ = make_state(16, H, d, S, "bench_shape")
+    r = rng("bench_shape")
+    shapes = {"qkv": (h, 3 * h), "out": (h, h), "fc1": (h, f), "fc2": (f, h)}
+    W = {n: f16(r.standard_normal((N, K), dtype=np.float32) * np.float32(1.0 / np.sqrt(K))) for n, (K, N) in shapes.items()}
+    bias = {n: f16(0.05 * r.standard_normal(N)) for n, (K, N) in shapes.items()}
+    layer = {n: lpq.lpq_quantize_pack(to_dev(W[n]), bits, scheme, bias=to_dev(bias[n])) for n in shapes}
+
+    def lin(name, a):
+        return orc.qlinear(a.astype(np.float16), W[name], bits, scheme, bias[name])
+
+    def compare(y_rows, ref, what):
+        yd = y_rows.astype(np.float64)
+        rel = np.linalg.norm(yd - ref) / np.linalg.norm(ref)
+        assert np.all(np.isfinite(yd)) and rel <= 2e-3, "%s rel-L2 %.3e" % (what, rel)
+        assert np.abs(yd - ref).max() <= 1e-2 * np.abs(ref).max(), what
+
+    # prefill: 4 x 512 tokens
+    x = f16(r.standard_normal((B * s_len, h), dtype=np.float32))
+    y, ws = lpq.lpq_decoder_layer(layer, st, lpq.LPQ_PREFILL, B, s_len, 0, to_dev(x))
+    seq, T_chk = 1, 48
+    rows = slice(seq * s_len, seq * s_len + T_chk)
+    k_ref, vt_ref = np.zeros((1, H, S, d), np.float16), np.zeros((1, H, d, S), np.float16)
+    ref = OL.decoder_layer(x[rows], lin, ln[0], ln[1], k_ref, vt_ref, 1, T_chk, 0, H, 1e-5, "relu")
+    compare(y[rows].cpu().numpy(), ref, "prefill 4 x 512, prompt %d, first %d tokens" % (seq, T_chk))
+    kd = st.k_cache[seq, :, :T_chk].cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(kd - k_ref[0, :, :T_chk].astype(np.float64)) <= 2e-3 * np.linalg.norm(kd)
+
+    # decode: 16 sequences at position s + n / 2
+    n_seq, pos = 16, s_len + n_gen // 2
+    k0 = f16(r.standard_normal((n_seq, H, S, d), dtype=np.float32))
+    v0 = f16(r.standard_normal((n_seq, H, d, S), dtype=np.float32))
+    st.k_cache.copy_(to_dev(k0)), st.vt_cache.copy_(to_dev(v0))
+    xd = f16(r.standard_normal((n_seq, h), dtype=np.float32))
+    yd, _ = lpq.lpq_decoder_layer(layer, st, lpq.LPQ_DECODE, n_seq, 1, pos, to_dev(xd))
+    yd = yd.cpu().numpy()
+    for b in (0, 9):
+        kb, vb = k0[b:b + 1].copy(), v0[b:b + 1].copy()
+        ref = OL.decoder_layer(xd[b:b + 1], lin, ln[0], ln[1], kb, vb, 1, 1, pos, H, 1e-5, "relu")
+        compare(yd[b:b + 1], ref, "decode step, sequence %d of 16 at position %d" % (b, pos))
+        assert np.array_equal(u16(st.k_cache[b, :, pos]), kb[0, :, pos].view(np.uint16)) or \
+            np.linalg.norm(st.k_cache[b, :, pos].cpu().numpy().astype(np.float64) - kb[0, :, pos].astype(np.float64)) <= 2e-3 * np.linalg.norm(kb[0, :, pos].astype(np.float64))
+
+
 @pytest.mark.parametrize("stochastic", [False, True], ids=["deterministic", "stochastic"])
 @pytest.mark.parametrize("N,K,M", [(1, 128, 1), (70, 640, 33), (5120, 5120, 16), (333, 14336, 5)])
 def test_variance_indicator(N, K, M, stochastic):

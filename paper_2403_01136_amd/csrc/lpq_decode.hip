@@ -203,7 +203,10 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             // them, vector work between them is.  So the codes of MFMA step j + 1 are unpacked in the
             // same scheduling group as the matrix instructions of step j.
             h8 wj[2][RT];
-            const _Float16 one = (_Float16)1.0f;
+            // sum(x) comes from a matrix instruction against a block of ones -- for the grouped scheme against 2^-24 (the
+            // smallest fp16 subnormal), so that it carries the same factor as the codes' products and the scale needs no
+            // multiplication by 2^24 per tile and step: the accumulators then hold y * 2^-24 until the unit ends
+            const _Float16 one = SCHEME == SCH_ASYM ? __builtin_bit_cast(_Float16, (uint16_t)1) : (_Float16)1.0f;
             const h8 ones = {one, one, one, one, one, one, one, one};
             const f4 zero4 = {0, 0, 0, 0};
             f4 d[RT][MT], xs[MT];
@@ -240,11 +243,8 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             if constexpr (SCHEME == SCH_ASYM) {
 #pragma unroll
                 for (int t = 0; t < RT; ++t) {
-                    const uint32_t sp = b.s[t >> 1], zp = b.z[t >> 1];
-                    const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
-                    const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
-                    const float sf = (float)__builtin_bit_cast(_Float16, sh) * 16777216.0f;     // scale * 2^24
-                    const float zf = (float)__builtin_bit_cast(_Float16, zh);
+                    const float sf = (float)as_h2(b.s[t >> 1])[t & 1];
+                    const float zf = (float)as_h2(b.z[t >> 1])[t & 1];
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -359,6 +359,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                     for (int t = 0; t < RT; ++t) {
                         float a = acc[t][mt][v];
                         if constexpr (POST && SCHEME == SCH_SYM) a = a * 16777216.0f - 128.0f * xsum[mt][v];   // undo 2^-24 and the +128 offset
+                        if constexpr (POST && SCHEME == SCH_ASYM) a *= 16777216.0f;                            // undo 2^-24
                         val[t] = a * post[t];
                     }
                     if (!partial) {

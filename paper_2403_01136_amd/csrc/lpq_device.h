@@ -172,7 +172,10 @@ __device__ __forceinline__ h8 unpack_subnormal_step(const WRaw<V>& w, int j)
     if constexpr (V == V_W4) {
         constexpr uint32_t M4 = 0x000F000Fu;
         const uint32_t q = w.q[j];
-        const u32x4 o = {q & M4, (q >> 4) & M4, (q >> 8) & M4, (q >> 12) & M4};
+        // the top nibble of each half-word needs no mask: a packed 16-bit shift fills each half with zeros on its own
+        typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+        const u16x2 top = __builtin_bit_cast(u16x2, q) >> (uint16_t)12;
+        const u32x4 o = {q & M4, (q >> 4) & M4, (q >> 8) & M4, __builtin_bit_cast(uint32_t, top)};
         return __builtin_bit_cast(h8, o);
     } else if constexpr (V == V_W3) {
         constexpr uint32_t M3 = 0x00070007u;

@@ -329,8 +329,9 @@ __device__ __forceinline__ void apply_scale_zero(h8 v[4], _Float16 s, _Float16 z
 
 __device__ __forceinline__ f4 mfma16(h8 a, h8 b, f4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
 
-// 32x32x16 runs the matrix cores at twice the rate of 16x16x32 (measured: 2.4 vs 1.2 PFLOP/s), so the
-// compute-bound kernels use it.  Its B operand wants lane = row % 32 + 32 * (k half); two tiles in
+// 32x32x16 does twice the multiply-accumulates of 16x16x32 per operand register read (and per LDS operand read), at the
+// same rate per cycle (counters: 32 against 16-18 matrix-pipe cycles per instruction), so the compute-bound kernels
+// use it.  Its B operand wants lane = row % 32 + 32 * (k half); two tiles in
 // the 16x16x32 layout (lane = row % 16 + 16 * kq) become two such operands with one
 // v_permlane16_swap per register: afterwards `lo` holds {tile a kq0, tile b kq0, tile a kq2, tile b kq2}
 // and `hi` holds {tile a kq1, tile b kq1, tile a kq3, tile b kq3}, i.e. 32 rows x (k slots kq, kq+2).

@@ -5,7 +5,7 @@
 // One launch covers every linear of a stage that shares a storage variant: the launch's workgroups
 // are the BM x 256 output tiles of all those linears, longest K first, so the chip stays full until
 // the last few tiles instead of draining at the end of every linear.  The matrix instruction is
-// v_mfma_f32_32x32x16_f16 (twice the rate of 16x16x32 on this chip).  Two kernels, chosen per storage
+// v_mfma_f32_32x32x16_f16 (half the operand reads of 16x16x32 per multiply-accumulate).  Two kernels, chosen per storage
 // variant (launch_tiles):
 //
 // prefill_kernel (3- and 4-bit codes; every variant at 128-token tiles): a workgroup of four wavefronts,

@@ -202,7 +202,7 @@ lpq_status lpq_stage_linears(const lpq_layer *layers, int32_t n_layers, lpq_phas
 
 /* lpq_stage_linears for callers that cannot allocate device memory while they run: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same results, but the
- * fp32 partial tiles of the launches live in a static 32 MiB array inside the library (one copy per device, held
+ * fp32 partial tiles and activation group sums of the launches live in a static 36 MiB array inside the library (one copy per device, held
  * until the process ends) instead of the growing workspace, and the call never allocates or frees.  That array
  * covers every decode-phase launch of up to 32 token rows, and a prefill-phase call none of whose launches is split
  * over K (stage-wide launches are not); a call that would need more returns LPQ_ERR_BUFSIZE and launches nothing

@@ -210,6 +210,10 @@ void rows_plan(const LinDesc& L, int tok_tiles, int cus, int* tiles, int* splits
     }
 }
 
+// Bytes of a linear's group sums in a decode launch of up to 32 token rows (group_sums_kernel): per token row an fp16
+// pair per 128-column group, groups padded to a multiple of 16, and 16 bytes for the row's scale factors.
+size_t group_sums_bytes(int64_t K) { return (size_t)32 * (4 * (((size_t)K / 128 + 15) & ~(size_t)15) + 16); }
+
 struct LinearCall {
     const lpq_qweight* w;
     const void* x;
@@ -232,8 +236,18 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
     if (st != LPQ_OK) return st;
     const int tok_rows = std::min(64, (M + 15) / 16 * 16);
     const int slot_floats = tok_rows * waves * 64;
+    // after the partial tiles: the activations' group sums of one launch at up to 32 token rows per pass (see
+    // group_sums_kernel); launches and passes run one after the other on the stream and share the space
+    const size_t partial_bytes = ((size_t)2 * n_blocks * slot_floats * sizeof(float) + 255) & ~(size_t)255;
+    size_t sums_bytes = 0;
+    if (M % 64 >= 1 && M % 64 <= 32)
+        for (size_t li = 0; li < n_launch; ++li) {
+            size_t b = 0;
+            for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c) b += group_sums_bytes(calls[c].w->d.K);
+            sums_bytes = std::max(sums_bytes, b);
+        }
     float* ws = nullptr;
-    st = workspace(static_ws, (size_t)2 * n_blocks * slot_floats * sizeof(float), &ws);
+    st = workspace(static_ws, partial_bytes + sums_bytes, &ws);
     if (st != LPQ_OK) return st;
     for (size_t li = 0; li < n_launch; ++li) {
         DecodeArgs a;
@@ -246,7 +260,9 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         a.row_tiles = 4;
         a.pad = 0;
         a.partial = ws;
+        a.xsum16 = sums_bytes ? reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(ws) + partial_bytes) : nullptr;
         uint64_t total = 0;
+        size_t sums_off16 = 0;               // in 16-byte units
         for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c) {
             const lpq_qweight& w = *calls[c].w;
             LinDesc& L = a.lin[a.n_lin++];
@@ -258,7 +274,8 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
             L.bias = static_cast<const uint16_t*>(w.bias);
             L.residual = static_cast<const uint16_t*>(calls[c].residual);
             L.act = calls[c].act;
-            L.pad = 0;
+            L.aux = (int32_t)sums_off16;
+            sums_off16 += group_sums_bytes(w.d.K) / 16;
             L.K = w.d.K;
             L.N = w.d.N;
             L.variant = variant_of(w.d);
@@ -312,15 +329,15 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
                 for (int i = 0; i < p.n_lin; ++i) {
                     LinDesc& L = p.lin[i];
                     L.row_blocks = L.N / 16 / group_tiles(L);
-                    // K splits (L.pad) of a launch of several linears: only if it leaves most compute units without a
+                    // K splits (L.aux) of a launch of several linears: only if it leaves most compute units without a
                     // workgroup, and only down to 32 steps per workgroup
                     const int KT = L.K / 128;
                     const int want = (int)std::max<int64_t>(1, 320 / std::max<int64_t>(1, row_blocks));
-                    L.pad = splits1 > 0 ? splits1 : std::max(1, std::min(std::min(want, KT / 32), 8));
+                    L.aux = splits1 > 0 ? splits1 : std::max(1, std::min(std::min(want, KT / 32), 8));
                     L.step_weight = (uint32_t)partial_floats;             // float offset of this linear's partial sums
-                    if (L.pad > 1) partial_floats += (int64_t)L.pad * 16 * tok_tiles * L.N;
+                    if (L.aux > 1) partial_floats += (int64_t)L.aux * 16 * tok_tiles * L.N;
                     L.cum_weight = (uint64_t)blocks;
-                    blocks += (int64_t)L.row_blocks * L.pad;
+                    blocks += (int64_t)L.row_blocks * L.aux;
                 }
                 if (blocks > 0x7fffffffLL || partial_floats > 0x7fffffffLL) return LPQ_ERR_UNSUPPORTED;
                 if (partial_floats) {

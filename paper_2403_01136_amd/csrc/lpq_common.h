@@ -25,7 +25,8 @@ struct LinDesc {
     int32_t row_blocks;     // N / rows per wave (64; 32 for fp16 weights)
     int32_t row_superblocks;// ceil(row_blocks / waves per workgroup)
     int32_t act;            // lpq_activation applied to acc + bias (before the residual)
-    int32_t pad;
+    int32_t aux;            // stage-wide kernel: offset of the linear's group sums in DecodeArgs::xsum16, in 16-byte units;
+                            // small-launch kernel: number of K splits
 };
 
 enum { MAX_LIN_PER_LAUNCH = 40 };   // keeps DecodeArgs under 4 KB of kernel arguments
@@ -40,8 +41,10 @@ struct DecodeArgs {
     int32_t row_tiles, pad;              // small-launch kernel only: 16-row tiles per workgroup (2 .. 5; fp16 weights: at most 2)
     uint64_t total_weight;
     float* partial;
+    const uint16_t* xsum16;              // stage-wide kernel, up to 32 token rows: per-group sums of the activations (group_sums_kernel)
     LinDesc lin[MAX_LIN_PER_LAUNCH];
 };
+static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 // One linear of a grouped prefill launch: its output is cut into tiles of BM tokens x 256 rows of W.
 // Workgroup ids go round-robin over the chip's 8 XCDs (each with its own L2), so workgroup

@@ -16,6 +16,10 @@
 // registers, unpacks them there into MFMA B operands and multiplies them with the activations
 // (MFMA A operands), which the workgroup stages once through a double-buffered LDS slab.
 //
+// Up to 32 token rows per pass the scale is applied after the matrix cores, per 128-column group, and the zero term
+// (sum over groups of zero * sum of x) once per unit from the activations' group sums, which group_sums_kernel
+// computes in front of the launch.
+//
 // A launch that streams little (a single linear of a decoder layer, up to 32 token rows per pass) takes a second
 // kernel, decode_rows_kernel further down: one workgroup per group of 16-row tiles whose waves split K, no LDS
 // staging, no fix-up pass.
@@ -48,6 +52,9 @@ template <int TOK, int WAVES> struct PipeCfg {
 // 16-byte operand reads of 16 consecutive rows hit 16 different bank groups.
 template <int TOK, int WAVES> struct DecodeSmem { uint16_t x[2][TOK][PipeCfg<TOK, WAVES>::ROW_HALVES]; };
 
+// Halves per token row of a linear's group sums (see group_sums_kernel).
+__device__ __host__ __forceinline__ int group_sums_stride(int K) { return 2 * ((K / 128 + 15) & ~15) + 8; }
+
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -70,7 +77,7 @@ struct Chunk {
 // [s_begin, s_end), else as an fp32 partial tile in slot_first (the unit this range entered mid-way)
 // or slot_last (the unit it leaves mid-way) -- and cleared.
 template <int V, int TOK, int WAVES>
-__device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long s_begin, long s_end,
+__device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long s_begin, long s_end, const uint16_t* __restrict__ xsum16,
                                           float* __restrict__ slot_first, float* __restrict__ slot_last, DecodeSmem<TOK, WAVES>& sm)
 {
     constexpr int RT = DecodeCfg<V>::RT;
@@ -83,7 +90,8 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     constexpr int WANT = TOK == 32 ? 2 : (int)DecodeCfg<V>::DEPTH;
     constexpr int STAGES = WANT < CHUNK ? WANT : CHUNK;
     // vector-memory loads of one Stage: the tiles (one load per KB, the 768-byte 3-bit tile included) and scale + zero
-    constexpr int STAGE_LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) + (SCHEME == SCH_ASYM ? 2 : 0);
+    constexpr bool POST = TOK <= 32 && V != V_F16;   // scale and zero folded in after the matrix cores (see compute below)
+    constexpr int STAGE_LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) + (SCHEME == SCH_ASYM ? (POST ? 1 : 2) : 0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, kq = lane >> 4;
     const int KT = L.K / 128;
@@ -108,15 +116,12 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     auto row_block = [&](int sb) { return (long)sb * WAVES + wave; };
 
     f4 acc[RT][MT];                   // narrow path
-    f4 xsum[MT];                      // narrow path, per-row scheme only: sum of x over the unit's K range
     f16x accw[NP][MT2];               // wide path: [tile pair][32-token tile]
     auto clear_acc = [&]() {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            xsum[mt] = f4{0, 0, 0, 0};
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int t = 0; t < RT; ++t) acc[t][mt] = f4{0, 0, 0, 0};
-        }
 #pragma unroll
         for (int p = 0; p < NP; ++p)
 #pragma unroll
@@ -129,7 +134,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     // ---- weight pipeline: one Stage = everything one 128-column step needs from global memory
     struct Stage {
         WRaw<V> w[RT];
-        u32x2 s, z;          // fp16 scale / zero of the lane's four rows (tiles 0..3), grouped scheme only
+        u32x2 s, z;          // fp16 scale / zero of the lane's four rows (tiles 0..3), grouped scheme only (z: 64-token path only)
     };
     Stage st[STAGES];
     auto issue = [&](Stage& b, int sb, int kt) {
@@ -144,17 +149,17 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         if constexpr (SCHEME == SCH_ASYM) {
             const size_t idx = (size_t)kt * L.N + rbc * 64 + 4 * r;
             b.s = *reinterpret_cast<const u32x2*>(L.scales + idx);
-            b.z = *reinterpret_cast<const u32x2*>(L.zeros + idx);
+            if constexpr (!POST) b.z = *reinterpret_cast<const u32x2*>(L.zeros + idx);
         }
     };
     // Two ways to fold scale and zero in.  POST (up to 32 tokens): multiply raw codes (as fp16
     // subnormals, code * 2^-24) on the matrix cores per 128-column group, then acc += scale *
-    // (codes . x) + zero * sum(x) in fp32, with sum(x) from one extra MFMA against a block of ones
-    // -- unpacking a code is then a shift and a mask, and the fold costs 8 fp32 FMAs per tile and
-    // token tile instead of the int -> fp16 conversions and packed FMAs per weight.  Otherwise (64
-    // tokens, where the fp32 work has outgrown the saving): dequantise each weight to fp16 once,
-    // w~ = scale * code + zero.
-    constexpr bool POST = TOK <= 32 && V != V_F16;
+    // (codes . x) in fp32 -- unpacking a code is then a shift and a mask, and the fold costs 4 fp32
+    // FMAs per tile and token tile instead of the int -> fp16 conversions and packed FMAs per weight.
+    // The zero term, sum over groups of zero[n][g] * sum_g(x[m]), is itself a small matrix product
+    // (K / 128 deep): it is added once per unit, at its end, from the group sums that
+    // group_sums_kernel left in xsum16 (add_zero_term below).  Otherwise (64 tokens, where the fp32
+    // work has outgrown the saving): dequantise each weight to fp16 once, w~ = scale * code + zero.
     // MFMA A operand: 8 consecutive columns (16-byte group c16 of 128-column step `step`) of a token row
     auto x_operand = [&](int buf, int row, int step, int c16) {
         return *reinterpret_cast<const h8*>(&sm.x[buf][row][step * 128 + 8 * (c16 ^ (row & 15))]);
@@ -203,13 +208,8 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             // them, vector work between them is.  So the codes of MFMA step j + 1 are unpacked in the
             // same scheduling group as the matrix instructions of step j.
             h8 wj[2][RT];
-            // sum(x) comes from a matrix instruction against a block of ones -- for the grouped scheme against 2^-24 (the
-            // smallest fp16 subnormal), so that it carries the same factor as the codes' products and the scale needs no
-            // multiplication by 2^24 per tile and step: the accumulators then hold y * 2^-24 until the unit ends
-            const _Float16 one = SCHEME == SCH_ASYM ? __builtin_bit_cast(_Float16, (uint16_t)1) : (_Float16)1.0f;
-            const h8 ones = {one, one, one, one, one, one, one, one};
             const f4 zero4 = {0, 0, 0, 0};
-            f4 d[RT][MT], xs[MT];
+            f4 d[RT][MT];
 #pragma unroll
             for (int t = 0; t < RT; ++t) wj[0][t] = unpack_subnormal_step<V>(b.w[t], 0);
             h8 a[2][MT];
@@ -222,11 +222,6 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                 if (j < 3) {
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) a[(j + 1) & 1][mt] = x_operand(buf, 16 * mt + r, step, 4 * (j + 1) + kq);
-                }
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    if constexpr (SCHEME == SCH_ASYM) xs[mt] = mfma16(a[j & 1][mt], ones, j == 0 ? zero4 : xs[mt]);
-                    else                               xsum[mt] = mfma16(a[j & 1][mt], ones, xsum[mt]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -244,12 +239,10 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
 #pragma unroll
                 for (int t = 0; t < RT; ++t) {
                     const float sf = (float)as_h2(b.s[t >> 1])[t & 1];
-                    const float zf = (float)as_h2(b.z[t >> 1])[t & 1];
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            acc[t][mt][v] = __builtin_fmaf(sf, d[t][mt][v], __builtin_fmaf(zf, xs[mt][v], acc[t][mt][v]));
+                        for (int v = 0; v < 4; ++v) acc[t][mt][v] = __builtin_fmaf(sf, d[t][mt][v], acc[t][mt][v]);
                 }
             }
         } else {
@@ -341,6 +334,75 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         }
         if (!WIDE && rb < L.row_blocks) {
             const long nbase = (RT == 4) ? rb * 64 + 4 * r : (rb >> 1) * 64 + 4 * r + 2 * (rb & 1);
+            if constexpr (POST) {
+                // The accumulators hold y * 2^-24 without the zero term: the grouped scheme's sum over groups of
+                // zero[n][g] * sum_g(x[m]), the per-row scheme's -128 * sum(x[m]) for the offset of its codes.  That
+                // term is a matrix product over the groups this range covered, [tokens][groups] . [groups][rows], with
+                // each group sum as an fp16 pair hi + lo in two adjacent k slots, scaled per token row (see
+                // group_sums_kernel): bring the accumulators to y * scale, chain the product onto them, 16 groups
+                // per matrix instruction, then divide the scale out.
+                static_assert(RT == 4, "the zero term reads the zeros of a 64-row block");
+                const long u0 = (long)sb * KT;
+                const int g_lo = (int)(max(u0, s_begin) - u0), g_hi = (int)(min(u0 + KT, s_end) - u0);
+                const int stride = group_sums_stride(L.K);
+                const uint16_t* xs = xsum16 + (size_t)L.aux * 8;
+                const int cnt = min(TOK, M - m0);                            // token rows the sums were taken for
+                float undo[MT][4];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float* f = reinterpret_cast<const float*>(xs + (size_t)min(16 * mt + 4 * kq + v, cnt - 1) * stride + (stride - 8));
+                        const float pre = f[0];
+                        undo[mt][v] = f[1];
+#pragma unroll
+                        for (int t = 0; t < RT; ++t) acc[t][mt][v] *= pre;
+                    }
+                // CB matrix steps (16 groups each) per round of loads: a round costs a memory latency that nothing hides
+                constexpr int CB = TOK <= 16 ? 4 : 1;
+                const int c_last = (KT + 15) / 16 - 1;                       // the sums are padded to whole matrix steps
+                for (int c0 = g_lo >> 4; 16 * c0 < g_hi; c0 += CB) {
+                    h8 a[CB][MT];
+                    u32x2 z[CB][4];
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) {
+                        const int c = min(c0 + cb, c_last);
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            a[cb][mt] = *reinterpret_cast<const h8*>(xs + (size_t)min(16 * mt + r, cnt - 1) * stride + 32 * c + 8 * kq);
+                        if constexpr (SCHEME == SCH_ASYM) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                z[cb][i] = *reinterpret_cast<const u32x2*>(L.zeros + (size_t)min(16 * c + 4 * kq + i, KT - 1) * L.N + rb * 64 + 4 * r);
+                        }
+                    }
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) {
+                        u32x4 bz[RT];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int g = 16 * (c0 + cb) + 4 * kq + i;       // k slots 8 kq + 2 i and + 1
+                            const bool valid = g >= g_lo && g < g_hi;
+#pragma unroll
+                            for (int t = 0; t < RT; ++t) {
+                                uint32_t h = 0xd800u;                        // per-row scheme: -128
+                                if constexpr (SCHEME == SCH_ASYM) h = (t & 1) ? (z[cb][i][t >> 1] >> 16) : (z[cb][i][t >> 1] & 0xffffu);
+                                bz[t][i] = valid ? (h | (h << 16)) : 0u;
+                            }
+                        }
+#pragma unroll
+                        for (int t = 0; t < RT; ++t)
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt) acc[t][mt] = mfma16(a[cb][mt], __builtin_bit_cast(h8, bz[t]), acc[t][mt]);
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < RT; ++t)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[t][mt][v] *= undo[mt][v];
+            }
             float post[RT], bias[RT];
 #pragma unroll
             for (int t = 0; t < RT; ++t) {
@@ -357,10 +419,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                     float val[RT];
 #pragma unroll
                     for (int t = 0; t < RT; ++t) {
-                        float a = acc[t][mt][v];
-                        if constexpr (POST && SCHEME == SCH_SYM) a = a * 16777216.0f - 128.0f * xsum[mt][v];   // undo 2^-24 and the +128 offset
-                        if constexpr (POST && SCHEME == SCH_ASYM) a *= 16777216.0f;                            // undo 2^-24
-                        val[t] = a * post[t];
+                        val[t] = acc[t][mt][v] * post[t];
                     }
                     if (!partial) {
                         typedef _Float16 hv __attribute__((ext_vector_type(RT)));
@@ -459,6 +518,90 @@ __device__ __forceinline__ uint64_t range_begin(const DecodeArgs& a, int b)
     return a.total_weight * (uint64_t)b / (uint64_t)a.n_blocks;      // total_weight < 2^50, b < 2^13
 }
 
+// Group sums of the activations, for the zero term of decode_kernel at up to 32 token rows per pass.  Workgroup
+// (blockIdx.x = linear, blockIdx.y = row of the pass) adds x over each 128-column group of token row a.m0 + row (sixteen
+// lanes per group, a fixed order) and writes the sums as fp16 pairs for the matrix cores: sum * scale = hi + lo (lo = the
+// rounding error of hi), scale the power of two that brings the row's largest |sum| into [2^13, 2^14) -- so that rows of
+// tiny activations keep their bits and rows of large ones stay in range.  Layout of a row, group_sums_stride(K) halves
+// from out + 8 * aux: the pairs of groups 0 .. K/128 - 1, zero pairs up to a multiple of 16 groups (they meet zero
+// operands, but must not be NaN), then two floats, scale * 2^24 and 1 / scale.
+// The kernel is a round of memory latency in front of every decode launch, so a thread requests all it adds -- up to
+// GS_ROUNDS groups, K <= 65536 -- before it adds anything, and keeps the sums in registers for the second use; a longer
+// row is read twice.
+constexpr int GS_ROUNDS = 32, GS_BATCH = 8;
+
+__global__ __launch_bounds__(256) void group_sums_kernel(const DecodeArgs a, uint16_t* __restrict__ out)
+{
+    __shared__ float wmax[4];
+    const LinDesc& L = a.lin[blockIdx.x];
+    if (L.variant == V_F16) return;
+    const int row = blockIdx.y, tok = a.m0 + row;
+    const int KT = L.K / 128, GP = (KT + 15) & ~15, rounds = GP / 16;
+    uint16_t* dst = out + (size_t)L.aux * 8 + (size_t)row * group_sums_stride(L.K);
+    const int l16 = threadIdx.x & 15, g0 = threadIdx.x >> 4;
+    const uint16_t* src = L.x + (size_t)tok * L.K + 8 * l16;
+    auto add16 = [&](h8 v, bool valid) {              // a group's sum, the same value in all sixteen lanes
+        float sum = (((float)v[0] + (float)v[1]) + ((float)v[2] + (float)v[3])) + (((float)v[4] + (float)v[5]) + ((float)v[6] + (float)v[7]));
+        sum = valid ? sum : 0.0f;
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 16);
+        return sum;
+    };
+    auto group_sum = [&](int g) {
+        const h8 v = *reinterpret_cast<const h8*>(src + (size_t)min(g, KT - 1) * 128);
+        return add16(v, g < KT);
+    };
+    const bool fits = rounds <= GS_ROUNDS;
+    float sums[GS_ROUNDS];
+    float big = 0.0f;
+    if (fits) {
+#pragma unroll
+        for (int i0 = 0; i0 < GS_ROUNDS; i0 += GS_BATCH) {
+            if (i0 >= rounds) break;                                // wave-uniform
+            h8 v[GS_BATCH];
+#pragma unroll
+            for (int j = 0; j < GS_BATCH; ++j) v[j] = *reinterpret_cast<const h8*>(src + (size_t)min(g0 + 16 * (i0 + j), KT - 1) * 128);
+#pragma unroll
+            for (int j = 0; j < GS_BATCH; ++j) {
+                sums[i0 + j] = add16(v[j], g0 + 16 * (i0 + j) < KT);
+                big = fmaxf(big, fabsf(sums[i0 + j]));
+            }
+        }
+    } else {
+        for (int g = g0; g < GP; g += 16) big = fmaxf(big, fabsf(group_sum(g)));
+    }
+#pragma unroll
+    for (int o = 32; o >= 16; o >>= 1) big = fmaxf(big, __shfl_xor(big, o, 64));
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = big;
+    __syncthreads();
+    big = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    float scale = 1.0f;
+    if (big > 0.0f && big < __builtin_inff()) {
+        int ex;
+        (void)frexpf(big, &ex);                       // big = f * 2^ex, f in [0.5, 1)
+        scale = ldexpf(1.0f, max(-40, min(40, 14 - ex)));
+    }
+    auto store = [&](int g, float sum) {
+        const float scaled = sum * scale;
+        const _Float16 hi = (_Float16)scaled;
+        const _Float16 lo = (_Float16)(scaled - (float)hi);
+        if (l16 == 0 && g < GP)
+            reinterpret_cast<uint32_t*>(dst)[g] = (uint32_t)__builtin_bit_cast(uint16_t, hi) | ((uint32_t)__builtin_bit_cast(uint16_t, lo) << 16);
+    };
+    if (fits) {
+#pragma unroll
+        for (int i = 0; i < GS_ROUNDS; ++i)
+            if (i < rounds) store(g0 + 16 * i, sums[i]);
+    } else {
+        for (int g = g0; g < GP; g += 16) store(g, group_sum(g));
+    }
+    if (threadIdx.x == 0) {
+        float* f = reinterpret_cast<float*>(dst + 2 * GP);
+        f[0] = scale * 16777216.0f;
+        f[1] = 1.0f / scale;
+    }
+}
+
 template <int TOK, int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const DecodeArgs a)
 {
@@ -480,11 +623,11 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const Dec
         const long budget = (long)((hi - start + L.step_weight - 1) / L.step_weight);      // steps of this range from here
         const long s_end = min(steps, c.step + budget);
         switch (L.variant) {
-        case V_W3: run_range<V_W3, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
-        case V_W4: run_range<V_W4, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
-        case V_W8: run_range<V_W8, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
-        case V_I8: run_range<V_I8, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
-        default:   run_range<V_F16, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, slot_first, slot_last, sm); break;
+        case V_W3: run_range<V_W3, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        case V_W4: run_range<V_W4, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        case V_W8: run_range<V_W8, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        case V_I8: run_range<V_I8, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        default:   run_range<V_F16, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
         }
         c.step = s_end;
     }
@@ -619,7 +762,7 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
 // tiles through a ring of stages in registers together with the activations of those steps (read straight from
 // global memory: they are small and stay in L2; no LDS staging, no barrier in the loop), and the waves'
 // accumulators are added through LDS at the end, in wave order.  A linear with few tiles and a long K (the
-// second feed-forward matrix) is also split over L.pad workgroups per group, each taking a range of the steps
+// second feed-forward matrix) is also split over L.aux workgroups per group, each taking a range of the steps
 // and leaving fp32 sums in partial[split][16 MT][N] (at float offset L.step_weight of the launch's partial buffer)
 // for a small second kernel; otherwise there are no partial tiles and no second kernel.  L.row_blocks is the
 // linear's number of groups, a.lin[i].cum_weight the number of workgroups of the linears before i, a.n_blocks
@@ -642,7 +785,7 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
     const int KT = L.K / 128;
     const long g0 = rb * RT;                                        // first tile; tile g is tile g % 4 of 64-row block g / 4
     // the workgroup's steps [kt0, kt1): all of them, or the split's share (the first KT % splits take one more)
-    const int splits = L.pad, share = KT / splits, extra = KT % splits;
+    const int splits = L.aux, share = KT / splits, extra = KT % splits;
     const int kt0 = split * share + min(split, extra), kt1 = kt0 + share + (split < extra ? 1 : 0);
     const int n_w = kt1 - kt0 > wave ? (kt1 - kt0 - wave + WAVES - 1) / WAVES : 0;      // this wave's steps
     const uint16_t* __restrict__ xrow[MT];                          // token tile m holds rows 16 m .. 16 m + 15; rows past M repeat the last one
@@ -838,7 +981,7 @@ __global__ __launch_bounds__(256) void decode_rows_reduce_kernel(const DecodeArg
         const size_t e = 4 * q;
         const int n = (int)(e % L.N);
         f4 sum = *reinterpret_cast<const f4*>(partial + e);
-        for (int sp = 1; sp < L.pad; ++sp) sum += *reinterpret_cast<const f4*>(partial + sp * plane + e);
+        for (int sp = 1; sp < L.aux; ++sp) sum += *reinterpret_cast<const f4*>(partial + sp * plane + e);
         typedef _Float16 h4 __attribute__((ext_vector_type(4)));
         h4 res = {0, 0, 0, 0}, out;
         if (L.residual) res = *reinterpret_cast<const h4*>(L.residual + e);
@@ -858,10 +1001,11 @@ __global__ __launch_bounds__(256) void decode_rows_reduce_kernel(const DecodeArg
 }  // namespace lpq
 
 // Scratch of the entry point that allocates nothing (lpq_stage_linears_noalloc): the fp32 partial tiles that the
-// library otherwise keeps in its growing workspace.  32 MiB per device, held until the process ends; it covers every
-// decode launch of up to 32 token rows (2 slots x 256 workgroups x 32 rows x 512 columns x 4 bytes).  Nothing in it
-// has to start at zero: every partial tile that is read was written earlier in the same call.
-constexpr size_t LPQ_SCRATCH_BYTES = (size_t)32 << 20;
+// library otherwise keeps in its growing workspace, and the activations' group sums of a decode launch.  36 MiB per
+// device, held until the process ends; it covers every decode launch of up to 32 token rows (2 slots x 256 workgroups
+// x 32 rows x 512 columns x 4 bytes of partial tiles, and up to 4 MiB of group sums: 40 linears of K = 57344 take
+// 2.2 MiB).  Nothing in it has to start at zero: whatever is read was written earlier in the same call.
+constexpr size_t LPQ_SCRATCH_BYTES = (size_t)36 << 20;
 static __device__ __align__(256) unsigned char scratch[LPQ_SCRATCH_BYTES];
 
 namespace lpq {
@@ -932,7 +1076,7 @@ hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s)
 #undef LPQ_ROWS_CASE
     hipError_t e = hipGetLastError();
     for (int li = 0; li < a.n_lin && e == hipSuccess; ++li) {
-        if (a.lin[li].pad <= 1) continue;
+        if (a.lin[li].aux <= 1) continue;
         const size_t quads = (size_t)a.M * a.lin[li].N / 4;
         decode_rows_reduce_kernel<<<(unsigned)std::min<size_t>((quads + 255) / 256, 4096), 256, 0, s>>>(a, li);
         e = hipGetLastError();
@@ -943,6 +1087,17 @@ hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s)
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t s)
 {
     if (a.waves != 8) return hipErrorInvalidValue;
+    const int rows = a.M - a.m0;
+    if (rows <= 32) {       // the kernels for up to 32 token rows take the zero term from the activations' group sums
+        bool any = false;
+        for (int li = 0; li < a.n_lin; ++li) any = any || a.lin[li].variant != V_F16;
+        if (any) {
+            if (!a.xsum16) return hipErrorInvalidValue;
+            group_sums_kernel<<<dim3((unsigned)a.n_lin, (unsigned)rows), 256, 0, s>>>(a, const_cast<uint16_t*>(a.xsum16));
+            const hipError_t e0 = hipGetLastError();
+            if (e0 != hipSuccess) return e0;
+        }
+    }
     hipError_t e = launch_waves<8>(a, s);
     if (e != hipSuccess) return e;
     if (a.n_blocks > 1) {

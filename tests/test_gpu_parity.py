@@ -141,6 +141,43 @@ def test_decode_split_k_and_many_rows(orc, bits, scheme, M, decode_kernel_choice
     check_output(y, orc.qlinear(x, w, bits, scheme, bias), "decode split-K %d-bit M=%d" % (bits, M))
 
 
+@pytest.mark.parametrize("bits,scheme", [(3, 1), (4, 1), (8, 1), (8, 2)], ids=["w3", "w4", "w8", "i8sym"])
+def test_decode_zero_term_rows_of_unlike_magnitude(orc, bits, scheme):
+    """Up to 32 token rows the stage-wide kernel adds the zero term once per unit, as a matrix product with the activations'
+    group sums held as fp16 pairs scaled per token row.  Rows 2^-11 and 2^5 times the others in one micro-batch: every row
+    keeps the tolerance on its own, whatever its neighbours' scale."""
+    lpq.lpq_set_decode_routing(0, 0)
+    try:
+        N, K = 192, 2048
+        w = wl.weight_np(N, K, "zrow", bits, scheme)
+        for M in (7, 24):
+            x = wl.act_np(M, K, False, "zrow", M).astype(np.float32)
+            x *= np.array([2.0 ** -11, 1.0, 2.0 ** 5])[np.arange(M) % 3][:, None]
+            x = x.astype(np.float16)
+            y = lpq.lpq_qlinear_decode(lpq.lpq_quantize_pack(to_dev(w), bits, scheme), to_dev(x))
+            ref = orc.qlinear(x, w, bits, scheme)
+            for m in range(M):
+                check_output(y[m:m + 1], ref[m:m + 1], "decode %d-bit M=%d row %d" % (bits, M, m))
+    finally:
+        lpq.lpq_set_decode_routing(-1, -1)
+
+
+@pytest.mark.parametrize("bits,scheme", [(3, 1), (8, 2)], ids=["w3", "i8sym"])
+def test_decode_zero_term_very_long_rows(orc, bits, scheme):
+    """K = 66048 is 516 groups: more than a thread of the group-sum kernel keeps in registers, so it reads the row twice;
+    the 516 groups are also not a multiple of the 16 a matrix instruction of the zero term covers."""
+    lpq.lpq_set_decode_routing(0, 0)
+    try:
+        N, K = 128, 66048
+        w = wl.weight_np(N, K, "zlong", bits, scheme)
+        for M in (3, 18):
+            x = wl.act_np(M, K, True, "zlong", M)
+            y = lpq.lpq_qlinear_decode(lpq.lpq_quantize_pack(to_dev(w), bits, scheme), to_dev(x))
+            check_output(y, orc.qlinear(x, w, bits, scheme), "decode %d-bit M=%d K=%d" % (bits, M, K))
+    finally:
+        lpq.lpq_set_decode_routing(-1, -1)
+
+
 # ---- a4: prefill linear --------------------------------------------------------------------
 
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)

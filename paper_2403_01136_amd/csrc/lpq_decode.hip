@@ -40,9 +40,10 @@ template <int V> struct DecodeCfg { enum { RT = (V == V_F16) ? 2 : 4, DEPTH = (V
 // A launch is specialised on TOK, the token rows it covers: 16 or 32 (one or two 16-token tiles on the
 // 16x16x32 MFMA, scale and zero applied after the matrix cores) or 64 (32x32x16 MFMA at twice the
 // matrix-core rate, weights dequantised to fp16 in registers).  Activation staging: CHUNK 128-column steps per LDS
-// buffer, sized so that two buffers of every workgroup resident on a CU fill 128 KB of its LDS.
-template <int TOK, int WAVES> struct PipeCfg {
-    enum { FIT = 32 * WAVES / TOK, CHUNK = FIT < 8 ? FIT : 8 };
+// buffer: at most CAP (8, or 16 where a launch of up to 16 token rows asks for it), and at most what lets two buffers
+// of a workgroup fit 128 KB of the CU's LDS.
+template <int TOK, int WAVES, int CAP> struct PipeCfg {
+    enum { FIT = 32 * WAVES / TOK, CHUNK = FIT < CAP ? FIT : CAP };
     enum { ROW_HALVES = CHUNK * 128 };
     enum { XQ = TOK * CHUNK / 4 / WAVES };          // 1 KB global-to-LDS loads per wave and chunk
 };
@@ -50,7 +51,7 @@ template <int TOK, int WAVES> struct PipeCfg {
 // Token row `row` keeps the 16-byte column group c16 of each of its 128-column steps in slot
 // c16 ^ (row % 16) of that step: rows are a multiple of 256 bytes apart, and the swizzle makes the
 // 16-byte operand reads of 16 consecutive rows hit 16 different bank groups.
-template <int TOK, int WAVES> struct DecodeSmem { uint16_t x[2][TOK][PipeCfg<TOK, WAVES>::ROW_HALVES]; };
+template <int TOK, int WAVES, int CAP> struct DecodeSmem { uint16_t x[2][TOK][PipeCfg<TOK, WAVES, CAP>::ROW_HALVES]; };
 
 // Halves per token row of a linear's group sums (see group_sums_kernel).
 __device__ __host__ __forceinline__ int group_sums_stride(int K) { return 2 * ((K / 128 + 15) & ~15) + 8; }
@@ -76,16 +77,16 @@ struct Chunk {
 // the end of a unit the accumulators are stored -- as fp16 if the unit's whole K range lay inside
 // [s_begin, s_end), else as an fp32 partial tile in slot_first (the unit this range entered mid-way)
 // or slot_last (the unit it leaves mid-way) -- and cleared.
-template <int V, int TOK, int WAVES>
+template <int V, int TOK, int WAVES, int CAP>
 __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long s_begin, long s_end, const uint16_t* __restrict__ xsum16,
-                                          float* __restrict__ slot_first, float* __restrict__ slot_last, DecodeSmem<TOK, WAVES>& sm)
+                                          float* __restrict__ slot_first, float* __restrict__ slot_last, DecodeSmem<TOK, WAVES, CAP>& sm)
 {
     constexpr int RT = DecodeCfg<V>::RT;
     constexpr int SCHEME = VInfo<V>::SCHEME;
     constexpr bool WIDE = TOK > 32;                 // 32x32x16 path
     constexpr int MT = WIDE ? 1 : TOK / 16;         // narrow path: 16-token tiles
     constexpr int NP = RT / 2, MT2 = WIDE ? TOK / 32 : 1;      // wide path: tile pairs and 32-token tiles
-    constexpr int CHUNK = PipeCfg<TOK, WAVES>::CHUNK, XQ = PipeCfg<TOK, WAVES>::XQ;
+    constexpr int CHUNK = PipeCfg<TOK, WAVES, CAP>::CHUNK, XQ = PipeCfg<TOK, WAVES, CAP>::XQ;
     // 32-token launches keep two steps in flight per wave: their second token tile needs the registers
     constexpr int WANT = TOK == 32 ? 2 : (int)DecodeCfg<V>::DEPTH;
     constexpr int STAGES = WANT < CHUNK ? WANT : CHUNK;
@@ -602,11 +603,11 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const DecodeArgs a, uin
     }
 }
 
-template <int TOK, int WAVES>
+template <int TOK, int WAVES, int CAP>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const DecodeArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
-    DecodeSmem<TOK, WAVES>& sm = *reinterpret_cast<DecodeSmem<TOK, WAVES>*>(smem_raw);
+    DecodeSmem<TOK, WAVES, CAP>& sm = *reinterpret_cast<DecodeSmem<TOK, WAVES, CAP>*>(smem_raw);
     // Workgroup ids go round-robin over the 8 XCDs, each with its own L2.  XCD x takes the x-th eighth of the
     // ranges, so that a linear's activations are fetched into one or two L2s instead of all eight.
     const int b = (a.n_blocks & 7) == 0 ? (int)(blockIdx.x & 7) * (a.n_blocks >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
@@ -623,11 +624,11 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const Dec
         const long budget = (long)((hi - start + L.step_weight - 1) / L.step_weight);      // steps of this range from here
         const long s_end = min(steps, c.step + budget);
         switch (L.variant) {
-        case V_W3: run_range<V_W3, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
-        case V_W4: run_range<V_W4, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
-        case V_W8: run_range<V_W8, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
-        case V_I8: run_range<V_I8, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
-        default:   run_range<V_F16, TOK, WAVES>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        case V_W3: run_range<V_W3, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        case V_W4: run_range<V_W4, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        case V_W8: run_range<V_W8, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        case V_I8: run_range<V_I8, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        default:   run_range<V_F16, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
         }
         c.step = s_end;
     }
@@ -1033,7 +1034,7 @@ hipError_t static_scratch(void** ptr, size_t* bytes)
     return hipSuccess;
 }
 
-template <int TOK, int WAVES>
+template <int TOK, int WAVES, int CAP>
 static hipError_t launch_tok(const DecodeArgs& a, hipStream_t s)
 {
     // the slab may exceed the 64 KB that needs no opt-in: raise the kernel's limit once per device
@@ -1044,11 +1045,11 @@ static hipError_t launch_tok(const DecodeArgs& a, hipStream_t s)
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     std::call_once(flags[dev], [&] {
-        results[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<TOK, WAVES>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(DecodeSmem<TOK, WAVES>));
+        results[dev] = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<TOK, WAVES, CAP>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(DecodeSmem<TOK, WAVES, CAP>));
     });
     if (results[dev] != hipSuccess) return results[dev];
-    decode_kernel<TOK, WAVES><<<(unsigned)a.n_blocks, 64 * WAVES, sizeof(DecodeSmem<TOK, WAVES>), s>>>(a);
+    decode_kernel<TOK, WAVES, CAP><<<(unsigned)a.n_blocks, 64 * WAVES, sizeof(DecodeSmem<TOK, WAVES, CAP>), s>>>(a);
     return hipGetLastError();
 }
 
@@ -1056,7 +1057,14 @@ template <int WAVES>
 static hipError_t launch_waves(const DecodeArgs& a, hipStream_t s)
 {
     const int rows = a.M - a.m0;
-    return rows <= 16 ? launch_tok<16, WAVES>(a, s) : rows <= 32 ? launch_tok<32, WAVES>(a, s) : launch_tok<64, WAVES>(a, s);
+    if (rows > 32) return launch_tok<64, WAVES, 8>(a, s);
+    if (rows > 16) return launch_tok<32, WAVES, 8>(a, s);
+    // Up to 16 token rows the LDS holds two buffers of 16 steps.  The longer chunk halves the workgroup barriers (2-3 %
+    // on a 3-bit stage of K = 14336 and 57344), but a linear's K then has to be whole chunks: a remainder chunk runs in
+    // the conditional form of the main loop, which costs more than the barriers saved.
+    bool whole = true;
+    for (int li = 0; li < a.n_lin; ++li) whole = whole && (a.lin[li].K / 128) % 16 == 0;
+    return whole ? launch_tok<16, WAVES, 16>(a, s) : launch_tok<16, WAVES, 8>(a, s);
 }
 
 hipError_t launch_decode_rows(const DecodeArgs& a, hipStream_t s)

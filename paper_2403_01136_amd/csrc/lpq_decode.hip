@@ -25,6 +25,7 @@
 // staging, no fix-up pass.
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 #include "lpq_common.h"
 #include "lpq_device.h"
@@ -458,19 +459,26 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     while (cur.n > 0) {
         if (nxt.n > 0) fill_x_chunk(nxt, buf ^ 1);
         const bool active = row_block(cur.sb) < L.row_blocks;
-        if (cur.n == CHUNK && active && nxt.n >= STAGES) {
-            // steady state: a full chunk followed by enough steps to refill every slot -- no
-            // per-step conditions, so the whole chunk is one schedulable block
+        // steady state: a chunk of N steps (a full one; in the 16-step form also a linear's remainder of exactly 8)
+        // followed by enough steps to refill every slot -- no per-step conditions, so the whole chunk is one
+        // schedulable block
+        auto steady_chunk = [&](auto n_steps) {
+            constexpr int N = decltype(n_steps)::value;
 #pragma unroll
-            for (int i = 0; i < CHUNK; ++i) {
+            for (int i = 0; i < N; ++i) {
                 compute(st[i % STAGES], buf, i);
                 const int q = i + STAGES;                   // slot to refill
-                if (q < CHUNK) issue(st[i % STAGES], cur.sb, cur.kt0 + q);
-                else           issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - CHUNK));
+                if (q < N) issue(st[i % STAGES], cur.sb, cur.kt0 + q);
+                else       issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - N));
                 if constexpr (WIDE) __builtin_amdgcn_sched_barrier(0);      // keeps a step's operand reads out of earlier steps (register pressure)
             }
-            // the next chunk's activations were requested before this chunk's STAGES refills, which stay in flight
+            // the next chunk's activations were requested before this chunk's last STAGES refills, which stay in flight
             wait_vmem_all_but<STAGES * STAGE_LOADS>();
+        };
+        if (cur.n == CHUNK && active && nxt.n >= STAGES) {
+            steady_chunk(std::integral_constant<int, CHUNK>());
+        } else if (CHUNK == 16 && cur.n == 8 && active && nxt.n >= STAGES) {
+            steady_chunk(std::integral_constant<int, CHUNK == 16 ? 8 : CHUNK>());
         } else {
 #pragma unroll
             for (int i = 0; i < CHUNK; ++i) {
@@ -1060,10 +1068,10 @@ static hipError_t launch_waves(const DecodeArgs& a, hipStream_t s)
     if (rows > 32) return launch_tok<64, WAVES, 8>(a, s);
     if (rows > 16) return launch_tok<32, WAVES, 8>(a, s);
     // Up to 16 token rows the LDS holds two buffers of 16 steps.  The longer chunk halves the workgroup barriers (2-3 %
-    // on a 3-bit stage of K = 14336 and 57344), but a linear's K then has to be whole chunks: a remainder chunk runs in
-    // the conditional form of the main loop, which costs more than the barriers saved.
+    // on a 3-bit stage of K = 14336 and 57344), but a linear's K then has to be whole or half chunks: any other
+    // remainder runs in the conditional form of the main loop, which costs more than the barriers saved.
     bool whole = true;
-    for (int li = 0; li < a.n_lin; ++li) whole = whole && (a.lin[li].K / 128) % 16 == 0;
+    for (int li = 0; li < a.n_lin; ++li) whole = whole && (a.lin[li].K / 128) % 8 == 0;
     return whole ? launch_tok<16, WAVES, 16>(a, s) : launch_tok<16, WAVES, 8>(a, s);
 }
 

@@ -534,21 +534,22 @@ __device__ __forceinline__ uint64_t range_begin(const DecodeArgs& a, int b)
 // tiny activations keep their bits and rows of large ones stay in range.  Layout of a row, group_sums_stride(K) halves
 // from out + 8 * aux: the pairs of groups 0 .. K/128 - 1, zero pairs up to a multiple of 16 groups (they meet zero
 // operands, but must not be NaN), then two floats, scale * 2^24 and 1 / scale.
-// The kernel is a round of memory latency in front of every decode launch, so a thread requests all it adds -- up to
-// GS_ROUNDS groups, K <= 65536 -- before it adds anything, and keeps the sums in registers for the second use; a longer
-// row is read twice.
-constexpr int GS_ROUNDS = 32, GS_BATCH = 8;
+// The kernel is a round of memory latency in front of every decode launch, so a workgroup is 1024 threads (64 groups at a
+// time) and a thread requests all it adds -- up to GS_ROUNDS groups, K <= 65536 -- before it adds anything, keeping the
+// sums in registers for the second use; a longer row is read twice.
+constexpr int GS_THREADS = 1024, GS_ROUNDS = 8, GS_LANES = 16, GS_GROUPS = GS_THREADS / GS_LANES;
 
-__global__ __launch_bounds__(256) void group_sums_kernel(const DecodeArgs a, uint16_t* __restrict__ out)
+__global__ __launch_bounds__(GS_THREADS) void group_sums_kernel(const DecodeArgs a, uint16_t* __restrict__ out)
 {
-    __shared__ float wmax[4];
+    __shared__ float wmax[GS_THREADS / 64];
     const LinDesc& L = a.lin[blockIdx.x];
     if (L.variant == V_F16) return;
     const int row = blockIdx.y, tok = a.m0 + row;
-    const int KT = L.K / 128, GP = (KT + 15) & ~15, rounds = GP / 16;
+    const int KT = L.K / 128, GP = (KT + 15) & ~15, rounds = (GP + GS_GROUPS - 1) / GS_GROUPS;
     uint16_t* dst = out + (size_t)L.aux * 8 + (size_t)row * group_sums_stride(L.K);
     const int l16 = threadIdx.x & 15, g0 = threadIdx.x >> 4;
     const uint16_t* src = L.x + (size_t)tok * L.K + 8 * l16;
+    auto load = [&](int g) { return *reinterpret_cast<const h8*>(src + (size_t)min(g, KT - 1) * 128); };
     auto add16 = [&](h8 v, bool valid) {              // a group's sum, the same value in all sixteen lanes
         float sum = (((float)v[0] + (float)v[1]) + ((float)v[2] + (float)v[3])) + (((float)v[4] + (float)v[5]) + ((float)v[6] + (float)v[7]));
         sum = valid ? sum : 0.0f;
@@ -556,34 +557,29 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const DecodeArgs a, uin
         for (int o = 8; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 16);
         return sum;
     };
-    auto group_sum = [&](int g) {
-        const h8 v = *reinterpret_cast<const h8*>(src + (size_t)min(g, KT - 1) * 128);
-        return add16(v, g < KT);
-    };
     const bool fits = rounds <= GS_ROUNDS;
     float sums[GS_ROUNDS];
     float big = 0.0f;
     if (fits) {
+        h8 v[GS_ROUNDS];
 #pragma unroll
-        for (int i0 = 0; i0 < GS_ROUNDS; i0 += GS_BATCH) {
-            if (i0 >= rounds) break;                                // wave-uniform
-            h8 v[GS_BATCH];
+        for (int i = 0; i < GS_ROUNDS; ++i)
+            if (i < rounds) v[i] = load(g0 + GS_GROUPS * i);                       // wave-uniform condition
 #pragma unroll
-            for (int j = 0; j < GS_BATCH; ++j) v[j] = *reinterpret_cast<const h8*>(src + (size_t)min(g0 + 16 * (i0 + j), KT - 1) * 128);
-#pragma unroll
-            for (int j = 0; j < GS_BATCH; ++j) {
-                sums[i0 + j] = add16(v[j], g0 + 16 * (i0 + j) < KT);
-                big = fmaxf(big, fabsf(sums[i0 + j]));
-            }
+        for (int i = 0; i < GS_ROUNDS; ++i) {
+            sums[i] = i < rounds ? add16(v[i], g0 + GS_GROUPS * i < KT) : 0.0f;
+            big = fmaxf(big, fabsf(sums[i]));
         }
     } else {
-        for (int g = g0; g < GP; g += 16) big = fmaxf(big, fabsf(group_sum(g)));
+        for (int g = g0; g < GP; g += GS_GROUPS) big = fmaxf(big, fabsf(add16(load(g), g < KT)));
     }
 #pragma unroll
     for (int o = 32; o >= 16; o >>= 1) big = fmaxf(big, __shfl_xor(big, o, 64));
     if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = big;
     __syncthreads();
-    big = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    big = 0.0f;
+#pragma unroll
+    for (int w = 0; w < GS_THREADS / 64; ++w) big = fmaxf(big, wmax[w]);
     float scale = 1.0f;
     if (big > 0.0f && big < __builtin_inff()) {
         int ex;
@@ -600,9 +596,9 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const DecodeArgs a, uin
     if (fits) {
 #pragma unroll
         for (int i = 0; i < GS_ROUNDS; ++i)
-            if (i < rounds) store(g0 + 16 * i, sums[i]);
+            if (i < rounds) store(g0 + GS_GROUPS * i, sums[i]);
     } else {
-        for (int g = g0; g < GP; g += 16) store(g, group_sum(g));
+        for (int g = g0; g < GP; g += GS_GROUPS) store(g, add16(load(g), g < KT));
     }
     if (threadIdx.x == 0) {
         float* f = reinterpret_cast<float*>(dst + 2 * GP);
@@ -1109,7 +1105,7 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t s)
         for (int li = 0; li < a.n_lin; ++li) any = any || a.lin[li].variant != V_F16;
         if (any) {
             if (!a.xsum16) return hipErrorInvalidValue;
-            group_sums_kernel<<<dim3((unsigned)a.n_lin, (unsigned)rows), 256, 0, s>>>(a, const_cast<uint16_t*>(a.xsum16));
+            group_sums_kernel<<<dim3((unsigned)a.n_lin, (unsigned)rows), GS_THREADS, 0, s>>>(a, const_cast<uint16_t*>(a.xsum16));
             const hipError_t e0 = hipGetLastError();
             if (e0 != hipSuccess) return e0;
         }

@@ -305,8 +305,8 @@ def main():
                     help="also run a plain 1 GiB device copy 3 times, so a --pmc run can scale FETCH_SIZE / WRITE_SIZE by it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (pipeline stages are independent units; "
-              "see DESIGN.md for how the path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: the library runs on ONE GPU only (a pipeline stage is an independent unit: with more GPUs each "
+              "runs its own stage and only activations cross); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch

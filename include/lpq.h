@@ -202,10 +202,12 @@ lpq_status lpq_stage_linears(const lpq_layer *layers, int32_t n_layers, lpq_phas
 
 /* lpq_stage_linears for callers that cannot allocate device memory while they run: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same results, but the
- * fp32 partial tiles and activation group sums of the launches live in a static 36 MiB array inside the library (one copy per device, held
- * until the process ends) instead of the growing workspace, and the call never allocates or frees.  That array
- * covers every decode-phase launch of up to 32 token rows, and a prefill-phase call none of whose launches is split
- * over K (stage-wide launches are not); a call that would need more returns LPQ_ERR_BUFSIZE and launches nothing
+ * fp32 partial tiles and the prepared activations of the launches live in a static 128 MiB array inside the library
+ * (one copy per device, held until the process ends) instead of the growing workspace, and the call never allocates or
+ * frees.  That array covers a decode-phase call of any number of rows (64 MiB of partial tiles per pass of 64 rows; up to
+ * 16 rows 16 MiB and, for 3-bit linears, 2 bytes per token row and column of the launch's activations: ten
+ * BLOOM-176B-shaped layers at 16 rows take 31 MiB), and a prefill-phase call none of whose launches is
+ * split over K (stage-wide launches are not); a call that would need more returns LPQ_ERR_BUFSIZE and launches nothing
  * further.  All calls on a device share the array, which keeps the last call's contents (nothing in it has to
  * start at zero: every partial tile read was written by the same call); calls that overlap on one device race.
  * Errors: as lpq_stage_linears, plus BUFSIZE as above. */

@@ -210,9 +210,15 @@ void rows_plan(const LinDesc& L, int tok_tiles, int cus, int* tiles, int* splits
     }
 }
 
-// Bytes of a linear's group sums in a decode launch of up to 32 token rows (group_sums_kernel): per token row an fp16
-// pair per 128-column group, groups padded to a multiple of 16, and 16 bytes for the row's scale factors.
-size_t group_sums_bytes(int64_t K) { return (size_t)32 * (4 * (((size_t)K / 128 + 15) & ~(size_t)15) + 16); }
+// Bytes that decode_prepare_kernel leaves for a linear in a decode launch of up to 32 token rows per pass.  The group
+// sums: per token row (32 of them) an fp16 pair per 128-column group, groups padded to a multiple of 16, and 16 bytes
+// for the row's factors; behind them, for 3-bit weights that the launch reads in place, `rows` rows of scaled
+// activations.
+size_t prepared_bytes(const lpq_qdesc& d, int rows, bool in_place)
+{
+    const size_t sums = (size_t)32 * (4 * (((size_t)d.K / 128 + 15) & ~(size_t)15) + 16);
+    return sums + (in_place && variant_of(d) == 0 ? (size_t)rows * (size_t)d.K * 2 : 0);
+}
 
 struct LinearCall {
     const lpq_qweight* w;
@@ -221,6 +227,24 @@ struct LinearCall {
     const void* residual = nullptr;
     int32_t act = LPQ_ACT_NONE;
 };
+
+// Whether a stage-wide decode launch of M token rows reads its 3-bit codes in place (lpq_decode.hip: a third of the
+// unpacking instructions less, against a copy of those linears' activations scaled beforehand).  The copy costs by
+// the row, the saving is per weight: it pays at up to 16 rows where 3-bit weights are a good part of what the launch
+// streams.  Measured: +2.5 % (16 rows) to +5 % (1 row) on an all-3-bit stage, +0.5 % on one of alternating 3- and
+// 4-bit layers, -0.6 % where an eighth of the bytes is 3-bit; at 32 rows -3 to -5 %.
+bool reads_in_place(const std::vector<LinearCall>& calls, size_t begin, size_t end, int32_t M)
+{
+    if (M > 16) return false;
+    double w3 = 0.0, all = 0.0;
+    for (size_t c = begin; c < end; ++c) {
+        const lpq_qdesc& d = calls[c].w->d;
+        const double bytes = (double)d.K * (double)d.N * d.bits;
+        all += bytes;
+        if (variant_of(d) == 0) w3 += bytes;
+    }
+    return w3 >= 0.25 * all;
+}
 
 // Decode-phase dispatch of a list of independent linears: grouped launches of at most
 // MAX_LIN_PER_LAUNCH linears, 64 token rows per pass, each launch one round of equally loaded
@@ -236,14 +260,17 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
     if (st != LPQ_OK) return st;
     const int tok_rows = std::min(64, (M + 15) / 16 * 16);
     const int slot_floats = tok_rows * waves * 64;
-    // after the partial tiles: the activations' group sums of one launch at up to 32 token rows per pass (see
-    // group_sums_kernel); launches and passes run one after the other on the stream and share the space
+    // after the partial tiles: what decode_prepare_kernel leaves for one launch whose last pass has up to 32 token
+    // rows; launches and passes run one after the other on the stream and share the space
     const size_t partial_bytes = ((size_t)2 * n_blocks * slot_floats * sizeof(float) + 255) & ~(size_t)255;
+    const int last_rows = (M - 1) % 64 + 1;
     size_t sums_bytes = 0;
-    if (M % 64 >= 1 && M % 64 <= 32)
+    if (last_rows <= 32)
         for (size_t li = 0; li < n_launch; ++li) {
             size_t b = 0;
-            for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c) b += group_sums_bytes(calls[c].w->d.K);
+            const size_t c0 = li * per_launch, c1 = std::min(n, (li + 1) * per_launch);
+            const bool in_place = reads_in_place(calls, c0, c1, M);
+            for (size_t c = c0; c < c1; ++c) b += prepared_bytes(calls[c].w->d, last_rows, in_place);
             sums_bytes = std::max(sums_bytes, b);
         }
     float* ws = nullptr;
@@ -260,9 +287,10 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         a.row_tiles = 4;
         a.pad = 0;
         a.partial = ws;
-        a.xsum16 = sums_bytes ? reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(ws) + partial_bytes) : nullptr;
+        a.prep = sums_bytes ? reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(ws) + partial_bytes) : nullptr;
         uint64_t total = 0;
         size_t sums_off16 = 0;               // in 16-byte units
+        const bool in_place = reads_in_place(calls, li * per_launch, std::min(n, (li + 1) * per_launch), M);
         for (size_t c = li * per_launch; c < std::min(n, (li + 1) * per_launch); ++c) {
             const lpq_qweight& w = *calls[c].w;
             LinDesc& L = a.lin[a.n_lin++];
@@ -275,7 +303,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
             L.residual = static_cast<const uint16_t*>(calls[c].residual);
             L.act = calls[c].act;
             L.aux = (int32_t)sums_off16;
-            sums_off16 += group_sums_bytes(w.d.K) / 16;
+            sums_off16 += prepared_bytes(w.d, last_rows, in_place) / 16;
             L.K = w.d.K;
             L.N = w.d.N;
             L.variant = variant_of(w.d);
@@ -358,6 +386,9 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         int64_t steps = 0;
         for (int i = 0; i < a.n_lin; ++i) steps += (int64_t)a.lin[i].row_superblocks * (a.lin[i].K / 128);
         a.n_blocks = (int32_t)std::max<int64_t>(1, std::min<int64_t>(n_blocks, steps / min_steps));
+        if (in_place)
+            for (int i = 0; i < a.n_lin; ++i)
+                if (a.lin[i].variant == 0) a.lin[i].variant = V_W3_INPLACE;
         for (int m0 = 0; m0 < M; m0 += 64) {
             a.m0 = m0;
             if (launch_decode(a, stream) != hipSuccess) return LPQ_ERR_DEVICE;

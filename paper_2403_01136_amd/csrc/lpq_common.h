@@ -10,6 +10,11 @@ namespace lpq {
 // Its work is steps = row_superblocks * (K/128) "block steps" (one 128-column step of the
 // WAVES row blocks a workgroup owns), each of weight `step_weight` (bytes streamed, scaled by a
 // per-variant cost factor); `cum_weight` is the total weight of the linears before it.
+// LinDesc::variant is the storage variant (0 .. 4: 3-, 4-, 8-bit grouped, 8-bit per row, fp16) -- or, in the descriptors
+// of a stage-wide decode launch only, this: 3-bit codes that the kernel masks where they lie, against activations scaled
+// for it beforehand (lpq_decode.hip); the host decides per launch.
+enum { V_W3_INPLACE = 5 };
+
 struct LinDesc {
     const uint8_t* codes;
     const uint16_t* scales;
@@ -25,7 +30,7 @@ struct LinDesc {
     int32_t row_blocks;     // N / rows per wave (64; 32 for fp16 weights)
     int32_t row_superblocks;// ceil(row_blocks / waves per workgroup)
     int32_t act;            // lpq_activation applied to acc + bias (before the residual)
-    int32_t aux;            // stage-wide kernel: offset of the linear's group sums in DecodeArgs::xsum16, in 16-byte units;
+    int32_t aux;            // stage-wide kernel: offset of the linear's prepared activations in DecodeArgs::prep, in 16-byte units;
                             // small-launch kernel: number of K splits
 };
 
@@ -41,7 +46,8 @@ struct DecodeArgs {
     int32_t row_tiles, pad;              // small-launch kernel only: 16-row tiles per workgroup (2 .. 5; fp16 weights: at most 2)
     uint64_t total_weight;
     float* partial;
-    const uint16_t* xsum16;              // stage-wide kernel, up to 32 token rows: per-group sums of the activations (group_sums_kernel)
+    const uint16_t* prep;                // stage-wide kernel, up to 32 token rows per pass: what decode_prepare_kernel leaves
+                                         // (the activations' group sums; for 3-bit weights the activations, scaled)
     LinDesc lin[MAX_LIN_PER_LAUNCH];
 };
 static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KB");

@@ -17,7 +17,7 @@
 // (MFMA A operands), which the workgroup stages once through a double-buffered LDS slab.
 //
 // Up to 32 token rows per pass the scale is applied after the matrix cores, per 128-column group, and the zero term
-// (sum over groups of zero * sum of x) once per unit from the activations' group sums, which group_sums_kernel
+// (sum over groups of zero * sum of x) once per unit from the activations' group sums, which decode_prepare_kernel
 // computes in front of the launch.
 //
 // A launch that streams little (a single linear of a decoder layer, up to 32 token rows per pass) takes a second
@@ -54,7 +54,7 @@ template <int TOK, int WAVES, int CAP> struct PipeCfg {
 // 16-byte operand reads of 16 consecutive rows hit 16 different bank groups.
 template <int TOK, int WAVES, int CAP> struct DecodeSmem { uint16_t x[2][TOK][PipeCfg<TOK, WAVES, CAP>::ROW_HALVES]; };
 
-// Halves per token row of a linear's group sums (see group_sums_kernel).
+// Halves per token row of a linear's group sums (see decode_prepare_kernel).
 __device__ __host__ __forceinline__ int group_sums_stride(int K) { return 2 * ((K / 128 + 15) & ~15) + 8; }
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -68,6 +68,16 @@ template <int N> __device__ __forceinline__ void wait_vmem_all_but()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// The codes of one MFMA step as fp16 subnormals, for the kernel that applies scale and zero after the matrix cores:
+// 3-bit fields where they lie (the activations carry the inverse factors: 9 of a tile's 33 vector instructions less),
+// wider ones moved to bit 0.  (4-bit fields in place save one instruction of six per register quadruple, less than
+// preparing the activations costs: measured 0.3-4 % slower on 4-bit stages, so they are not.)
+template <int V, bool INPL> __device__ __forceinline__ h8 unpack_post(const WRaw<V>& w, int j)
+{
+    if constexpr (V == V_W3 && INPL) return unpack_inplace_step<V>(w, j);
+    else return unpack_subnormal_step<V>(w, j);
+}
+
 // A chunk: up to CHUNK consecutive 128-column steps of one (linear, row superblock) unit.
 struct Chunk {
     int sb, kt0, n;      // row superblock, first step, number of steps (0 = none)
@@ -78,8 +88,8 @@ struct Chunk {
 // the end of a unit the accumulators are stored -- as fp16 if the unit's whole K range lay inside
 // [s_begin, s_end), else as an fp32 partial tile in slot_first (the unit this range entered mid-way)
 // or slot_last (the unit it leaves mid-way) -- and cleared.
-template <int V, int TOK, int WAVES, int CAP>
-__device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long s_begin, long s_end, const uint16_t* __restrict__ xsum16,
+template <int V, int TOK, int WAVES, int CAP, bool INPL = false>
+__device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long s_begin, long s_end, const uint16_t* __restrict__ prep,
                                           float* __restrict__ slot_first, float* __restrict__ slot_last, DecodeSmem<TOK, WAVES, CAP>& sm)
 {
     constexpr int RT = DecodeCfg<V>::RT;
@@ -93,6 +103,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     constexpr int STAGES = WANT < CHUNK ? WANT : CHUNK;
     // vector-memory loads of one Stage: the tiles (one load per KB, the 768-byte 3-bit tile included) and scale + zero
     constexpr bool POST = TOK <= 32 && V != V_F16;   // scale and zero folded in after the matrix cores (see compute below)
+    constexpr bool INPLACE = POST && V == V_W3 && INPL;   // 3-bit codes masked where they lie, against activations scaled for it
     constexpr int STAGE_LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) + (SCHEME == SCH_ASYM ? (POST ? 1 : 2) : 0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, kq = lane >> 4;
@@ -160,7 +171,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     // FMAs per tile and token tile instead of the int -> fp16 conversions and packed FMAs per weight.
     // The zero term, sum over groups of zero[n][g] * sum_g(x[m]), is itself a small matrix product
     // (K / 128 deep): it is added once per unit, at its end, from the group sums that
-    // group_sums_kernel left in xsum16 (add_zero_term below).  Otherwise (64 tokens, where the fp32
+    // decode_prepare_kernel left in prep (add_zero_term below).  Otherwise (64 tokens, where the fp32
     // work has outgrown the saving): dequantise each weight to fp16 once, w~ = scale * code + zero.
     // MFMA A operand: 8 consecutive columns (16-byte group c16 of 128-column step `step`) of a token row
     auto x_operand = [&](int buf, int row, int step, int c16) {
@@ -213,7 +224,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             const f4 zero4 = {0, 0, 0, 0};
             f4 d[RT][MT];
 #pragma unroll
-            for (int t = 0; t < RT; ++t) wj[0][t] = unpack_subnormal_step<V>(b.w[t], 0);
+            for (int t = 0; t < RT; ++t) wj[0][t] = unpack_post<V, INPLACE>(b.w[t], 0);
             h8 a[2][MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) a[0][mt] = x_operand(buf, 16 * mt + r, step, kq);
@@ -228,7 +239,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int t = 0; t < RT; ++t) {
-                    if (j < 3) wj[(j + 1) & 1][t] = unpack_subnormal_step<V>(b.w[t], j + 1);
+                    if (j < 3) wj[(j + 1) & 1][t] = unpack_post<V, INPLACE>(b.w[t], j + 1);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
                         if constexpr (SCHEME == SCH_ASYM) d[t][mt] = mfma16(a[j & 1][mt], wj[j & 1][t], j == 0 ? zero4 : d[t][mt]);
@@ -270,6 +281,9 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         }
     };
 
+    // INPLACE: rows 0 .. of this pass of the activations that decode_prepare_kernel scaled, behind the linear's 32 rows of group sums
+    const uint16_t* xrows = INPLACE ? prep + (size_t)L.aux * 8 + (size_t)32 * group_sums_stride(L.K) : L.x;
+    const int xrow0 = INPLACE ? 0 : m0, xrow_last = INPLACE ? min(TOK, M - m0) - 1 : M - 1;
     // ---- activation staging: the x columns of one chunk, shared by the workgroup through LDS.
     // Global-to-LDS loads, 1 KB per wave and instruction (four 256-byte row segments); a lane fetches
     // the column group that belongs in its 16-byte slot after swizzling.  Token rows past M and steps
@@ -281,8 +295,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             const int q = XQ * wave + i;
             const int u = 4 * q + (lane >> 4), row = u / CHUNK, seg = min(u % CHUNK, c.n - 1);
             const int c16 = (lane & 15) ^ (row & 15);
-            const int tok = min(m0 + row, M - 1);
-            const uint16_t* g = L.x + (size_t)tok * L.K + (size_t)(c.kt0 + seg) * 128 + c16 * 8;
+            const uint16_t* g = xrows + (size_t)min(xrow0 + row, xrow_last) * L.K + (size_t)(c.kt0 + seg) * 128 + c16 * 8;
             __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(&sm.x[buf][0][0] + 512 * q), 16, 0, 0);
         }
         asm volatile("" ::: "memory");      // weight loads issued later stay later: vmcnt counts in issue order
@@ -341,13 +354,13 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                 // zero[n][g] * sum_g(x[m]), the per-row scheme's -128 * sum(x[m]) for the offset of its codes.  That
                 // term is a matrix product over the groups this range covered, [tokens][groups] . [groups][rows], with
                 // each group sum as an fp16 pair hi + lo in two adjacent k slots, scaled per token row (see
-                // group_sums_kernel): bring the accumulators to y * scale, chain the product onto them, 16 groups
+                // decode_prepare_kernel): bring the accumulators to y * scale, chain the product onto them, 16 groups
                 // per matrix instruction, then divide the scale out.
                 static_assert(RT == 4, "the zero term reads the zeros of a 64-row block");
                 const long u0 = (long)sb * KT;
                 const int g_lo = (int)(max(u0, s_begin) - u0), g_hi = (int)(min(u0 + KT, s_end) - u0);
                 const int stride = group_sums_stride(L.K);
-                const uint16_t* xs = xsum16 + (size_t)L.aux * 8;
+                const uint16_t* xs = prep + (size_t)L.aux * 8;
                 const int cnt = min(TOK, M - m0);                            // token rows the sums were taken for
                 float undo[MT][4];
 #pragma unroll
@@ -527,26 +540,38 @@ __device__ __forceinline__ uint64_t range_begin(const DecodeArgs& a, int b)
     return a.total_weight * (uint64_t)b / (uint64_t)a.n_blocks;      // total_weight < 2^50, b < 2^13
 }
 
-// Group sums of the activations, for the zero term of decode_kernel at up to 32 token rows per pass.  Workgroup
-// (blockIdx.x = linear, blockIdx.y = row of the pass) adds x over each 128-column group of token row a.m0 + row (sixteen
-// lanes per group, a fixed order) and writes the sums as fp16 pairs for the matrix cores: sum * scale = hi + lo (lo = the
-// rounding error of hi), scale the power of two that brings the row's largest |sum| into [2^13, 2^14) -- so that rows of
-// tiny activations keep their bits and rows of large ones stay in range.  Layout of a row, group_sums_stride(K) halves
-// from out + 8 * aux: the pairs of groups 0 .. K/128 - 1, zero pairs up to a multiple of 16 groups (they meet zero
-// operands, but must not be NaN), then two floats, scale * 2^24 and 1 / scale.
+// What a decode launch of up to 32 token rows per pass needs from its activations beforehand.  Workgroup
+// (blockIdx.x = linear, blockIdx.y = row of the pass) reads token row a.m0 + row of the linear's x once and writes, at
+// prep + 8 * aux halves:
+//  - the group sums for the zero term: x added over each 128-column group (sixteen lanes per group, a fixed order), as
+//    fp16 pairs for the matrix cores: sum * scale = hi + lo (lo = the rounding error of hi), scale the power of two that
+//    brings the row's largest |sum| into [2^13, 2^14) -- so that rows of tiny activations keep their bits and rows of
+//    large ones stay in range.  A row is group_sums_stride(K) halves: the pairs of groups 0 .. K/128 - 1, zero pairs up
+//    to a multiple of 16 groups (they meet zero operands, but must not be NaN), then two floats, pre and undo: the
+//    accumulators are multiplied by pre before the zero term is chained onto them and by undo afterwards;
+//  - for 3-bit weights that the launch reads in place (variant V_W3_INPLACE), behind the 32 rows of sums: the row scaled for codes that are masked where they lie
+//    (unpack_inplace_step): column c of a 128-column step times 2^-(3 * inplace_class(c / 32, (c % 8) / 2)), times the
+//    power of two that brings the row's largest |x| into [2^14, 2^15) -- exact, and with the row at the
+//    top of the fp16 range the factors of up to 2^-6 cost only elements 2^23 below the row's largest any bits.  pre
+//    carries the inverse of that power.
 // The kernel is a round of memory latency in front of every decode launch, so a workgroup is 1024 threads (64 groups at a
-// time) and a thread requests all it adds -- up to GS_ROUNDS groups, K <= 65536 -- before it adds anything, keeping the
-// sums in registers for the second use; a longer row is read twice.
+// time) and a thread requests all it adds -- up to GS_ROUNDS groups, K <= 65536 -- before it adds anything, keeping
+// the sums in registers for the second use; a longer row is read twice.
 constexpr int GS_THREADS = 1024, GS_ROUNDS = 8, GS_LANES = 16, GS_GROUPS = GS_THREADS / GS_LANES;
 
-__global__ __launch_bounds__(GS_THREADS) void group_sums_kernel(const DecodeArgs a, uint16_t* __restrict__ out)
+template <bool ANY_INPLACE>
+__global__ __launch_bounds__(GS_THREADS) void decode_prepare_kernel(const DecodeArgs a, uint16_t* __restrict__ prep)
 {
-    __shared__ float wmax[GS_THREADS / 64];
+    __shared__ float wmax[2][GS_THREADS / 64];
     const LinDesc& L = a.lin[blockIdx.x];
     if (L.variant == V_F16) return;
+    const bool scaled = ANY_INPLACE && L.variant == V_W3_INPLACE;
+    constexpr int width = 3;
     const int row = blockIdx.y, tok = a.m0 + row;
     const int KT = L.K / 128, GP = (KT + 15) & ~15, rounds = (GP + GS_GROUPS - 1) / GS_GROUPS;
-    uint16_t* dst = out + (size_t)L.aux * 8 + (size_t)row * group_sums_stride(L.K);
+    uint16_t* base = prep + (size_t)L.aux * 8;
+    uint16_t* dst = base + (size_t)row * group_sums_stride(L.K);
+    uint16_t* xq = base + (size_t)32 * group_sums_stride(L.K) + (size_t)row * L.K;
     const int l16 = threadIdx.x & 15, g0 = threadIdx.x >> 4;
     const uint16_t* src = L.x + (size_t)tok * L.K + 8 * l16;
     auto load = [&](int g) { return *reinterpret_cast<const h8*>(src + (size_t)min(g, KT - 1) * 128); };
@@ -557,11 +582,17 @@ __global__ __launch_bounds__(GS_THREADS) void group_sums_kernel(const DecodeArgs
         for (int o = 8; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 16);
         return sum;
     };
+    auto largest = [&](h8 v) {
+        float m = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf((float)v[i]));
+        return m;
+    };
     const bool fits = rounds <= GS_ROUNDS;
+    h8 v[GS_ROUNDS];
     float sums[GS_ROUNDS];
-    float big = 0.0f;
+    float big = 0.0f, xbig = 0.0f;
     if (fits) {
-        h8 v[GS_ROUNDS];
 #pragma unroll
         for (int i = 0; i < GS_ROUNDS; ++i)
             if (i < rounds) v[i] = load(g0 + GS_GROUPS * i);                       // wave-uniform condition
@@ -569,40 +600,71 @@ __global__ __launch_bounds__(GS_THREADS) void group_sums_kernel(const DecodeArgs
         for (int i = 0; i < GS_ROUNDS; ++i) {
             sums[i] = i < rounds ? add16(v[i], g0 + GS_GROUPS * i < KT) : 0.0f;
             big = fmaxf(big, fabsf(sums[i]));
+            if (scaled && i < rounds) xbig = fmaxf(xbig, largest(v[i]));           // a clamped group repeats a real one
         }
     } else {
-        for (int g = g0; g < GP; g += GS_GROUPS) big = fmaxf(big, fabsf(add16(load(g), g < KT)));
+        for (int g = g0; g < GP; g += GS_GROUPS) {
+            const h8 u = load(g);
+            big = fmaxf(big, fabsf(add16(u, g < KT)));
+            if (scaled) xbig = fmaxf(xbig, largest(u));
+        }
     }
 #pragma unroll
-    for (int o = 32; o >= 16; o >>= 1) big = fmaxf(big, __shfl_xor(big, o, 64));
-    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = big;
+    for (int o = 32; o >= 1; o >>= 1) {
+        big = fmaxf(big, __shfl_xor(big, o, 64));
+        xbig = fmaxf(xbig, __shfl_xor(xbig, o, 64));
+    }
+    if ((threadIdx.x & 63) == 0) { wmax[0][threadIdx.x >> 6] = big; wmax[1][threadIdx.x >> 6] = xbig; }
     __syncthreads();
-    big = 0.0f;
+    big = xbig = 0.0f;
 #pragma unroll
-    for (int w = 0; w < GS_THREADS / 64; ++w) big = fmaxf(big, wmax[w]);
-    float scale = 1.0f;
-    if (big > 0.0f && big < __builtin_inff()) {
+    for (int w = 0; w < GS_THREADS / 64; ++w) { big = fmaxf(big, wmax[0][w]); xbig = fmaxf(xbig, wmax[1][w]); }
+    // the power of two that brings m into [2^(top-1), 2^top); 1 for a row of zeros (or one that holds an infinity)
+    auto power_for = [](float m, int top) {
+        if (!(m > 0.0f && m < __builtin_inff())) return 1.0f;
         int ex;
-        (void)frexpf(big, &ex);                       // big = f * 2^ex, f in [0.5, 1)
-        scale = ldexpf(1.0f, max(-40, min(40, 14 - ex)));
-    }
-    auto store = [&](int g, float sum) {
-        const float scaled = sum * scale;
-        const _Float16 hi = (_Float16)scaled;
-        const _Float16 lo = (_Float16)(scaled - (float)hi);
+        (void)frexpf(m, &ex);                         // m = f * 2^ex, f in [0.5, 1)
+        return ldexpf(1.0f, max(-40, min(40, top - ex)));
+    };
+    const float scale = power_for(big, 14);
+    const float xscale = scaled ? power_for(xbig, 15) : 1.0f;
+    auto store_sum = [&](int g, float sum) {
+        const float sc = sum * scale;
+        const _Float16 hi = (_Float16)sc;
+        const _Float16 lo = (_Float16)(sc - (float)hi);
         if (l16 == 0 && g < GP)
             reinterpret_cast<uint32_t*>(dst)[g] = (uint32_t)__builtin_bit_cast(uint16_t, hi) | ((uint32_t)__builtin_bit_cast(uint16_t, lo) << 16);
+    };
+    // the lane's eight columns are columns 8 * (l16 % 4) .. + 7 of MFMA step l16 / 4: output registers k = 0 .. 3 of that step
+    float mult[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        mult[k] = ldexpf(xscale, -width * inplace_class<V_W3>(l16 >> 2, k));
+    }
+    auto store_row = [&](int g, h8 u) {
+        if (g >= KT) return;
+        h8 o;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = (_Float16)((float)u[i] * mult[i >> 1]);
+        *reinterpret_cast<h8*>(xq + (size_t)g * 128 + 8 * l16) = o;
     };
     if (fits) {
 #pragma unroll
         for (int i = 0; i < GS_ROUNDS; ++i)
-            if (i < rounds) store(g0 + GS_GROUPS * i, sums[i]);
+            if (i < rounds) store_sum(g0 + GS_GROUPS * i, sums[i]);
+        // the row is read once more (from the caches) rather than kept: the registers would halve the workgroups a CU holds
+        if (scaled)
+            for (int g = g0; g < KT; g += GS_GROUPS) store_row(g, load(g));
     } else {
-        for (int g = g0; g < GP; g += GS_GROUPS) store(g, add16(load(g), g < KT));
+        for (int g = g0; g < GP; g += GS_GROUPS) {
+            const h8 u = load(g);
+            store_sum(g, add16(u, g < KT));
+            if (scaled) store_row(g, u);
+        }
     }
     if (threadIdx.x == 0) {
         float* f = reinterpret_cast<float*>(dst + 2 * GP);
-        f[0] = scale * 16777216.0f;
+        f[0] = scale * 16777216.0f / xscale;
         f[1] = 1.0f / scale;
     }
 }
@@ -628,11 +690,14 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const Dec
         const long budget = (long)((hi - start + L.step_weight - 1) / L.step_weight);      // steps of this range from here
         const long s_end = min(steps, c.step + budget);
         switch (L.variant) {
-        case V_W3: run_range<V_W3, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
-        case V_W4: run_range<V_W4, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
-        case V_W8: run_range<V_W8, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
-        case V_I8: run_range<V_I8, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
-        default:   run_range<V_F16, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.xsum16, slot_first, slot_last, sm); break;
+        case V_W3: run_range<V_W3, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.prep, slot_first, slot_last, sm); break;
+        case V_W3_INPLACE:
+            if constexpr (TOK <= 16) run_range<V_W3, TOK, WAVES, CAP, true>(L, a.M, a.m0, c.step, s_end, a.prep, slot_first, slot_last, sm);
+            break;
+        case V_W4: run_range<V_W4, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.prep, slot_first, slot_last, sm); break;
+        case V_W8: run_range<V_W8, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.prep, slot_first, slot_last, sm); break;
+        case V_I8: run_range<V_I8, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.prep, slot_first, slot_last, sm); break;
+        default:   run_range<V_F16, TOK, WAVES, CAP>(L, a.M, a.m0, c.step, s_end, a.prep, slot_first, slot_last, sm); break;
         }
         c.step = s_end;
     }
@@ -1005,12 +1070,15 @@ __global__ __launch_bounds__(256) void decode_rows_reduce_kernel(const DecodeArg
 
 }  // namespace lpq
 
-// Scratch of the entry point that allocates nothing (lpq_stage_linears_noalloc): the fp32 partial tiles that the
-// library otherwise keeps in its growing workspace, and the activations' group sums of a decode launch.  36 MiB per
-// device, held until the process ends; it covers every decode launch of up to 32 token rows (2 slots x 256 workgroups
-// x 32 rows x 512 columns x 4 bytes of partial tiles, and up to 4 MiB of group sums: 40 linears of K = 57344 take
-// 2.2 MiB).  Nothing in it has to start at zero: whatever is read was written earlier in the same call.
-constexpr size_t LPQ_SCRATCH_BYTES = (size_t)36 << 20;
+// Scratch of the entry point that allocates nothing (lpq_stage_linears_noalloc): what the library otherwise keeps in
+// its growing workspace -- the fp32 partial tiles of the launches and the prepared activations of a decode launch.
+// 128 MiB per device, held until the process ends.  A decode launch of up to 32 token rows takes 32 MiB of partial
+// tiles (2 slots x 256 workgroups x 32 rows x 512 columns x 4 bytes), group sums (40 linears of K = 57344: 2.2 MiB)
+// and, at up to 16 rows, 2 bytes per token row and column of scaled activations for 3-bit linears read in place (ten
+// BLOOM-176B-shaped layers at 16 rows: 31 MiB); passes of 64 rows take 64 MiB of partial tiles.  Nothing in it has to
+// start at zero:
+// whatever is read was written earlier in the same call.
+constexpr size_t LPQ_SCRATCH_BYTES = (size_t)128 << 20;
 static __device__ __align__(256) unsigned char scratch[LPQ_SCRATCH_BYTES];
 
 namespace lpq {
@@ -1104,8 +1172,12 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t s)
         bool any = false;
         for (int li = 0; li < a.n_lin; ++li) any = any || a.lin[li].variant != V_F16;
         if (any) {
-            if (!a.xsum16) return hipErrorInvalidValue;
-            group_sums_kernel<<<dim3((unsigned)a.n_lin, (unsigned)rows), GS_THREADS, 0, s>>>(a, const_cast<uint16_t*>(a.xsum16));
+            if (!a.prep) return hipErrorInvalidValue;
+            bool inplace = false;
+            for (int li = 0; li < a.n_lin; ++li) inplace = inplace || a.lin[li].variant == V_W3_INPLACE;
+            const dim3 grid((unsigned)a.n_lin, (unsigned)rows);
+            if (inplace) decode_prepare_kernel<true><<<grid, GS_THREADS, 0, s>>>(a, const_cast<uint16_t*>(a.prep));
+            else         decode_prepare_kernel<false><<<grid, GS_THREADS, 0, s>>>(a, const_cast<uint16_t*>(a.prep));
             const hipError_t e0 = hipGetLastError();
             if (e0 != hipSuccess) return e0;
         }

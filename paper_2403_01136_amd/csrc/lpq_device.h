@@ -198,6 +198,39 @@ __device__ __forceinline__ h8 unpack_subnormal_step(const WRaw<V>& w, int j)
     }
 }
 
+// ---- 3-bit codes as subnormals WHERE THEY LIE ---------------------------------------------
+// A field need not be moved to bit 0 to be an operand: masked in place at bit offset s <= 6 (so that it ends below
+// the exponent's second bit) the half-word is the fp16 number code * 2^s * 2^-24, exactly.  The factor 2^s is taken out
+// on the other side of the product: the activations of those columns are multiplied by 2^-s beforehand (an exact
+// scaling, together with a power of two per token row that keeps every element in the normal range; the kernel that
+// prepares a decode launch's activations does it).  A 3-bit half-word then needs one shift (by 9, for its fields 3
+// and 4) instead of four.  inplace_class<V>(j, k) is the power of 8 that output register k of MFMA step j carries:
+// columns 2k and 2k + 1 of the lane's eight.
+template <int V> __device__ __host__ constexpr int inplace_class(int j, int k)
+{
+    static_assert(V == V_W3, "only 3-bit codes are read in place");
+    return (4 * j + k) < 15 ? ((4 * j + k) % 5) % 3 : 0;
+}
+
+template <int V>
+__device__ __forceinline__ h8 unpack_inplace_step(const WRaw<V>& w, int j)
+{
+    static_assert(V == V_W3, "only 3-bit codes are read in place");
+    u32x4 o;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int P = 4 * j + k;
+        if (P < 15) {
+            const int f = P % 5;
+            const uint32_t src = f >= 3 ? (w.q[P / 5] >> 9) : w.q[P / 5];
+            o[k] = src & (0x00070007u << (3 * (f % 3)));
+        } else {
+            o[k] = ((w.q[0] >> 15) & 0x00010001u) | ((w.q[1] >> 14) & 0x00020002u) | ((w.q[2] >> 13) & 0x00040004u);
+        }
+    }
+    return __builtin_bit_cast(h8, o);
+}
+
 // One MFMA step (32 columns: j) of a tile as integer-valued fp16 codes (the 0x6400 mantissa trick above).
 template <int V>
 __device__ __forceinline__ h8 unpack_codes_step(const WRaw<V>& w, int j)

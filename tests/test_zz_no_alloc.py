@@ -70,9 +70,9 @@ def test_noalloc_matches_stage_linears_twice_in_a_row(orc, case, even_share):
         lpq.lpq_set_decode_routing(-1, -1)
 
 
-def test_noalloc_prefill_and_size_limit(orc):
-    """A stage-wide prefill launch needs no partial sums and runs; a decode call beyond 32 token rows needs more than the
-    static array holds and is refused with LPQ_ERR_BUFSIZE (nothing is allocated instead)."""
+def test_noalloc_prefill_and_many_rows(orc):
+    """A stage-wide prefill launch needs no partial sums and runs (one that the library splits over K may be refused);
+    a decode call of 300 rows runs in passes of 64 rows, whose partial tiles the static array holds."""
     import torch
     h, f, specs, M = 256, 1024, [(4, 1), (16, 0)], 300
     layers, xs, host, outputs = _stage("noalloc_pre", h, f, 3 * h, specs, M)
@@ -88,8 +88,47 @@ def test_noalloc_prefill_and_size_limit(orc):
         assert e.status == 6
     lpq.lpq_set_decode_routing(0, 0)
     try:
+        ys = outputs()
+        lpq.lpq_stage_linears_noalloc(lpq.Stage(layers, xs, ys), lpq.LPQ_DECODE)
+        torch.cuda.synchronize()
+        for li, (bits, scheme) in enumerate(specs):
+            for name in wl.LINEARS:
+                w, x = host[li][name]
+                check_output(ys[li][name], orc.qlinear(x, w, bits, scheme), "decode 300 rows, layer %d %s" % (li, name))
+    finally:
+        lpq.lpq_set_decode_routing(-1, -1)
+
+
+def test_noalloc_size_limit():
+    """A decode launch whose prepared activations (up to 16 rows, 2 bytes per token row and column of every 3-bit linear;
+    here four feed-forward matrices of K = 2^20 at 16 rows: 128 MiB) do not fit the static array beside its partial tiles
+    is refused with LPQ_ERR_BUFSIZE; nothing is allocated instead and nothing is launched."""
+    import torch
+    lpq.load_library()
+    h, f, M = 128, 1 << 20, 16
+    shapes = {"qkv": (h, 3 * h), "out": (h, h), "fc1": (h, f), "fc2": (f, h)}
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    layers, xs, ys = [], [], []
+    x_h = torch.randn((M, h), generator=gen, device="cuda", dtype=torch.float16)
+    x_f = torch.randn((M, f), generator=gen, device="cuda", dtype=torch.float16)
+    for li in range(4):
+        lw = {}
+        for name, (K, N) in shapes.items():
+            w = torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float16)
+            lw[name] = lpq.lpq_quantize_pack(w, 3, 1)
+            del w
+        layers.append(lw)
+        xs.append({n: (x_f if n == "fc2" else x_h) for n in shapes})
+        ys.append({n: torch.full((M, shapes[n][1]), float("nan"), dtype=torch.float16, device="cuda") for n in shapes})
+    lpq.lpq_set_decode_routing(0, 0)
+    try:
         with pytest.raises(lpq.LpqError) as err:
-            lpq.lpq_stage_linears_noalloc(lpq.Stage(layers, xs, ys), lpq.LPQ_DECODE)      # 300 rows: 64-row passes
+            lpq.lpq_stage_linears_noalloc(lpq.Stage(layers, xs, ys), lpq.LPQ_DECODE)
         assert err.value.status == 6
+        torch.cuda.synchronize()
+        assert all(torch.isnan(y).all() for l in ys for y in l.values()), "a refused call wrote outputs"
+        lpq.lpq_stage_linears(lpq.Stage(layers, xs, ys), lpq.LPQ_DECODE)          # the allocating entry point takes it
+        torch.cuda.synchronize()
+        assert all(torch.isfinite(y).all() for l in ys for y in l.values())
     finally:
         lpq.lpq_set_decode_routing(-1, -1)

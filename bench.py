@@ -346,7 +346,7 @@ def main():
         out.update({"value": wbytes / ms / 1e6, "ms_per_step": ms, "host_ms_per_step": wall})
         out["roofline"] = {"bound": "hbm", "achieved": algo / ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": algo / ms / 1e6 / HBM_PEAK_GBS, "traffic": None,
-                           "kernel": "group_sums_kernel + decode_kernel + decode_fixup_kernel (one grouped decode launch of the stage)",
+                           "kernel": "decode_prepare_kernel + decode_kernel + decode_fixup_kernel (one grouped decode launch of the stage)",
                            "algorithmic_bytes_per_launch": algo}
     psteps, pwarm = max(3, args.steps // 10), max(1, args.warmup // 5)
     if args.only in ("all", "prefill"):

@@ -37,5 +37,15 @@ def build_library(extra_flags=(), verbose=False):
     return LIB
 
 
+def build_probe(verbose=False):
+    """The issue-rate probe (csrc/probe_issue_rates.hip): a stand-alone measuring tool, not linked into the library."""
+    exe = os.path.join(HERE, "probe_issue_rates")
+    subprocess.check_call(["hipcc"] + [f for f in FLAGS if f != "-fPIC"] + [os.path.join(CSRC, "probe_issue_rates.hip"), "-o", exe])
+    if verbose:
+        print("built", exe)
+    return exe
+
+
 if __name__ == "__main__":
     build_library(sys.argv[1:], verbose=True)
+    build_probe(verbose=True)

@@ -132,3 +132,41 @@ def test_noalloc_size_limit():
         assert all(torch.isfinite(y).all() for l in ys for y in l.values())
     finally:
         lpq.lpq_set_decode_routing(-1, -1)
+
+
+def test_noalloc_under_graph_capture():
+    """What the entry point is for: a decode step captured into a HIP graph (no allocation may happen while a stream
+    captures) and replayed with new activations in the same buffers.  Every replay equals the eager call on the same
+    inputs bit for bit; eager work and synchronisations sit between the replays."""
+    import torch
+    lpq.load_library()
+    h, f, specs, M = 256, 1024, [(3, 1), (4, 1), (8, 2), (16, 0)], 16
+    layers, xs, host, outputs = _stage("noalloc_graph", h, f, 3 * h, specs, M)
+    lpq.lpq_set_decode_routing(0, 0)
+    try:
+        y_graph, y_eager = outputs(), outputs()
+        stage_g, stage_e = lpq.Stage(layers, xs, y_graph), lpq.Stage(layers, xs, y_eager)
+        lpq.lpq_stage_linears_noalloc(stage_g, lpq.LPQ_DECODE)           # once outside the capture: per-device set-up happens here
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            lpq.lpq_stage_linears_noalloc(stage_g, lpq.LPQ_DECODE)
+        gen = torch.Generator(device="cuda").manual_seed(11)
+        for rep in range(3):
+            for lx in xs:                                                 # new activations, same buffers
+                for t in {id(v): v for v in lx.values()}.values():
+                    t.copy_(torch.randn(t.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.float16))
+            for ly in y_graph:
+                for t in ly.values():
+                    t.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            lpq.lpq_stage_linears_noalloc(stage_e, lpq.LPQ_DECODE)
+            torch.cuda.synchronize()
+            for li in range(len(specs)):
+                for name in wl.LINEARS:
+                    a, b = y_graph[li][name], y_eager[li][name]
+                    assert not torch.isnan(a).any(), "replay %d layer %d %s: output not fully written" % (rep, li, name)
+                    assert torch.equal(a.view(torch.int16), b.view(torch.int16)), "replay %d layer %d %s" % (rep, li, name)
+    finally:
+        lpq.lpq_set_decode_routing(-1, -1)

@@ -105,7 +105,7 @@ __device__ __forceinline__ void unpack_codes(const WRaw<V>& w, h8 out[4])
 {
     constexpr uint32_t MAGIC = 0x64006400u;
     uint32_t magic_v;                                   // the magic constant held in a VGPR (see and_or)
-    asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
+    asm("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
     if constexpr (V == V_W4) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -237,7 +237,7 @@ __device__ __forceinline__ h8 unpack_codes_step(const WRaw<V>& w, int j)
 {
     constexpr uint32_t MAGIC = 0x64006400u;
     uint32_t magic_v;
-    asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
+    asm("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
     if constexpr (V == V_W4) {
         const uint32_t q = w.q[j], t = q >> 8;
         const h2 p0 = magic_to_int(and_or(q, 0x000F000Fu, magic_v), 0);
@@ -289,7 +289,7 @@ __device__ __forceinline__ void unpack_codes_half(const WRaw<V>& w, int half, h8
 {
     constexpr uint32_t MAGIC = 0x64006400u;
     uint32_t magic_v;
-    asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
+    asm("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
     if constexpr (V == V_W4) {
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {

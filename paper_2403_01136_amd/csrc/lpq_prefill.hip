@@ -29,6 +29,7 @@
 // multiply-accumulate -- bytes moved through LDS and from L2 -- more than idle issue slots.
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 #include "lpq_common.h"
 #include "lpq_device.h"
@@ -118,6 +119,9 @@ void prefill_kernel(const PrefillArgs a)
 #pragma unroll
         for (int q = q_begin; q < q_end; ++q) {
             const int row0 = 4 * (XQ * wave + q);
+            // opaque here, so that the widening to 64 bits happens next to the load and the instruction takes the
+            // scalar base and the 32-bit lane offset as they are (no 64-bit vector add per load)
+            asm volatile("" : "+v"(xoff[q]));
             __builtin_amdgcn_global_load_lds((gptr_t)(base + xoff[q]), (lptr_t)&sm.x[buf][row0][0], 16, 0, 0);
         }
     };
@@ -207,12 +211,15 @@ void prefill_kernel(const PrefillArgs a)
     constexpr int SEGS = 4 * MTB;                    // segments per 128-column step
     constexpr int STRIDE = MTB / 4;                  // segments between two pieces of unpacking work
     constexpr int FILL_SEGS = 4;                     // odd segments that carry the next slab's loads
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
+    // One 128-column step.  CUR: which of the two sets of packed weights holds this step's (the other receives the next
+    // step's); the steps alternate, so that nothing is copied from one set to the other.
+    auto step = [&](int kt, auto cur_set) {
+        constexpr int CUR = HALF_LOADS ? 0 : decltype(cur_set)::value;
         const int buf = kt & 1;
         // Loads for the next step go out first and land while this step is multiplied.  Past the last
         // step they re-read it (no branches in the loop); what is built from them is never multiplied.
         const int ktn = min(kt + 1, kt_end - 1);
-        if constexpr (!HALF_LOADS) load_w(ws[1], ktn, 0);
+        if constexpr (!HALF_LOADS) load_w(ws[CUR ^ 1], ktn, 0);
         // the next slab's 16 loads go out four at a time between the matrix instructions of the step's first
         // four odd segments (the even ones carry the unpacking): issued in a block up front they hold back
         // the step's first matrix instruction by as many issue slots, spread over more segments the last of
@@ -223,7 +230,7 @@ void prefill_kernel(const PrefillArgs a)
         for (int half = 0; half < 2; ++half) {
             if constexpr (HALF_LOADS) load_w(ws[half], ktn, half);       // the half step after next
             // the half step unpacked now: (kt, 1) during half 0, (kt + 1, 0) during half 1
-            const WStep& src = HALF_LOADS ? ws[1 - half] : ws[half];
+            const WStep& src = HALF_LOADS ? ws[1 - half] : ws[CUR ^ half];
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
@@ -253,8 +260,13 @@ void prefill_kernel(const PrefillArgs a)
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): next slab written before anyone reads it
         __syncthreads();
-        if constexpr (!HALF_LOADS) ws[0] = ws[1];
+    };
+    int kt = kt_begin;
+    for (; kt + 1 < kt_end; kt += 2) {
+        step(kt, std::integral_constant<int, 0>());
+        step(kt + 1, std::integral_constant<int, 1>());
     }
+    if (kt < kt_end) step(kt, std::integral_constant<int, 0>());
 
     if (!active) return;
     // epilogue: lane (n = lane%32, half = lane/32) holds, for pair p, output row 64*rb + 4*(n%16) + 2*(n/16) + p

@@ -398,6 +398,7 @@ void prefill_ring_kernel(const PrefillArgs a)
     const char* xtile = reinterpret_cast<const char*>(L.x + (size_t)m0 * K);
     auto fill_x = [&](int dbl, int xslot, int i) {   // double steps past the end repeat the last one (never multiplied)
         const char* base = xtile + (size_t)min(dbl, dbl_last) * 128;
+        asm volatile("" : "+v"(xoff[i]));            // widened next to the load: scalar base + 32-bit lane offset, no 64-bit vector add
         __builtin_amdgcn_global_load_lds((gptr_t)(base + xoff[i]), (lptr_t)&ring.x[xslot][1024 * (4 * wave + i)], 16, 0, 0);
         asm volatile("" ::: "memory");
     };
@@ -405,11 +406,14 @@ void prefill_ring_kernel(const PrefillArgs a)
     const long rb_fill = min((long)tile_n * 4 + (wave >> 1), RB - 1);
     const int t_fill = 2 * (wave & 1);
     const uint8_t* wsrc = codes + ((size_t)rb_fill * KT * 4 + t_fill) * (size_t)VInfo<V>::TILE_BYTES;     // + kt * 4 * TILE_BYTES
+    uint32_t lane16[2] = {16u * (uint32_t)lane, 16u * (uint32_t)lane + 4096u};
     auto fill_w_dma = [&](int sub, int stage, int tt) {
         if constexpr (DMA_W) {
             const int sc = min(sub, sub_last);
-            const uint8_t* g = wsrc + (size_t)(sc >> 2) * 4 * 4096 + 1024 * (sc & 3) + 16 * lane;
-            __builtin_amdgcn_global_load_lds((gptr_t)(g + 4096 * tt), (lptr_t)&ring.w[stage][1024 * (2 * wave + tt)], 16, 0, 0);
+            // scalar base + 32-bit lane offset (the second tile's 4096 bytes are beyond the instruction's immediate: they ride in the offset)
+            const uint8_t* g = wsrc + (size_t)(sc >> 2) * 4 * 4096 + 1024 * (sc & 3);
+            asm volatile("" : "+v"(lane16[tt]));
+            __builtin_amdgcn_global_load_lds((gptr_t)(g + lane16[tt]), (lptr_t)&ring.w[stage][1024 * (2 * wave + tt)], 16, 0, 0);
             asm volatile("" ::: "memory");
         }
     };
@@ -430,20 +434,22 @@ void prefill_ring_kernel(const PrefillArgs a)
             }
         }
     };
-    Packed cur, nxt;                                 // the group being turned into pieces, and the one after it
-    // Ahead of a group's first piece the registers move on: cur <- that group, nxt <- loads of the one after it.
-    auto rotate = [&](int piece, int kt_next) {
+    // Two sets of packed codes: the group being turned into pieces and the one after it.  They swap roles with every
+    // group (nothing is copied): ahead of a group's first piece the set that has just been used up receives the loads
+    // of the group after next.
+    Packed pk[2];
+    auto rotate = [&](int piece, int kt_next, int free_set) {
         if constexpr (!DMA_W) {
             if (piece == 0) {
-                cur = nxt;
-                load_packed(nxt, kt_next);
+                load_packed(pk[free_set], kt_next);
                 asm volatile("" ::: "memory");       // ahead of the sub-step's fills in issue order (see FILL_OPS)
             }
         }
     };
-    // tile tt of piece `piece` of the group in `cur` -> stage
-    auto produce = [&](int piece, int tt, int stage) {
+    // tile tt of piece `piece` of the group in set `set` -> stage
+    auto produce = [&](int piece, int tt, int stage, int set) {
         if constexpr (!DMA_W) {
+            const Packed& cur = pk[set];
             h8 v = unpack_codes_step<V>(cur.t[tt], piece);
             if constexpr (SCHEME == SCH_ASYM) {
                 const int t = t_fill + tt;
@@ -499,14 +505,14 @@ void prefill_ring_kernel(const PrefillArgs a)
     constexpr int FILL_OPS = DMA_W ? 4 : 2;
 
     // ---- prologue: sub-steps 0 .. 2 of the weights, 0 .. 3 of the activations -----------------------------------
-    load_packed(nxt, kt_begin);
+    load_packed(pk[0], kt_begin);
 #pragma unroll
     for (int p = 0; p < WRING - 1; ++p) {
-        rotate(p & 3, kt_begin + (p >> 2) + 1);
+        rotate(p & 3, kt_begin + (p >> 2) + 1, 1);
         fill_w_dma(sub_begin + p, p, 0);
         fill_w_dma(sub_begin + p, p, 1);
-        produce(p & 3, 0, p);
-        produce(p & 3, 1, p);
+        produce(p & 3, 0, p, 0);
+        produce(p & 3, 1, p, 0);
     }
 #pragma unroll
     for (int d = 0; d < 2; ++d)
@@ -517,15 +523,19 @@ void prefill_ring_kernel(const PrefillArgs a)
     asm volatile("" ::: "memory");
     Operands op[2];
     read_operands(op[0], 0, 0, 0, 0);
-    int sc = 0, xc = 0;                              // stages of the sub-step being multiplied
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
+    static_assert(WRING == 4, "a group of four sub-steps is one turn of the weight ring: its stage is the sub-step's index in the group");
+    int xc = 0;                                      // activation stage of the sub-step being multiplied
+    // One group of four sub-steps.  SET: the set of packed codes that holds this group's (its last piece is produced in
+    // the group's first sub-step; from the second on the pieces come from the next group, in the other set).
+    auto group = [&](int kt, auto cur_set) {
+        constexpr int SET = decltype(cur_set)::value;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             __builtin_amdgcn_s_waitcnt(waitcnt_imm(FILL_OPS, 0));
             __builtin_amdgcn_s_barrier();            // B_i
             asm volatile("" ::: "memory");
             const int sub = 4 * kt + j, par = j & 1;
-            const int sf = sc == 0 ? WRING - 1 : sc - 1, sn = sc == WRING - 1 ? 0 : sc + 1;      // the free weight stage, the next one
+            const int sc = j, sf = (j + WRING - 1) % WRING, sn = (j + 1) % WRING;      // this sub-step's weight stage, the free one, the next one
             const int xf = xc == 0 ? XRING - 1 : xc - 1, xn = xc == XRING - 1 ? 0 : xc + 1;      // (xc + 2) % 3 is free
             // the free weight stage takes sub-step i + 3: piece (j + 3) % 4 of group kt + (j + 3) / 4
             const int piece = (j + 3) & 3;
@@ -539,7 +549,7 @@ void prefill_ring_kernel(const PrefillArgs a)
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                if (c == 0) rotate(piece, kt + ((j + 3) >> 2) + 1);
+                if (c == 0) rotate(piece, kt + ((j + 3) >> 2) + 1, SET);
                 if (c == 1) fill_x((sub + 4) >> 1, xf, 2 * par);
                 if (c == 3) fill_x((sub + 4) >> 1, xf, 2 * par + 1);
                 __builtin_amdgcn_sched_barrier(0);
@@ -562,8 +572,8 @@ void prefill_ring_kernel(const PrefillArgs a)
                 // the unpacking of the two tiles (some forty vector instructions) is dealt out between the eight matrix
                 // instructions: a long run of vector instructions from one wave keeps the other wave's matrix
                 // instructions from issuing
-                produce(piece, 0, sf);
-                produce(piece, 1, sf);
+                produce(piece, 0, sf, j == 0 ? SET : SET ^ 1);
+                produce(piece, 1, sf, j == 0 ? SET : SET ^ 1);
 #pragma unroll
                 for (int c = 0; c < 4; ++c) multiply2(op[1], c);
 #pragma unroll
@@ -574,10 +584,15 @@ void prefill_ring_kernel(const PrefillArgs a)
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            sc = sn;
             if (par) xc = xn;
         }
+    };
+    int kt = kt_begin;
+    for (; kt + 1 < kt_end; kt += 2) {
+        group(kt, std::integral_constant<int, 0>());
+        group(kt + 1, std::integral_constant<int, 1>());
     }
+    if (kt < kt_end) group(kt, std::integral_constant<int, 0>());
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));   // the fills past the end have landed before the workgroup's LDS is released
 
     if (!active) return;

@@ -150,19 +150,32 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         u32x2 s, z;          // fp16 scale / zero of the lane's four rows (tiles 0..3), grouped scheme only (z: 64-token path only)
     };
     Stage st[STAGES];
-    auto issue = [&](Stage& b, int sb, int kt) {
-        const long rbc = min(row_block(sb), (long)L.row_blocks - 1);
-        if constexpr (RT == 4) {
+    // A load's address is a scalar base -- the workgroup's first row block of superblock sb at step kt -- plus a 32-bit
+    // byte offset of the lane that only depends on sb (the wave's row block in the superblock, clamped to the
+    // linear's last one for a wave that idles, and the lane's place in a tile): the instruction takes both as they
+    // are, and the arithmetic per load stays on the scalar unit.
+    struct LaneOffs {
+        uint32_t w, s;       // into the codes; into scales / zeros (grouped scheme)
+    };
+    constexpr int LANE_BYTES = V == V_W3 ? 12 : 16, TILE = VInfo<V>::TILE_BYTES;
+    auto lane_offs = [&](int sb) {
+        const int wv = max(0, min(wave, L.row_blocks - 1 - sb * WAVES));
+        LaneOffs o;
+        if constexpr (RT == 4) o.w = (uint32_t)wv * (uint32_t)KT * (4u * TILE) + LANE_BYTES * (uint32_t)lane;
+        else o.w = ((uint32_t)(wv >> 1) * (uint32_t)KT * 4u + 2u * (uint32_t)(wv & 1)) * TILE + LANE_BYTES * (uint32_t)lane;      // half a 64-row block per wave
+        o.s = ((uint32_t)wv * 64u + 4u * (uint32_t)r) * 2u;
+        return o;
+    };
+    auto issue = [&](Stage& b, int sb, int kt, LaneOffs& o) {
+        const uint8_t* wbase = L.codes + ((size_t)sb * (WAVES * RT / 4) * KT + kt) * (4 * (size_t)TILE);
+        asm volatile("" : "+v"(o.w));        // widened next to the loads, so that base and offset stay apart
 #pragma unroll
-            for (int t = 0; t < RT; ++t) b.w[t] = load_tile<V>(L.codes, rbc, KT, kt, t, lane);
-        } else {   // half a 64-row block per wave: tiles 2*(rbc%2) + t
-#pragma unroll
-            for (int t = 0; t < RT; ++t) b.w[t] = load_tile<V>(L.codes, rbc >> 1, KT, kt, 2 * (int)(rbc & 1) + t, lane);
-        }
+        for (int t = 0; t < RT; ++t) b.w[t] = load_tile_at<V>(wbase + o.w + t * TILE);
         if constexpr (SCHEME == SCH_ASYM) {
-            const size_t idx = (size_t)kt * L.N + rbc * 64 + 4 * r;
-            b.s = *reinterpret_cast<const u32x2*>(L.scales + idx);
-            if constexpr (!POST) b.z = *reinterpret_cast<const u32x2*>(L.zeros + idx);
+            const size_t row0 = ((size_t)kt * L.N + (size_t)sb * (WAVES * 64)) * 2;
+            asm volatile("" : "+v"(o.s));
+            b.s = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(L.scales) + row0 + o.s);
+            if constexpr (!POST) b.z = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(L.zeros) + row0 + o.s);
         }
     };
     // Two ways to fold scale and zero in.  POST (up to 32 tokens): multiply raw codes (as fp16
@@ -462,10 +475,11 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     // ---- main loop over chunks; loads for slot i + STAGES are issued right after slot i is consumed,
     // whether that slot lies in this chunk or in the next one (possibly of the next unit)
     Chunk cur = first_chunk(s_begin), nxt = next_chunk(cur);
+    LaneOffs oc = lane_offs(cur.sb), on = lane_offs(nxt.sb);
     fill_x_chunk(cur, 0);
 #pragma unroll
     for (int i = 0; i < STAGES; ++i)
-        if (i < cur.n) issue(st[i], cur.sb, cur.kt0 + i);      // slots past a short chunk stay empty
+        if (i < cur.n) issue(st[i], cur.sb, cur.kt0 + i, oc);      // slots past a short chunk stay empty
     wait_vmem_all_but<0>();
     __syncthreads();
     int buf = 0;
@@ -481,8 +495,8 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             for (int i = 0; i < N; ++i) {
                 compute(st[i % STAGES], buf, i);
                 const int q = i + STAGES;                   // slot to refill
-                if (q < N) issue(st[i % STAGES], cur.sb, cur.kt0 + q);
-                else       issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - N));
+                if (q < N) issue(st[i % STAGES], cur.sb, cur.kt0 + q, oc);
+                else       issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - N), on);
                 if constexpr (WIDE) __builtin_amdgcn_sched_barrier(0);      // keeps a step's operand reads out of earlier steps (register pressure)
             }
             // the next chunk's activations were requested before this chunk's last STAGES refills, which stay in flight
@@ -497,8 +511,8 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             for (int i = 0; i < CHUNK; ++i) {
                 if (i < cur.n && active) compute(st[i % STAGES], buf, i);
                 const int q = i + STAGES;
-                if (q < CHUNK) { if (q < cur.n) issue(st[i % STAGES], cur.sb, cur.kt0 + q); }
-                else           { if (q - CHUNK < nxt.n) issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - CHUNK)); }
+                if (q < CHUNK) { if (q < cur.n) issue(st[i % STAGES], cur.sb, cur.kt0 + q, oc); }
+                else           { if (q - CHUNK < nxt.n) issue(st[i % STAGES], nxt.sb, nxt.kt0 + (q - CHUNK), on); }
             }
             wait_vmem_all_but<0>();
         }
@@ -512,6 +526,8 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         buf ^= 1;
         cur = nxt;
         nxt = next_chunk(nxt);
+        oc = on;
+        if (nxt.sb != cur.sb) on = lane_offs(nxt.sb);
     }
 }
 

@@ -69,6 +69,25 @@ __device__ __forceinline__ WRaw<V> load_tile(const uint8_t* __restrict__ codes, 
     return w;
 }
 
+// The same loads from the lane's own address in the tile (tile start + 12 or 16 bytes per lane).
+template <int V>
+__device__ __forceinline__ WRaw<V> load_tile_at(const uint8_t* __restrict__ p)
+{
+    WRaw<V> w;
+    if constexpr (V == V_W3) {
+        w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x3*>(p));
+    } else if constexpr (V == V_W4) {
+        w.q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    } else if constexpr (V == V_W8 || V == V_I8) {
+        w.q[0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        w.q[1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 1024));
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w.q[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 1024 * j));
+    }
+    return w;
+}
+
 // Output epilogue: activation (lpq_activation) on acc + bias, in fp32.
 __device__ __forceinline__ float apply_activation(float v, int act)
 {

@@ -17,8 +17,9 @@
 // direct global-to-LDS loads (no staging registers, no LDS store instructions); rows are 256 bytes
 // apart and the 16-byte column index is XOR-ed with the row index, so the 16-byte operand reads
 // of 16 consecutive token rows fall on 16 different bank groups.  Tiles t and t+2 of the wave's
-// block are paired into 32-row operands with v_permlane16_swap after dequantisation, so a lane ends
-// up with two consecutive output rows per token.  The overlap of dequantisation, operand reads and
+// block make one 32-row operand, so a lane ends up with two consecutive output rows per token: 3/4-bit
+// codes are loaded in that operand's lane order to begin with (a permutation of which lane fetches which
+// 12 or 16 bytes), 8-bit codes and fp16 weights are paired with v_permlane16_swap after dequantisation.  The overlap of dequantisation, operand reads and
 // matrix instructions is arranged inside each wave (see the main loop).
 //
 // prefill_ring_kernel (8-bit codes and fp16 weights at 256-token tiles): eight wavefronts, two per SIMD,
@@ -131,8 +132,18 @@ void prefill_kernel(const PrefillArgs a)
     constexpr bool HALF_LOADS = (V == V_F16 || V == V_W8 || V == V_I8);
     struct WStep {
         WRaw<V> raw[NW];                             // HALF_LOADS: fp16 uses q[0], q[1]; 8-bit uses q[0]
-        u32x2 s, z;                                  // fp16 scale / zero of the lane's four rows 4r..4r+3
+        u32x2 s, z;                                  // fp16 scale / zero of the lane's four rows 4r..4r+3 (3/4-bit: [0] only, its two rows)
     };
+    // 3/4-bit codes: a 32x32x16 B operand is tiles (p, p + 2) of the wave's block with lanes 0-15 / 16-31 on the two
+    // tiles and lanes 32-63 two k slots further on.  Instead of loading each tile in its own lane order and exchanging
+    // half the registers between lanes afterwards, a lane loads what it will hold: the packed codes of lane
+    // r + 32 * khalf (+ 16 for the second operand) of tile p + 2 * sel, where r = lane % 16, sel = lane / 16 % 2,
+    // khalf = lane / 32 -- the same bytes of the same tiles, in 192- or 256-byte runs per 16 lanes.  The lane's row of
+    // the block is then 4 r + p + 2 sel for pair p.
+    constexpr int TILE = VInfo<V>::TILE_BYTES, LANE_BYTES = TILE / 64;
+    const int sel = (lane >> 4) & 1;
+    uint32_t woff = (uint32_t)(2 * sel * TILE + LANE_BYTES * (r + 32 * (lane >> 5)));
+    uint32_t soff = (uint32_t)(4 * r + 2 * sel) * 2u;
     auto load_w = [&](WStep& w, int kt, int half) {
         if constexpr (V == V_F16) {
 #pragma unroll
@@ -153,12 +164,17 @@ void prefill_kernel(const PrefillArgs a)
                 w.z = *reinterpret_cast<const u32x2*>(zeros + idx);
             }
         } else {
+            // 3/4-bit codes arrive in the 32x32x16 operand's lane order (lane_src above): raw[p] is pair p's k slots
+            // (kq 0, kq 2), raw[p + 2] its (kq 1, kq 3), 16 lanes further on in the tile.  Scalar base, 32-bit lane offset.
+            const uint8_t* wbase = codes + ((size_t)rbc * KT + kt) * (4 * (size_t)TILE);
+            asm volatile("" : "+v"(woff));
 #pragma unroll
-            for (int t = 0; t < NW; ++t) w.raw[t] = load_tile<V>(codes, rbc, KT, kt, t, lane);
-            if constexpr (SCHEME == SCH_ASYM) {
-                const size_t idx = (size_t)kt * N + rbc * 64 + 4 * r;
-                w.s = *reinterpret_cast<const u32x2*>(scales + idx);
-                w.z = *reinterpret_cast<const u32x2*>(zeros + idx);
+            for (int t = 0; t < NW; ++t) w.raw[t] = load_tile_at<V>(wbase + woff + (t & 1) * TILE + (t >> 1) * 16 * LANE_BYTES);
+            if constexpr (SCHEME == SCH_ASYM) {      // rows 4r + 2 sel, 4r + 2 sel + 1: the lane's row of pair 0 and of pair 1
+                const size_t row0 = ((size_t)kt * N + rbc * 64) * 2;
+                asm volatile("" : "+v"(soff));
+                w.s[0] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(scales) + row0 + soff);
+                w.z[0] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(zeros) + row0 + soff);
             }
         }
     };
@@ -170,7 +186,8 @@ void prefill_kernel(const PrefillArgs a)
         } else {
             unpack_codes_half<V>(w.raw[t], half, out, 0);        // 8-bit pieces are loaded one at a time into q[0]
             if constexpr (SCHEME == SCH_ASYM) {
-                const uint32_t sp = w.s[t >> 1], zp = w.z[t >> 1];
+                // 8-bit tiles keep their own lane order (tile t: row 4r + t); 3/4-bit operand t belongs to pair t & 1
+                const uint32_t sp = w.s[HALF_LOADS ? t >> 1 : 0], zp = w.z[HALF_LOADS ? t >> 1 : 0];
                 const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
                 const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
                 apply_scale_zero_half(out, __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
@@ -188,6 +205,7 @@ void prefill_kernel(const PrefillArgs a)
     WStep ws[2];                 // HALF_LOADS: raw half steps by parity; else this step's and the next step's codes
     auto unpack_tile = [&](const WStep& w, int t, int half, int dst) { operands(w, t, half, wb[dst][t]); };
     auto pair_tiles = [&](int p, int dst) {
+        if constexpr (!HALF_LOADS) return;           // 3/4-bit codes were loaded in operand order
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) pair_tiles_for_mfma32(wb[dst][p][jj], wb[dst][p + 2][jj]);
     };

@@ -188,7 +188,7 @@ uint32_t variant_cost_x16(int variant)
 void rows_plan(const LinDesc& L, int tok_tiles, int cus, int* tiles, int* splits)
 {
     static const double tile_us[5] = {0.024, 0.032, 0.064, 0.064, 0.128};     // per tile and step, by variant
-    const int KT = L.K / 128, n_tiles = L.N / 16;
+    const int KT = L.kt, n_tiles = L.N / 16;
     double best = 1e30;
     *tiles = 4;
     *splits = 1;
@@ -301,19 +301,18 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
             L.y = static_cast<uint16_t*>(calls[c].y);
             L.bias = static_cast<const uint16_t*>(w.bias);
             L.residual = static_cast<const uint16_t*>(calls[c].residual);
-            L.act = calls[c].act;
+            L.act = (uint8_t)calls[c].act;
             L.aux = (int32_t)sums_off16;
             sums_off16 += prepared_bytes(w.d, last_rows, in_place) / 16;
-            L.K = w.d.K;
+            if (w.d.K / 128 > 0xffff) return LPQ_ERR_UNSUPPORTED;          // the descriptor keeps K / 128 in 16 bits
+            L.kt = (uint16_t)(w.d.K / 128);
             L.N = w.d.N;
-            L.variant = variant_of(w.d);
+            L.variant = (uint8_t)variant_of(w.d);
             const int rows = decode_rows_per_wave(L.variant);
-            L.row_blocks = L.N / rows;
-            L.row_superblocks = (L.row_blocks + waves - 1) / waves;
             const uint32_t step_bytes = (uint32_t)(waves * rows) * (128u * (uint32_t)w.d.bits / 8u + (w.d.scheme == LPQ_ASYM_GROUP ? 4u : 0u));
             L.step_weight = step_bytes * variant_cost_x16(L.variant);
             L.cum_weight = total;
-            total += (uint64_t)L.step_weight * (uint64_t)L.row_superblocks * (uint64_t)(L.K / 128);
+            total += (uint64_t)L.step_weight * (uint64_t)lin_row_superblocks(L, waves) * (uint64_t)L.kt;
         }
         if (total >= ((uint64_t)1 << 50)) return LPQ_ERR_UNSUPPORTED;
         a.total_weight = total;
@@ -328,7 +327,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         // pass to find most of them in the caches; measured on a decoder layer, 7-15 % faster than the even-share kernel.
         if (stream_bytes <= rows_max_bytes && (M <= 32 || (M <= 64 && stream_bytes <= std::min<int64_t>(rows_max_bytes, (int64_t)128 << 20)))) {
             // longest K first: the last workgroups to start are then the shortest
-            std::stable_sort(a.lin, a.lin + a.n_lin, [](const LinDesc& x, const LinDesc& y) { return x.K > y.K; });
+            std::stable_sort(a.lin, a.lin + a.n_lin, [](const LinDesc& x, const LinDesc& y) { return x.kt > y.kt; });
             int cus = 0;
             st = device_cus(&cus);
             if (st != LPQ_OK) return st;
@@ -339,7 +338,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
                 p.m0 = 0;
                 for (int i = 0; i < p.n_lin; ++i) {
                     LinDesc& L = p.lin[i];
-                    L.x += (size_t)m0 * L.K;
+                    L.x += (size_t)m0 * L.K();
                     L.y += (size_t)m0 * L.N;
                     if (L.residual) L.residual += (size_t)m0 * L.N;
                 }
@@ -348,7 +347,7 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
                 if (p.n_lin == 1) rows_plan(p.lin[0], tok_tiles, cus, &tiles, &splits1);
                 const int forced = g_rows_tiles.load();
                 if (forced >= 2 && forced <= 5 && forced != tiles) tiles = forced, splits1 = 0;
-                auto group_tiles = [&](const LinDesc& L) { return (L.variant == 4 && tiles > 2) ? 2 : tiles; };
+                auto group_tiles = [&](const LinDesc& L) { return rows_group_tiles(L.variant, tiles); };
                 for (int i = 0; i < p.n_lin; ++i)
                     if ((p.lin[i].N / 16) % group_tiles(p.lin[i]) != 0) tiles = 4, splits1 = 0;    // groups must tile every linear exactly
                 int64_t blocks = 0, row_blocks = 0;
@@ -356,16 +355,15 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
                 int64_t partial_floats = 0;
                 for (int i = 0; i < p.n_lin; ++i) {
                     LinDesc& L = p.lin[i];
-                    L.row_blocks = L.N / 16 / group_tiles(L);
                     // K splits (L.aux) of a launch of several linears: only if it leaves most compute units without a
                     // workgroup, and only down to 32 steps per workgroup
-                    const int KT = L.K / 128;
+                    const int KT = L.kt;
                     const int want = (int)std::max<int64_t>(1, 320 / std::max<int64_t>(1, row_blocks));
                     L.aux = splits1 > 0 ? splits1 : std::max(1, std::min(std::min(want, KT / 32), 8));
                     L.step_weight = (uint32_t)partial_floats;             // float offset of this linear's partial sums
                     if (L.aux > 1) partial_floats += (int64_t)L.aux * 16 * tok_tiles * L.N;
                     L.cum_weight = (uint64_t)blocks;
-                    blocks += (int64_t)L.row_blocks * L.aux;
+                    blocks += (int64_t)rows_row_blocks(L, tiles) * L.aux;
                 }
                 if (blocks > 0x7fffffffLL || partial_floats > 0x7fffffffLL) return LPQ_ERR_UNSUPPORTED;
                 if (partial_floats) {
@@ -384,8 +382,10 @@ lpq_status run_decode(const std::vector<LinearCall>& calls, int32_t M, hipStream
         // steps: thinner ranges stream no faster and only multiply the pieces the fix-up pass has to add.
         const int min_steps = M <= 16 ? 16 : 8;              // a 64-token step is 3x as long
         int64_t steps = 0;
-        for (int i = 0; i < a.n_lin; ++i) steps += (int64_t)a.lin[i].row_superblocks * (a.lin[i].K / 128);
+        for (int i = 0; i < a.n_lin; ++i) steps += (int64_t)lin_row_superblocks(a.lin[i], waves) * a.lin[i].kt;
         a.n_blocks = (int32_t)std::max<int64_t>(1, std::min<int64_t>(n_blocks, steps / min_steps));
+        a.range_q = a.total_weight / (uint64_t)a.n_blocks;
+        a.range_rem = (uint32_t)(a.total_weight % (uint64_t)a.n_blocks);
         if (in_place)
             for (int i = 0; i < a.n_lin; ++i)
                 if (a.lin[i].variant == 0) a.lin[i].variant = V_W3_INPLACE;

@@ -25,16 +25,17 @@ struct LinDesc {
     const uint16_t* residual;   // fp16 [M][N] added to the output before its one rounding, or null
     uint64_t cum_weight;
     uint32_t step_weight;
-    int32_t K, N;
-    int32_t variant;        // V_W3 .. V_F16
-    int32_t row_blocks;     // N / rows per wave (64; 32 for fp16 weights)
-    int32_t row_superblocks;// ceil(row_blocks / waves per workgroup)
-    int32_t act;            // lpq_activation applied to acc + bias (before the residual)
+    int32_t N;
     int32_t aux;            // stage-wide kernel: offset of the linear's prepared activations in DecodeArgs::prep, in 16-byte units;
                             // small-launch kernel: number of K splits
+    uint16_t kt;            // K / 128 (K < 2^23)
+    uint8_t variant;        // V_W3 .. V_F16, V_W3_INPLACE
+    uint8_t act;            // lpq_activation applied to acc + bias (before the residual)
+    __host__ __device__ int K() const { return (int)kt * 128; }
 };
+static_assert(sizeof(LinDesc) == 80, "48 of these and the header of DecodeArgs stay under 4 KB of kernel arguments");
 
-enum { MAX_LIN_PER_LAUNCH = 40 };   // keeps DecodeArgs under 4 KB of kernel arguments
+enum { MAX_LIN_PER_LAUNCH = 48 };   // keeps DecodeArgs under 4 KB of kernel arguments (a stage of twelve layers in one launch)
 
 // Even-share decomposition: the launch's total weight is cut into n_blocks equal ranges; workgroup
 // b streams the steps whose start offset falls in [b, b+1) * total / n_blocks.  A (linear, row
@@ -45,6 +46,8 @@ struct DecodeArgs {
     int32_t n_blocks, slot_floats;       // slot_floats: floats per partial tile = 64 tokens x rows per workgroup
     int32_t row_tiles, pad;              // small-launch kernel only: 16-row tiles per workgroup (2 .. 5; fp16 weights: at most 2)
     uint64_t total_weight;
+    uint64_t range_q;                    // total_weight / n_blocks and
+    uint32_t range_rem, pad2;            // total_weight % n_blocks: range b begins at range_q * b + range_rem * b / n_blocks
     float* partial;
     const uint16_t* prep;                // stage-wide kernel, up to 32 token rows per pass: what decode_prepare_kernel leaves
                                          // (the activations' group sums; for 3-bit weights the activations, scaled)
@@ -113,6 +116,12 @@ struct PrefillArgs {
 
 // rows of W one decode wavefront covers, per variant (fp16 rows are 4x-16x bigger, so fewer of them)
 __host__ __device__ inline int decode_rows_per_wave(int variant) { return variant == 4 ? 32 : 64; }
+// stage-wide decode kernel: a wave's row blocks of a linear (N / rows per wave) and the workgroups' superblocks of them
+__host__ __device__ inline int lin_row_blocks(const LinDesc& L) { return L.N >> (L.variant == 4 ? 5 : 6); }
+__host__ __device__ inline int lin_row_superblocks(const LinDesc& L, int waves) { return (lin_row_blocks(L) + waves - 1) / waves; }
+// small-launch decode kernel: 16-row tiles per workgroup (fp16 weights: at most two) and the groups of them in a linear
+__host__ __device__ inline int rows_group_tiles(int variant, int row_tiles) { return (variant == 4 && row_tiles > 2) ? 2 : row_tiles; }
+__host__ __device__ inline int rows_row_blocks(const LinDesc& L, int row_tiles) { return L.N / 16 / rows_group_tiles(L.variant, row_tiles); }
 
 int variant_of(const lpq_qdesc& d);           // -1 if the (bits, scheme) pair is not supported
 size_t tile_bytes_of(int variant);

@@ -107,7 +107,8 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     constexpr int STAGE_LOADS = RT * (VInfo<V>::TILE_BYTES >= 1024 ? VInfo<V>::TILE_BYTES / 1024 : 1) + (SCHEME == SCH_ASYM ? (POST ? 1 : 2) : 0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, kq = lane >> 4;
-    const int KT = L.K / 128;
+    const int KT = L.kt;
+    const int row_blocks = L.N / (V == V_F16 ? 32 : 64);     // of one wave each
 
     auto first_chunk = [&](long s) {
         Chunk c;
@@ -159,7 +160,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     };
     constexpr int LANE_BYTES = V == V_W3 ? 12 : 16, TILE = VInfo<V>::TILE_BYTES;
     auto lane_offs = [&](int sb) {
-        const int wv = max(0, min(wave, L.row_blocks - 1 - sb * WAVES));
+        const int wv = max(0, min(wave, row_blocks - 1 - sb * WAVES));
         LaneOffs o;
         if constexpr (RT == 4) o.w = (uint32_t)wv * (uint32_t)KT * (4u * TILE) + LANE_BYTES * (uint32_t)lane;
         else o.w = ((uint32_t)(wv >> 1) * (uint32_t)KT * 4u + 2u * (uint32_t)(wv & 1)) * TILE + LANE_BYTES * (uint32_t)lane;      // half a 64-row block per wave
@@ -295,7 +296,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     };
 
     // INPLACE: rows 0 .. of this pass of the activations that decode_prepare_kernel scaled, behind the linear's 32 rows of group sums
-    const uint16_t* xrows = INPLACE ? prep + (size_t)L.aux * 8 + (size_t)32 * group_sums_stride(L.K) : L.x;
+    const uint16_t* xrows = INPLACE ? prep + (size_t)L.aux * 8 + (size_t)32 * group_sums_stride(L.K()) : L.x;
     const int xrow0 = INPLACE ? 0 : m0, xrow_last = INPLACE ? min(TOK, M - m0) - 1 : M - 1;
     // ---- activation staging: the x columns of one chunk, shared by the workgroup through LDS.
     // Global-to-LDS loads, 1 KB per wave and instruction (four 256-byte row segments); a lane fetches
@@ -308,7 +309,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
             const int q = XQ * wave + i;
             const int u = 4 * q + (lane >> 4), row = u / CHUNK, seg = min(u % CHUNK, c.n - 1);
             const int c16 = (lane & 15) ^ (row & 15);
-            const uint16_t* g = xrows + (size_t)min(xrow0 + row, xrow_last) * L.K + (size_t)(c.kt0 + seg) * 128 + c16 * 8;
+            const uint16_t* g = xrows + (size_t)min(xrow0 + row, xrow_last) * L.K() + (size_t)(c.kt0 + seg) * 128 + c16 * 8;
             __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)(&sm.x[buf][0][0] + 512 * q), 16, 0, 0);
         }
         asm volatile("" ::: "memory");      // weight loads issued later stay later: vmcnt counts in issue order
@@ -317,7 +318,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     // ---- end of a unit: lane holds tokens 4*kq + v of RT consecutive rows starting at nbase
     auto finish_unit = [&](int sb, float* __restrict__ partial) {
         const long rb = row_block(sb);
-        if (WIDE && rb < L.row_blocks) {
+        if (WIDE && rb < row_blocks) {
             // lane (n = lane%32, half = lane/32) holds tokens 32*m2 + 8*(v/4) + 4*half + v%4 of NP consecutive rows:
             // tile pair p of a 4-tile block is tiles (p, p+2), i.e. rows 4r + p (n < 16) and 4r + 2 + p (n >= 16)
             const int ncol = lane & 31;
@@ -360,7 +361,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                     }
                 }
         }
-        if (!WIDE && rb < L.row_blocks) {
+        if (!WIDE && rb < row_blocks) {
             const long nbase = (RT == 4) ? rb * 64 + 4 * r : (rb >> 1) * 64 + 4 * r + 2 * (rb & 1);
             if constexpr (POST) {
                 // The accumulators hold y * 2^-24 without the zero term: the grouped scheme's sum over groups of
@@ -372,7 +373,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                 static_assert(RT == 4, "the zero term reads the zeros of a 64-row block");
                 const long u0 = (long)sb * KT;
                 const int g_lo = (int)(max(u0, s_begin) - u0), g_hi = (int)(min(u0 + KT, s_end) - u0);
-                const int stride = group_sums_stride(L.K);
+                const int stride = group_sums_stride(L.K());
                 const uint16_t* xs = prep + (size_t)L.aux * 8;
                 const int cnt = min(TOK, M - m0);                            // token rows the sums were taken for
                 float undo[MT][4];
@@ -485,7 +486,7 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
     int buf = 0;
     while (cur.n > 0) {
         if (nxt.n > 0) fill_x_chunk(nxt, buf ^ 1);
-        const bool active = row_block(cur.sb) < L.row_blocks;
+        const bool active = row_block(cur.sb) < row_blocks;
         // steady state: a chunk of N steps (a full one; in the 16-step form also a linear's remainder of exactly 8)
         // followed by enough steps to refill every slot -- no per-step conditions, so the whole chunk is one
         // schedulable block
@@ -537,6 +538,18 @@ struct Cursor {
     long step;       // block step inside the linear: sb * KT + kt
 };
 
+// floor(n / d) for n < 2^52 through one double-precision division: the quotient's integer part is off by at most
+// one, which the product shows.  (The 64-bit integer division it replaces is some two hundred instructions, and the
+// kernels here do several in a row before their first load.)
+__device__ __forceinline__ uint64_t div_floor(uint64_t n, uint32_t d)
+{
+    uint64_t q = (uint64_t)((double)n / (double)d);
+    const uint64_t p = q * d;
+    if (p > n) --q;
+    else if (n - p >= d) ++q;
+    return q;
+}
+
 // first step whose start offset is >= pos (pos <= total weight)
 __device__ __forceinline__ Cursor first_step_at(const DecodeArgs& a, uint64_t pos)
 {
@@ -547,13 +560,14 @@ __device__ __forceinline__ Cursor first_step_at(const DecodeArgs& a, uint64_t po
     }
     const LinDesc& L = a.lin[li];
     const uint64_t off = pos - L.cum_weight;
-    Cursor c = {li, (long)((off + L.step_weight - 1) / L.step_weight)};
+    Cursor c = {li, (long)div_floor(off + L.step_weight - 1, L.step_weight)};
     return c;
 }
 
 __device__ __forceinline__ uint64_t range_begin(const DecodeArgs& a, int b)
 {
-    return a.total_weight * (uint64_t)b / (uint64_t)a.n_blocks;      // total_weight < 2^50, b < 2^13
+    // floor(total_weight * b / n_blocks), total_weight < 2^50, b <= n_blocks < 2^13: the remainder's share needs 32 bits only
+    return a.range_q * (uint64_t)b + (a.range_rem * (uint32_t)b) / (uint32_t)a.n_blocks;
 }
 
 // What a decode launch of up to 32 token rows per pass needs from its activations beforehand.  Workgroup
@@ -584,12 +598,12 @@ __global__ __launch_bounds__(GS_THREADS) void decode_prepare_kernel(const Decode
     const bool scaled = ANY_INPLACE && L.variant == V_W3_INPLACE;
     constexpr int width = 3;
     const int row = blockIdx.y, tok = a.m0 + row;
-    const int KT = L.K / 128, GP = (KT + 15) & ~15, rounds = (GP + GS_GROUPS - 1) / GS_GROUPS;
+    const int KT = L.K() / 128, GP = (KT + 15) & ~15, rounds = (GP + GS_GROUPS - 1) / GS_GROUPS;
     uint16_t* base = prep + (size_t)L.aux * 8;
-    uint16_t* dst = base + (size_t)row * group_sums_stride(L.K);
-    uint16_t* xq = base + (size_t)32 * group_sums_stride(L.K) + (size_t)row * L.K;
+    uint16_t* dst = base + (size_t)row * group_sums_stride(L.K());
+    uint16_t* xq = base + (size_t)32 * group_sums_stride(L.K()) + (size_t)row * L.K();
     const int l16 = threadIdx.x & 15, g0 = threadIdx.x >> 4;
-    const uint16_t* src = L.x + (size_t)tok * L.K + 8 * l16;
+    const uint16_t* src = L.x + (size_t)tok * L.K() + 8 * l16;
     auto load = [&](int g) { return *reinterpret_cast<const h8*>(src + (size_t)min(g, KT - 1) * 128); };
     auto add16 = [&](h8 v, bool valid) {              // a group's sum, the same value in all sixteen lanes
         float sum = (((float)v[0] + (float)v[1]) + ((float)v[2] + (float)v[3])) + (((float)v[4] + (float)v[5]) + ((float)v[6] + (float)v[7]));
@@ -699,7 +713,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void decode_kernel(const Dec
     float* slot_last = slot_first + a.slot_floats;
     while (c.li < a.n_lin) {
         const LinDesc& L = a.lin[c.li];
-        const long steps = (long)L.row_superblocks * (L.K / 128);
+        const long steps = (long)lin_row_superblocks(L, WAVES) * L.kt;
         if (c.step >= steps) { ++c.li; c.step = 0; continue; }
         const uint64_t start = L.cum_weight + (uint64_t)c.step * L.step_weight;
         if (start >= hi) break;
@@ -728,8 +742,8 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
     const uint64_t X = range_begin(a, b + 1);
     const Cursor c = first_step_at(a, X);
     const LinDesc& L = a.lin[c.li];
-    const int KT = L.K / 128;
-    const long steps = (long)L.row_superblocks * KT;
+    const int KT = L.kt;
+    const long steps = (long)lin_row_superblocks(L, 8) * KT;       // this kernel follows the eight-wave launches only
     if (c.step >= steps || c.step % KT == 0) return;            // boundary falls between units
     const int sb = (int)(c.step / KT);
     const uint64_t unit_begin = L.cum_weight + (uint64_t)sb * KT * L.step_weight;
@@ -752,34 +766,45 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
     const int n_items = m_cnt * (rows_wg / 4);
     auto for_each_piece = [&](auto&& fn) {         // slot 2b+1, then slot 2b' of every later non-empty range that starts in this unit
         fn(2 * b + 1);
+        uint64_t lo = X;
         for (int bb = b + 1; bb < a.n_blocks; ++bb) {
-            const uint64_t lo = range_begin(a, bb);
-            const uint64_t first = L.cum_weight + (uint64_t)((lo - L.cum_weight + L.step_weight - 1) / L.step_weight) * L.step_weight;
+            const uint64_t next = range_begin(a, bb + 1);
+            const uint64_t first = L.cum_weight + div_floor(lo - L.cum_weight + L.step_weight - 1, L.step_weight) * L.step_weight;
             if (first >= unit_end) break;
-            if (first >= range_begin(a, bb + 1)) continue;      // empty range: it wrote nothing
-            fn(2 * bb);
+            if (first < next) fn(2 * bb);                       // else an empty range: it wrote nothing
+            lo = next;
         }
     };
-    auto finish = [&](int idx, f4 sv) {            // bias, activation, residual, one rounding
+    // bias and residual of an item do not depend on the pieces: they are requested ahead of them, so that their
+    // round of memory latency runs beside the pieces' instead of behind it
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    struct Extra { h4 bias, res; };
+    auto fetch = [&](int idx) {
+        Extra e = {h4{0, 0, 0, 0}, h4{0, 0, 0, 0}};
+        if (idx >= n_items) return e;
+        const int tok = idx / (rows_wg / 4), n4 = (idx % (rows_wg / 4)) * 4;
+        if (nbase + n4 >= L.N) return e;
+        if (L.bias) e.bias = *reinterpret_cast<const h4*>(L.bias + nbase + n4);
+        if (L.residual) e.res = *reinterpret_cast<const h4*>(L.residual + (size_t)(a.m0 + tok) * L.N + nbase + n4);
+        return e;
+    };
+    auto finish = [&](int idx, f4 sv, const Extra& e) {            // bias, activation, residual, one rounding
         if (idx >= n_items) return;
         const int tok = idx / (rows_wg / 4), n4 = (idx % (rows_wg / 4)) * 4;
         if (nbase + n4 >= L.N) return;
         if (L.bias)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) sv[v] += (float)__builtin_bit_cast(_Float16, L.bias[nbase + n4 + v]);
+            for (int v = 0; v < 4; ++v) sv[v] += (float)e.bias[v];
 #pragma unroll
         for (int v = 0; v < 4; ++v) sv[v] = apply_activation(sv[v], L.act);
-        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-        if (L.residual) {
-            const h4 res = *reinterpret_cast<const h4*>(L.residual + (size_t)(a.m0 + tok) * L.N + nbase + n4);
+        if (L.residual)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) sv[v] += (float)res[v];
-        }
+            for (int v = 0; v < 4; ++v) sv[v] += (float)e.res[v];
         const h4 out = {(_Float16)sv[0], (_Float16)sv[1], (_Float16)sv[2], (_Float16)sv[3]};
         *reinterpret_cast<h4*>(L.y + (size_t)(a.m0 + tok) * L.N + nbase + n4) = out;
     };
     // ranges that overlap the unit (an upper bound that needs no walk): unit weight / range weight, plus both ends
-    const uint64_t n_pieces = (uint64_t)KT * L.step_weight * (uint64_t)a.n_blocks / a.total_weight + 2;
+    const uint64_t n_pieces = (uint64_t)((double)((uint64_t)KT * L.step_weight) / (double)max(a.range_q, (uint64_t)1)) + 2;
     // blockIdx.y picks the pass: a unit of 64 tokens x 512 rows is eight passes, added by eight workgroups
     const int base = (int)blockIdx.y * 1024;
     if (base < n_items) {
@@ -792,6 +817,9 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
                 off[i] = (size_t)(idx / (rows_wg / 4)) * stride + (idx % (rows_wg / 4)) * 4;
                 sum[i] = f4{0, 0, 0, 0};
             }
+            Extra extra[PER_THREAD];
+#pragma unroll
+            for (int i = 0; i < PER_THREAD; ++i) extra[i] = fetch(base + threadIdx.x + 256 * i);
             for_each_piece([&](int slot) {         // all of a piece's loads are issued before the first add
                 const float* p = a.partial + (size_t)slot * a.slot_floats;
                 f4 v[PER_THREAD];
@@ -803,7 +831,7 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
                     if (base + threadIdx.x + 256 * i < n_items) sum[i] += v[i];
             });
 #pragma unroll
-            for (int i = 0; i < PER_THREAD; ++i) finish(base + threadIdx.x + 256 * i, sum[i]);
+            for (int i = 0; i < PER_THREAD; ++i) finish(base + threadIdx.x + 256 * i, sum[i], extra[i]);
             return;
         }
         f4 sum[PER_LANE];
@@ -833,7 +861,8 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
             for (int i = 0; i < 4; ++i) wsum[wave][lane + 64 * i] = sum[4 * q + i];
             __syncthreads();
             finish(base + 256 * q + threadIdx.x,
-                   (wsum[0][threadIdx.x] + wsum[1][threadIdx.x]) + (wsum[2][threadIdx.x] + wsum[3][threadIdx.x]));
+                   (wsum[0][threadIdx.x] + wsum[1][threadIdx.x]) + (wsum[2][threadIdx.x] + wsum[3][threadIdx.x]),
+                   fetch(base + 256 * q + threadIdx.x));
         }
     }
 }
@@ -850,7 +879,7 @@ __global__ __launch_bounds__(256) void decode_fixup_kernel(const DecodeArgs a)
 // accumulators are added through LDS at the end, in wave order.  A linear with few tiles and a long K (the
 // second feed-forward matrix) is also split over L.aux workgroups per group, each taking a range of the steps
 // and leaving fp32 sums in partial[split][16 MT][N] (at float offset L.step_weight of the launch's partial buffer)
-// for a small second kernel; otherwise there are no partial tiles and no second kernel.  L.row_blocks is the
+// for a small second kernel; otherwise there are no partial tiles and no second kernel.  rows_row_blocks(L, row_tiles) is the
 // linear's number of groups, a.lin[i].cum_weight the number of workgroups of the linears before i, a.n_blocks
 // their total.
 template <int V, int WAVES, int TILES, int MT>
@@ -868,7 +897,7 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // a scalar: the row block and the tile addresses derive from it
     const int r = lane & 15, kq = lane >> 4;
-    const int KT = L.K / 128;
+    const int KT = L.K() / 128;
     const long g0 = rb * RT;                                        // first tile; tile g is tile g % 4 of 64-row block g / 4
     // the workgroup's steps [kt0, kt1): all of them, or the split's share (the first KT % splits take one more)
     const int splits = L.aux, share = KT / splits, extra = KT % splits;
@@ -876,7 +905,7 @@ __device__ __forceinline__ void run_rows(const LinDesc& L, int M, long rb, int s
     const int n_w = kt1 - kt0 > wave ? (kt1 - kt0 - wave + WAVES - 1) / WAVES : 0;      // this wave's steps
     const uint16_t* __restrict__ xrow[MT];                          // token tile m holds rows 16 m .. 16 m + 15; rows past M repeat the last one
 #pragma unroll
-    for (int m = 0; m < MT; ++m) xrow[m] = L.x + (size_t)min(r + 16 * m, M - 1) * L.K + 8 * kq;
+    for (int m = 0; m < MT; ++m) xrow[m] = L.x + (size_t)min(r + 16 * m, M - 1) * L.K() + 8 * kq;
 
     struct Stage {
         WRaw<V> w[RT];
@@ -1044,8 +1073,9 @@ __global__ __launch_bounds__(64 * WAVES, (MT == 2 || TILES == 5) ? 1 : 8 / WAVES
     }
     const LinDesc& L = a.lin[li];
     const long wg = (long)b - (long)L.cum_weight;          // split-major: a split's groups are neighbours
-    const long rb = wg % L.row_blocks;
-    const int split = (int)(wg / L.row_blocks);
+    const int row_blocks = rows_row_blocks(L, a.row_tiles);
+    const long rb = wg % row_blocks;
+    const int split = (int)(wg / row_blocks);
     float* partial = a.partial + L.step_weight;
     switch (L.variant) {
     case V_W3: run_rows<V_W3, WAVES, TILES, MT>(L, a.M, rb, split, partial, red); break;
@@ -1089,7 +1119,7 @@ __global__ __launch_bounds__(256) void decode_rows_reduce_kernel(const DecodeArg
 // Scratch of the entry point that allocates nothing (lpq_stage_linears_noalloc): what the library otherwise keeps in
 // its growing workspace -- the fp32 partial tiles of the launches and the prepared activations of a decode launch.
 // 128 MiB per device, held until the process ends.  A decode launch of up to 32 token rows takes 32 MiB of partial
-// tiles (2 slots x 256 workgroups x 32 rows x 512 columns x 4 bytes), group sums (40 linears of K = 57344: 2.2 MiB)
+// tiles (2 slots x 256 workgroups x 32 rows x 512 columns x 4 bytes), group sums (48 linears of K = 57344: 2.7 MiB)
 // and, at up to 16 rows, 2 bytes per token row and column of scaled activations for 3-bit linears read in place (ten
 // BLOOM-176B-shaped layers at 16 rows: 31 MiB); passes of 64 rows take 64 MiB of partial tiles.  Nothing in it has to
 // start at zero:
@@ -1151,7 +1181,7 @@ static hipError_t launch_waves(const DecodeArgs& a, hipStream_t s)
     // on a 3-bit stage of K = 14336 and 57344), but a linear's K then has to be whole or half chunks: any other
     // remainder runs in the conditional form of the main loop, which costs more than the barriers saved.
     bool whole = true;
-    for (int li = 0; li < a.n_lin; ++li) whole = whole && (a.lin[li].K / 128) % 8 == 0;
+    for (int li = 0; li < a.n_lin; ++li) whole = whole && a.lin[li].kt % 8 == 0;
     return whole ? launch_tok<16, WAVES, 16>(a, s) : launch_tok<16, WAVES, 8>(a, s);
 }
 

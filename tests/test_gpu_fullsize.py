@@ -129,8 +129,9 @@ def test_bench_config_full_stage(orc):
 @pytest.mark.parametrize("ci", [2, 3, 4], ids=["opt30b_12_layers", "opt66b_10_layers", "bloom176b_10_layers"])
 def test_other_configs_whole_stage(orc, ci):
     """configs[2..4] as whole stages, at every decode micro-batch of their sweeps and at their prefill micro-batch:
-    the launch plan (even-share ranges, workgroups per XCD, launches of at most 40 linears -- configs[2] has 48 and
-    takes two) depends on the whole list of linears, so a sub-stage would test another plan."""
+    the launch plan (even-share ranges, workgroups per XCD, one decode launch of up to 48 linears -- configs[2] has
+    48 -- and one prefill launch per storage variant) depends on the whole list of linears, so a sub-stage would test
+    another plan."""
     cfg = wl.CONFIGS[ci]
     _run_config(orc, cfg, list(range(len(cfg["layers"]))), cfg["decode_Ms"], cfg["prefill_M"])
 

@@ -301,13 +301,13 @@ def test_stage_mixed_bits_small(orc, phase, M, decode_kernel_choice):
 @pytest.mark.parametrize("phase,M", [(lpq.LPQ_DECODE, 3), (lpq.LPQ_DECODE, 20), (lpq.LPQ_DECODE, 70), (lpq.LPQ_PREFILL, 130), (lpq.LPQ_PREFILL, 300)],
                          ids=["decode_M3", "decode_M20", "decode_M70", "prefill_M130", "prefill_M300"])
 def test_stage_with_more_linears_than_one_launch_holds(orc, phase, M, decode_kernel_choice):
-    """A stage of 12 layers = 48 linears: a grouped launch holds at most 40, so the decode phase takes two launches
-    that share the workspace, and a storage variant with more than 40 linears would take two prefill launches (here
-    the 4-bit variant has 44).  Every element of every output is checked."""
+    """A stage of 13 layers = 52 linears: a grouped decode launch holds at most 48, so the decode phase takes two
+    launches that share the workspace, and a storage variant with more than 40 linears takes two prefill launches
+    (here the 4-bit variant has 44).  Every element of every output is checked."""
     if decode_kernel_choice in ("rows_3", "rows_5"):
         pytest.skip("the stage's linears have 16, 32 and 48 tiles: no group of 3 or 5 fits them all")
-    specs = [(4, 1)] * 11 + [(3, 1)]
-    stage, ys, host = _build_stage("stage_48", 256, 512, 768, specs, M, True)
+    specs = [(4, 1)] * 11 + [(3, 1)] * 2
+    stage, ys, host = _build_stage("stage_52", 256, 512, 768, specs, M, True)
     lpq.lpq_stage_linears(stage, phase)
     for li, (bits, scheme) in enumerate(specs):
         for name in wl.LINEARS:

@@ -181,7 +181,8 @@ lpq_status lpq_qlinear_prefill(const lpq_qweight *w, const void *x, int32_t M, v
 
 /* The same function at a decode micro-batch (Sec. 4.3: M = xi rows, one token per sequence):
  * packed weights are streamed once from HBM and unpacked in registers.  Correct for every
- * M >= 1 (rows are processed 64 at a time).  Errors as for lpq_qlinear_prefill, plus BUFSIZE. */
+ * M >= 1 (rows are processed 64 at a time).  Errors as for lpq_qlinear_prefill, plus BUFSIZE, and UNSUPPORTED
+ * for K >= 2^23 (the decode kernels' descriptors keep K / 128 in 16 bits). */
 lpq_status lpq_qlinear_decode(const lpq_qweight *w, const void *x, int32_t M, void *y, void *hip_stream);
 
 /* One linear with a fused epilogue: y = fp16(act(x . w~^T + bias) + residual), one rounding.  `phase`
@@ -195,7 +196,8 @@ lpq_status lpq_qlinear_fused(const lpq_qweight *w, const void *x, int32_t M, voi
  * latency is the sum over its layers of the per-layer latency at that layer's precision).
  *   layers: host array [n_layers];  io: host array [n_layers] of device pointers.
  *   phase:  LPQ_PREFILL or LPQ_DECODE selects the kernel family; M as above.
- * In the decode phase the whole stage is one grouped launch (plus one split-K reduction).
+ * In the decode phase a stage of up to twelve layers is one grouped launch (with a short kernel that prepares the
+ * activations in front and a fix-up pass behind); a longer stage takes one such launch per twelve layers or fewer.
  * Errors: as above; nothing is launched unless every layer validates. */
 lpq_status lpq_stage_linears(const lpq_layer *layers, int32_t n_layers, lpq_phase phase, int32_t M,
                              const lpq_layer_io *io, void *hip_stream);

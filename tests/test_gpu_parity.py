@@ -178,6 +178,50 @@ def test_decode_zero_term_very_long_rows(orc, bits, scheme):
         lpq.lpq_set_decode_routing(-1, -1)
 
 
+@pytest.mark.parametrize("bits,scheme", [(3, 1), (8, 2)], ids=["w3", "i8"])
+def test_decode_longest_rows_and_the_limit_on_k(orc, bits, scheme):
+    """The decode kernels' descriptors keep K / 128 in 16 bits.  At the largest K they hold (65535 steps of 128 columns)
+    one-hot activation rows read single columns of the dequantised weight out of the product -- first, last and middle
+    groups -- and each is compared with the oracle on that group's 128 columns alone (quantisation is per group);
+    one step more is refused with LPQ_ERR_UNSUPPORTED and nothing is written."""
+    import torch
+    N, KT = 64, 65535
+    K = KT * 128
+    gen = torch.Generator(device="cuda").manual_seed(23)
+    w = torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float16)
+    qw = lpq.lpq_quantize_pack(w, bits, scheme)
+    cols = [0, 127, 128, 5 * 128 + 77, (KT // 2) * 128 + 3, (KT - 1) * 128, K - 1]
+    x = torch.zeros((len(cols), K), dtype=torch.float16, device="cuda")
+    for i, c in enumerate(cols):
+        x[i, c] = 1.0 + i / 8.0
+    y = lpq.lpq_qlinear_decode(qw, x)
+    torch.cuda.synchronize()
+    y_host = y.cpu().numpy().astype(np.float64)
+    for i, c in enumerate(cols):
+        g = c // 128
+        if scheme == 2:      # one scale per row over the whole of K: the oracle needs the row's largest magnitude, kept in a 129th group
+            wmax = w.abs().amax(dim=1, keepdim=True)
+            wg = torch.cat([w[:, g * 128:(g + 1) * 128], wmax.expand(N, 128)], dim=1).cpu().numpy()
+            xg = np.zeros((1, 256), dtype=np.float16)
+        else:
+            wg = w[:, g * 128:(g + 1) * 128].cpu().numpy()
+            xg = np.zeros((1, 128), dtype=np.float16)
+        xg[0, c % 128] = np.float16(1.0 + i / 8.0)
+        ref = orc.qlinear(xg, wg, bits, scheme)
+        check_output(torch.from_numpy(y_host[i:i + 1]), ref, "decode %d-bit K=%d, column %d" % (bits, K, c))
+    del qw, w, x, y
+    K2 = K + 128
+    w2 = torch.zeros((N, K2), dtype=torch.float16, device="cuda")
+    qw2 = lpq.lpq_quantize_pack(w2, bits, scheme)
+    x2 = torch.zeros((2, K2), dtype=torch.float16, device="cuda")
+    y2 = torch.full((2, N), float("nan"), dtype=torch.float16, device="cuda")
+    with pytest.raises(lpq.LpqError) as err:
+        lpq.lpq_qlinear_decode(qw2, x2, y2)
+    assert err.value.status == 8
+    torch.cuda.synchronize()
+    assert torch.isnan(y2).all(), "a refused call wrote outputs"
+
+
 # ---- a4: prefill linear --------------------------------------------------------------------
 
 @pytest.mark.parametrize("bits,scheme", VARIANTS, ids=VARIANT_IDS)

@@ -159,24 +159,39 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
         uint32_t w, s;       // into the codes; into scales / zeros (grouped scheme)
     };
     constexpr int LANE_BYTES = V == V_W3 ? 12 : 16, TILE = VInfo<V>::TILE_BYTES;
+    // Wide path, 3/4-bit codes: a 32x32x16 B operand is tiles (p, p + 2) of the wave's block with lanes 0-15 / 16-31 on
+    // the two tiles and lanes 32-63 two k slots further on.  A lane loads what it will hold -- the packed codes of lane
+    // r + 32 * khalf (+ 16 for the second operand) of tile p + 2 * sel, r = lane % 16, sel = lane / 16 % 2, khalf =
+    // lane / 32: the same bytes of the same tiles, in another lane order -- instead of every tile in its own order and
+    // an exchange of half the registers between lanes after unpacking.  Stage::w[p] is then pair p's operand of k slots
+    // (kq 0, kq 2), w[p + 2] that of (kq 1, kq 3); the lane's row of the block is 4 r + p + 2 sel.
+    constexpr bool PAIRED_LOADS = WIDE && (V == V_W3 || V == V_W4);
+    static_assert(!PAIRED_LOADS || RT == 4, "two pairs of tiles per wave");
     auto lane_offs = [&](int sb) {
         const int wv = max(0, min(wave, row_blocks - 1 - sb * WAVES));
+        const uint32_t sel = (uint32_t)(lane >> 4) & 1u;
+        const uint32_t in_tile = PAIRED_LOADS ? 2u * sel * TILE + LANE_BYTES * (uint32_t)(r + 32 * (lane >> 5)) : LANE_BYTES * (uint32_t)lane;
         LaneOffs o;
-        if constexpr (RT == 4) o.w = (uint32_t)wv * (uint32_t)KT * (4u * TILE) + LANE_BYTES * (uint32_t)lane;
-        else o.w = ((uint32_t)(wv >> 1) * (uint32_t)KT * 4u + 2u * (uint32_t)(wv & 1)) * TILE + LANE_BYTES * (uint32_t)lane;      // half a 64-row block per wave
-        o.s = ((uint32_t)wv * 64u + 4u * (uint32_t)r) * 2u;
+        if constexpr (RT == 4) o.w = (uint32_t)wv * (uint32_t)KT * (4u * TILE) + in_tile;
+        else o.w = ((uint32_t)(wv >> 1) * (uint32_t)KT * 4u + 2u * (uint32_t)(wv & 1)) * TILE + in_tile;      // half a 64-row block per wave
+        o.s = ((uint32_t)wv * 64u + 4u * (uint32_t)r + (PAIRED_LOADS ? 2u * sel : 0u)) * 2u;
         return o;
     };
     auto issue = [&](Stage& b, int sb, int kt, LaneOffs& o) {
         const uint8_t* wbase = L.codes + ((size_t)sb * (WAVES * RT / 4) * KT + kt) * (4 * (size_t)TILE);
         asm volatile("" : "+v"(o.w));        // widened next to the loads, so that base and offset stay apart
 #pragma unroll
-        for (int t = 0; t < RT; ++t) b.w[t] = load_tile_at<V>(wbase + o.w + t * TILE);
+        for (int t = 0; t < RT; ++t) b.w[t] = load_tile_at<V>(wbase + o.w + (PAIRED_LOADS ? (t & 1) * TILE + (t >> 1) * 16 * LANE_BYTES : t * TILE));
         if constexpr (SCHEME == SCH_ASYM) {
             const size_t row0 = ((size_t)kt * L.N + (size_t)sb * (WAVES * 64)) * 2;
             asm volatile("" : "+v"(o.s));
-            b.s = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(L.scales) + row0 + o.s);
-            if constexpr (!POST) b.z = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(L.zeros) + row0 + o.s);
+            if constexpr (PAIRED_LOADS) {    // the lane's two rows: of pair 0 and of pair 1
+                b.s[0] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(L.scales) + row0 + o.s);
+                b.z[0] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(L.zeros) + row0 + o.s);
+            } else {
+                b.s = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(L.scales) + row0 + o.s);
+                if constexpr (!POST) b.z = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(L.zeros) + row0 + o.s);
+            }
         }
     };
     // Two ways to fold scale and zero in.  POST (up to 32 tokens): multiply raw codes (as fp16
@@ -203,16 +218,17 @@ __device__ __forceinline__ void run_range(const LinDesc& L, int M, int m0, long 
                 for (int t = 0; t < RT; ++t) {
                     unpack_codes_half<V>(b.w[t], half, wb[t]);
                     if constexpr (SCHEME == SCH_ASYM) {
-                        const uint32_t sp = b.s[t >> 1], zp = b.z[t >> 1];
+                        const uint32_t sp = b.s[PAIRED_LOADS ? 0 : t >> 1], zp = b.z[PAIRED_LOADS ? 0 : t >> 1];      // PAIRED_LOADS: operand t belongs to pair t & 1
                         const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
                         const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
                         apply_scale_zero_half(wb[t], __builtin_bit_cast(_Float16, sh), __builtin_bit_cast(_Float16, zh));
                     }
                 }
+                if constexpr (!PAIRED_LOADS)
 #pragma unroll
-                for (int p = 0; p < NP; ++p)
+                    for (int p = 0; p < NP; ++p)
 #pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) pair_tiles_for_mfma32(wb[p][jj], wb[p + NP][jj]);
+                        for (int jj = 0; jj < 2; ++jj) pair_tiles_for_mfma32(wb[p][jj], wb[p + NP][jj]);
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj) {
                     const int j = 2 * half + jj;

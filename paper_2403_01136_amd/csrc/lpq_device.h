@@ -363,6 +363,32 @@ __device__ __forceinline__ void unpack_codes_half(const WRaw<V>& w, int half, h8
     }
 }
 
+// One pair of a lane's 32 codes (pair P = 0 .. 15: columns 2 P % 8, 2 P % 8 + 1 of the lane's eight in MFMA step P / 4)
+// as integer-valued fp16, 3- and 4-bit codes: what unpack_codes_half yields, one register at a time, for callers that
+// spread the unpacking thinly between matrix instructions.
+template <int V>
+__device__ __forceinline__ h2 unpack_codes_pair(const WRaw<V>& w, int P)
+{
+    static_assert(V == V_W3 || V == V_W4, "3- and 4-bit codes");
+    constexpr uint32_t MAGIC = 0x64006400u;
+    uint32_t magic_v;
+    asm("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(MAGIC));
+    if constexpr (V == V_W4) {
+        const uint32_t q = w.q[P / 4], src = (P % 4) >= 2 ? q >> 8 : q;
+        return (P % 2) ? magic_to_int(and_or(src, 0x00F000F0u, magic_v), 4) : magic_to_int(and_or(src, 0x000F000Fu, magic_v), 0);
+    } else {
+        if (P < 15) {
+            const int i = P / 5, f = P % 5, ff = f % 3;            // fields 3, 4 sit at bits 9, 12: shift them down first
+            const uint32_t src = (f >= 3) ? (w.q[i] >> 9) : w.q[i];
+            return magic_to_int(and_or(src, 0x00070007u << (3 * ff), magic_v), 3 * ff);
+        }
+        uint32_t u = and_or(w.q[0] >> 15, 0x00010001u, magic_v);
+        u = and_or(w.q[1] >> 14, 0x00020002u, u);
+        u = and_or(w.q[2] >> 13, 0x00040004u, u);
+        return magic_to_int(u, 0);
+    }
+}
+
 // w~ = scale * code + zero for the two operands of a half step
 __device__ __forceinline__ void apply_scale_zero_half(h8 v[2], _Float16 s, _Float16 z)
 {

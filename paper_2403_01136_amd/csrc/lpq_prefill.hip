@@ -199,11 +199,31 @@ void prefill_kernel(const PrefillArgs a)
     // issues in order, so vector work placed between two matrix instructions is free while work placed
     // in front of a run of them is not.  The step is therefore cut into segments of four matrix
     // instructions (one 32-token tile, both tile pairs, two k slots); while the segments of one half
-    // step run from wb[h], the next half step is unpacked into wb[1 - h], one tile per segment.
+    // step run from wb[h], the next half step is unpacked into wb[1 - h]: 3/4-bit codes a sixteenth of it
+    // per segment (unpack_piece), the other variants one tile per segment in six of the segments.
     // Scheduling barriers keep the compiler from regrouping the segments.
     h8 wb[2][NW][2];
     WStep ws[2];                 // HALF_LOADS: raw half steps by parity; else this step's and the next step's codes
     auto unpack_tile = [&](const WStep& w, int t, int half, int dst) { operands(w, t, half, wb[dst][t]); };
+    // 3/4-bit codes: a sixteenth of a half step's operands -- two pairs of codes of one operand, i.e. two registers:
+    // piece idx = 4 * (operand t) + q covers pairs 2 q, 2 q + 1 of the operand's eight in this half.  One piece per
+    // segment of four matrix instructions keeps the vector work between two of them under the 32 cycles the matrix
+    // pipe takes for one (a wave on its own issues a vector instruction every 5-6 cycles).
+    auto unpack_piece = [&](const WStep& w, int idx, int half, int dst) {
+        if constexpr (!HALF_LOADS) {
+            const int t = idx >> 2, q = idx & 3;
+            const uint32_t sp = w.s[0], zp = w.z[0];
+            const uint16_t sh = (uint16_t)((t & 1) ? (sp >> 16) : (sp & 0xffffu));
+            const uint16_t zh = (uint16_t)((t & 1) ? (zp >> 16) : (zp & 0xffffu));
+            const h2 s2 = splat(__builtin_bit_cast(_Float16, sh)), z2 = splat(__builtin_bit_cast(_Float16, zh));
+#pragma unroll
+            for (int k = 2 * q; k < 2 * q + 2; ++k) {
+                const h2 c = __builtin_elementwise_fma(unpack_codes_pair<V>(w.raw[t], 8 * half + k), s2, z2);
+                wb[dst][t][k >> 2][2 * (k & 3)] = c[0];
+                wb[dst][t][k >> 2][2 * (k & 3) + 1] = c[1];
+            }
+        }
+    };
     auto pair_tiles = [&](int p, int dst) {
         if constexpr (!HALF_LOADS) return;           // 3/4-bit codes were loaded in operand order
 #pragma unroll
@@ -266,12 +286,18 @@ void prefill_kernel(const PrefillArgs a)
                     acc[1][mt] = mfma32(xa[cur][0], wb[half][1][jj], acc[1][mt]);
                     acc[0][mt] = mfma32(xa[cur][1], wb[half][2][jj], acc[0][mt]);
                     acc[1][mt] = mfma32(xa[cur][1], wb[half][3][jj], acc[1][mt]);
-                    if (seg == 0 * STRIDE) unpack_tile(src, 0, 1 - half, 1 - half);
-                    if (seg == 1 * STRIDE) unpack_tile(src, 2, 1 - half, 1 - half);
-                    if (seg == 2 * STRIDE) pair_tiles(0, 1 - half);
-                    if (seg == 3 * STRIDE) unpack_tile(src, 1, 1 - half, 1 - half);
-                    if (seg == 4 * STRIDE) unpack_tile(src, 3, 1 - half, 1 - half);
-                    if (seg == 5 * STRIDE) pair_tiles(1, 1 - half);
+                    if constexpr (HALF_LOADS) {
+                        if (seg == 0 * STRIDE) unpack_tile(src, 0, 1 - half, 1 - half);
+                        if (seg == 1 * STRIDE) unpack_tile(src, 2, 1 - half, 1 - half);
+                        if (seg == 2 * STRIDE) pair_tiles(0, 1 - half);
+                        if (seg == 3 * STRIDE) unpack_tile(src, 1, 1 - half, 1 - half);
+                        if (seg == 4 * STRIDE) unpack_tile(src, 3, 1 - half, 1 - half);
+                        if (seg == 5 * STRIDE) pair_tiles(1, 1 - half);
+                    } else {
+                        constexpr int PER_SEG = 16 / (2 * MTB);      // sixteen pieces over the half step's 2 * MTB segments
+#pragma unroll
+                        for (int i = 0; i < PER_SEG; ++i) unpack_piece(src, seg * PER_SEG + i, 1 - half, 1 - half);
+                    }
                     if (half == 0 && (seg & 1) && seg < 2 * FILL_SEGS) fill_x_slab(ktn, buf ^ 1, (XQ / FILL_SEGS) * (seg >> 1), (XQ / FILL_SEGS) * ((seg >> 1) + 1));
                     __builtin_amdgcn_sched_barrier(0);
                 }

@@ -98,7 +98,7 @@ def act_bytes(cfg, M):
     return sum(2 * M * K + 2 * M * N for _ in cfg["layers"] for (K, N) in wl.linear_shapes(cfg).values())
 
 
-def cpu_baseline(cfg, M, budget_weights=0.9e9):
+def cpu_baseline(cfg, M, budget_weights=1.5e9):
     """The CPU oracle (as it stands) on a bounded sample of the same workload: for every layer of the
     stage, `budget_rows` output rows of its FC1 linear (about budget_weights weights in all: 10-30 s of
     host work), quantise -> dequantise -> fp64 matmul at the decode micro-batch.  Reported in the metric's
